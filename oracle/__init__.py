@@ -1,0 +1,21 @@
+"""CPU oracle for the LCD table-lookup linear layer.  TEST INFRASTRUCTURE ONLY.
+
+Only ``tests/``, ``__graft_entry__.smoke()`` and ``bench.py``'s ``cpu_baseline`` leg may
+import this package.  It shares no code with ``paper_2506_12038_amd`` and never imports it.
+"""
+from .lcd_oracle import (
+    build_oracle,
+    half_to_double,
+    dequant,
+    smooth,
+    lut_matmul,
+    bucket_matmul,
+    input_transform,
+    num_threads,
+)
+from .metrics import parity_errors
+
+__all__ = [
+    "build_oracle", "half_to_double", "dequant", "smooth", "lut_matmul", "bucket_matmul",
+    "input_transform", "num_threads", "parity_errors",
+]

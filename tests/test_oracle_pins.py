@@ -1,0 +1,248 @@
+"""Pins for the CPU oracle: it is checked against things other than itself.
+
+* exact rational brute force (python Fractions) on tiny shapes;
+* the bucket-sum identity  y_n = sum_c C[n,c] * sum_{k: idx=c} x_k/s_k  (paper Sec. 4.2);
+* codebook-permutation invariance;
+* one-hot probes, constant-index case, power-of-two scaling of s;
+* reduction to library routines (numpy int64 matmul, numpy fp64 matmul on a shared codebook);
+* row-dependence of the per-row codebook;
+* fp16 decoding against the IEEE format definition (golden values) and numpy's float16;
+* the input-transformation stage (Sec. 4.1, Eq. 10-11) against hand-worked values.
+"""
+from fractions import Fraction
+from pathlib import Path
+
+import numpy as np
+import pytest
+
+import oracle
+import synth
+
+GOLD = Path(__file__).resolve().parent / "golden"
+
+
+def frac_of_half(h: np.float16) -> Fraction:
+    return Fraction(float(h))  # float16 -> python float is exact; Fraction(float) is exact
+
+
+def brute_force(codebook, idx, x, s):
+    M, K = x.shape
+    N = idx.shape[0]
+    Y = [[Fraction(0) for _ in range(N)] for _ in range(M)]
+    for m in range(M):
+        for n in range(N):
+            acc = Fraction(0)
+            for k in range(K):
+                acc += frac_of_half(x[m, k]) / Fraction(float(s[k])) * frac_of_half(codebook[n, idx[n, k]])
+            Y[m][n] = acc
+    return Y
+
+
+def small_case(bits, M, N, K, seed):
+    rng = np.random.default_rng(seed)
+    codebook = (rng.standard_normal((N, 1 << bits)) * 0.02).astype(np.float16)
+    idx = rng.integers(0, 1 << bits, size=(N, K), dtype=np.uint8)
+    x = rng.standard_normal((M, K)).astype(np.float16)
+    x[:, rng.integers(0, K)] *= np.float16(50)
+    s = (0.5 + rng.random(K) * 3).astype(np.float32)
+    return codebook, idx, x, s
+
+
+@pytest.mark.parametrize("bits", [2, 3])
+@pytest.mark.parametrize("shape", [(1, 4, 16), (3, 8, 64), (2, 5, 37)])
+def test_exact_rational_brute_force(bits, shape):
+    M, N, K = shape
+    codebook, idx, x, s = small_case(bits, M, N, K, 100 + bits + K)
+    Y = oracle.lut_matmul(codebook, idx, x, s, bits)
+    Yb = oracle.bucket_matmul(codebook, idx, x, s, bits)
+    ref = brute_force(codebook, idx, x, s)
+    for m in range(M):
+        for n in range(N):
+            exact = ref[m][n]
+            scale = sum(abs(frac_of_half(x[m, k]) / Fraction(float(s[k])) * frac_of_half(codebook[n, idx[n, k]]))
+                        for k in range(K))
+            tol = float(scale) * (K + 4) * 2.0 ** -52
+            assert abs(Fraction(Y[m, n]) - exact) <= tol
+            assert abs(Fraction(Yb[m, n]) - exact) <= tol
+
+
+@pytest.mark.parametrize("bits", [2, 3])
+def test_bucket_sum_identity(bits):
+    L = synth.make_layer(0, 0, 96, 512, bits, 3)
+    Y = oracle.lut_matmul(L["codebook"], L["idx"], L["x"], L["s"], bits)
+    Yb = oracle.bucket_matmul(L["codebook"], L["idx"], L["x"], L["s"], bits)
+    # independent numpy evaluation of the bucket form
+    xs = L["x"].astype(np.float64) / L["s"].astype(np.float64)
+    Yn = np.zeros_like(Y)
+    for c in range(1 << bits):
+        S = xs @ (L["idx"] == c).astype(np.float64).T
+        Yn += S * L["codebook"][:, c].astype(np.float64)[None, :]
+    scale = np.abs(xs) @ np.abs(L["codebook"].astype(np.float64)[np.arange(96)[:, None], L["idx"]]).T
+    assert np.all(np.abs(Y - Yb) <= scale * 1e-13)
+    assert np.all(np.abs(Y - Yn) <= scale * 1e-13)
+
+
+@pytest.mark.parametrize("bits", [2, 3])
+def test_codebook_permutation_invariance(bits):
+    codebook, idx, x, s = small_case(bits, 2, 24, 128, 7)
+    rng = np.random.default_rng(8)
+    cb2 = codebook.copy()
+    idx2 = idx.copy()
+    for n in range(codebook.shape[0]):
+        perm = rng.permutation(1 << bits)  # new position p holds old centroid perm[p]
+        inv = np.argsort(perm)
+        cb2[n] = codebook[n, perm]
+        idx2[n] = inv[idx[n]]
+    assert np.array_equal(oracle.dequant(codebook, idx, bits), oracle.dequant(cb2, idx2, bits))
+    Y1 = oracle.lut_matmul(codebook, idx, x, s, bits)
+    Y2 = oracle.lut_matmul(cb2, idx2, x, s, bits)
+    assert np.array_equal(Y1, Y2)  # bit-identical: What is identical and the k order is fixed
+
+
+@pytest.mark.parametrize("bits", [2, 3])
+def test_one_hot_probes_read_single_columns(bits):
+    N, K = 12, 40
+    codebook, idx, _, _ = small_case(bits, 1, N, K, 21)
+    for k in range(K):
+        for j in (0, 3, -2):
+            x = np.zeros((1, K), dtype=np.float16)
+            x[0, k] = 1.0
+            s = np.ones(K, dtype=np.float32)
+            s[k] = 2.0 ** j
+            Y = oracle.lut_matmul(codebook, idx, x, s, bits)
+            expect = codebook[np.arange(N), idx[:, k]].astype(np.float64) * 2.0 ** (-j)
+            assert np.array_equal(Y[0], expect)
+
+
+@pytest.mark.parametrize("bits", [2, 3])
+def test_constant_index(bits):
+    codebook, idx, x, s = small_case(bits, 2, 9, 50, 33)
+    for c in range(1 << bits):
+        idc = np.full_like(idx, c)
+        Y = oracle.lut_matmul(codebook, idc, x, s, bits)
+        xs = [[Fraction(float(x[m, k])) / Fraction(float(s[k])) for k in range(50)] for m in range(2)]
+        for m in range(2):
+            tot = sum(xs[m])
+            for n in range(9):
+                exact = tot * Fraction(float(codebook[n, c]))
+                assert abs(Fraction(Y[m, n]) - exact) <= abs(float(exact)) * 1e-12 + 1e-18
+
+
+def test_uniform_grid_reduces_to_integer_matmul():
+    # shared codebook C[c] = c (a=0, d=1), integer activations, s = 1: an exact int matmul
+    bits = 3
+    rng = np.random.default_rng(5)
+    N, K, M = 17, 96, 4
+    codebook = np.tile(np.arange(8, dtype=np.float16)[None, :], (N, 1))
+    idx = rng.integers(0, 8, size=(N, K), dtype=np.uint8)
+    xi = rng.integers(-20, 21, size=(M, K))
+    x = xi.astype(np.float16)
+    s = np.ones(K, dtype=np.float32)
+    Y = oracle.lut_matmul(codebook, idx, x, s, bits)
+    assert np.array_equal(Y, (xi.astype(np.int64) @ idx.astype(np.int64).T).astype(np.float64))
+    # affine grid a + d*c  ->  a*rowsum(x) + d*(x @ idx^T)
+    a, d = 0.5, 0.25
+    codebook2 = (a + d * np.arange(8)).astype(np.float16)
+    Y2 = oracle.lut_matmul(np.tile(codebook2[None, :], (N, 1)), idx, x, s, bits)
+    expect = a * xi.sum(axis=1, keepdims=True) + d * (xi.astype(np.int64) @ idx.astype(np.int64).T)
+    assert np.array_equal(Y2, expect)
+
+
+@pytest.mark.parametrize("bits", [2, 3])
+def test_shared_codebook_matches_numpy_matmul(bits):
+    L = synth.make_layer(1, 0, 64, 256, bits, 5, variant="A")
+    Y = oracle.lut_matmul(L["codebook"], L["idx"], L["x"], L["s"], bits)
+    W = L["codebook"][0].astype(np.float64)[L["idx"]]          # library gather
+    xs = L["x"].astype(np.float64) / L["s"].astype(np.float64)  # library divide
+    ref = xs @ W.T                                              # library matmul
+    scale = np.abs(xs) @ np.abs(W).T
+    assert np.all(np.abs(Y - ref) <= scale * 1e-13)
+    # a transposed operand or a dropped s would be far outside this tolerance
+    assert not np.allclose(Y, L["x"].astype(np.float64) @ W.T, rtol=1e-3)
+
+
+def test_scaling_and_linearity():
+    bits = 2
+    codebook, idx, x, s = small_case(bits, 2, 16, 64, 77)
+    Y = oracle.lut_matmul(codebook, idx, x, s, bits)
+    assert np.array_equal(oracle.lut_matmul(codebook, idx, x, s * 2, bits), Y / 2)
+    x1 = x.copy(); x2 = x.copy()
+    x1[:, ::2] = 0; x2[:, 1::2] = 0
+    Y12 = oracle.lut_matmul(codebook, idx, x1, s, bits) + oracle.lut_matmul(codebook, idx, x2, s, bits)
+    assert np.allclose(Y12, Y, rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("bits", [2, 3])
+def test_row_dependence(bits):
+    codebook, idx, x, s = small_case(bits, 2, 10, 48, 91)
+    Y = oracle.lut_matmul(codebook, idx, x, s, bits)
+    cb2 = codebook.copy()
+    cb2[4] = (cb2[4].astype(np.float32) * 1.5).astype(np.float16)
+    Y2 = oracle.lut_matmul(cb2, idx, x, s, bits)
+    changed = np.any(Y != Y2, axis=0)
+    assert changed[4] and changed.sum() == 1
+
+
+def test_index_out_of_range_is_rejected():
+    codebook, idx, x, s = small_case(2, 1, 4, 8, 3)
+    idx[1, 2] = 4
+    with pytest.raises(ValueError):
+        oracle.lut_matmul(codebook, idx, x, s, 2)
+
+
+def test_half_decoding_golden_and_all_patterns():
+    for line in (GOLD / "fp16_values.txt").read_text().splitlines():
+        if not line or line.startswith("#"):
+            continue
+        hx, val = line.split()
+        got = oracle.half_to_double(int(hx, 16))
+        assert got == float(val) and np.signbit(got) == np.signbit(float(val))
+    allbits = np.arange(65536, dtype=np.uint16)
+    ref = allbits.view(np.float16).astype(np.float64)
+    eye = allbits.reshape(1, -1)  # decode through oracle.smooth with s = 1
+    got = oracle.smooth(eye, np.ones(65536, dtype=np.float32))[0]
+    assert np.array_equal(np.isnan(got), np.isnan(ref))
+    ok = ~np.isnan(ref)
+    assert np.array_equal(got[ok], ref[ok])
+
+
+def test_centroid_golden():
+    for line in (GOLD / "centroids.txt").read_text().splitlines():
+        if not line or line.startswith("#"):
+            continue
+        parts = line.split()
+        bits = int(parts[0])
+        vals = np.array([float(v) for v in parts[1:]])
+        got = synth.centroid_set(bits).astype(np.float64)
+        assert np.all(np.abs(got - vals) <= np.abs(vals) * 2.0 ** -11 + 1e-7)
+        assert np.all(np.diff(got) > 0)
+
+
+def test_input_transform_hand_values():
+    # Eq. 10-11 with s_m = [2, 0.5, 1, 1], s_q = 0.25, b = 8:
+    #   x = [1.0, 1.0, 100.0, -0.375]  ->  x/(s_m*s_q) = [2, 8, 400, -1.5]  ->  [2, 8, 127, -2]
+    x = np.array([[1.0, 1.0, 100.0, -0.375]], dtype=np.float16)
+    s_m = np.array([2, 0.5, 1, 1], dtype=np.float32)
+    q = oracle.input_transform(x, s_m, 0.25, 8)
+    assert q.tolist() == [[2, 8, 127, -2]]
+    # ties to even, and the negative clip bound -128
+    x = np.array([[0.625, 0.875, -1000.0]], dtype=np.float16)
+    q = oracle.input_transform(x, np.ones(3, dtype=np.float32), 0.25, 8)
+    assert q.tolist() == [[2, 4, -128]]
+    # b = 4 range is [-8, 7]
+    q = oracle.input_transform(np.array([[10.0, -10.0]], dtype=np.float16), np.ones(2, dtype=np.float32), 1.0, 4)
+    assert q.tolist() == [[7, -8]]
+
+
+def test_generators_follow_the_recipe():
+    L = synth.make_layer(0, 0, 256, 4096, 2, 4)
+    p = np.bincount(L["idx"].ravel(), minlength=4) / L["idx"].size
+    assert p[1] > p[0] and p[2] > p[3] and abs(p[0] - 0.2313) < 0.01 and abs(p[1] - 0.2687) < 0.01
+    assert len(L["outliers"]) == 41
+    normal = np.setdiff1d(np.arange(4096), L["outliers"])
+    assert np.abs(L["x"][:, L["outliers"]].astype(np.float32)).mean() > 10 * np.abs(L["x"][:, normal].astype(np.float32)).mean()
+    assert L["s"].dtype == np.float32 and np.all(L["s"] >= 1e-5)
+    assert L["s"][L["outliers"]].mean() > 4 * L["s"][normal].mean()
+    L2 = synth.make_layer(0, 0, 256, 4096, 2, 4)
+    assert all(np.array_equal(L[k], L2[k]) for k in L)
+    assert len(np.unique(L["codebook"], axis=0)) > 200  # variant B: rows differ
