@@ -1,0 +1,133 @@
+/*
+ * lcd.h -- C ABI of the MI355X (gfx950) library for LCD's smoothed table-lookup linear layer.
+ *
+ * The operation (paper Sec. 4, "Inference with Table Lookup"; Sec. 3.4 for the smoothing):
+ *
+ *     Y[m][n] = sum_k ( X[m][k] / s[k] ) * C[n][ idx[n][k] ]        m < M, n < N, k < K
+ *
+ *   idx[n][k]  2- or 3-bit index of the centroid that weight (n,k) was clustered to
+ *              (Sec. 3.2: a clustered weight W' is its centroid);
+ *   C[n][c]    per-output-row codebook of 2^bits fp16 centroids; the centroids already
+ *              contain the offline smoothing of the weights (Sec. 3.4: weights are scaled by
+ *              the smoothing factor offline, inputs are divided by it at inference);
+ *   s[k]       per-input-channel smoothing factor, fp32, > 0;
+ *   X, Y       fp16, row-major.  Accumulation is fp32; one rounding to fp16 at the store.
+ *
+ * Conventions for every entry point
+ *   - Pointers marked DEVICE must be device memory of the current HIP device, 16-byte
+ *     aligned; pointers marked HOST are ordinary host memory.
+ *   - The caller owns every buffer.  The library never allocates, frees or keeps a pointer
+ *     after the call has enqueued its work.
+ *   - Device work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the default
+ *     stream).  No entry point synchronises; results are valid once the stream has reached
+ *     the call's work.
+ *   - Arguments are validated on the host before anything is launched; a failed call
+ *     launches nothing and returns a status != LCD_OK.  lcd_last_error_string() then holds a
+ *     message (thread-local).
+ *   - Shapes: bits in {2,3};  N % 16 == 0;  K % 256 == 0;  N, K >= 1 tile.
+ *   - Two calls that share a workspace buffer must be ordered on one stream.
+ */
+#ifndef LCD_H
+#define LCD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LCD_OK = 0,
+    LCD_ERR_NULL = 1,        /* a required pointer is NULL                          */
+    LCD_ERR_BAD_BITS = 2,    /* bits not in {2,3}                                   */
+    LCD_ERR_BAD_SHAPE = 3,   /* N or K not positive / not a multiple of the tile    */
+    LCD_ERR_BAD_M = 4,       /* M out of range for the entry point                  */
+    LCD_ERR_SIZE = 5,        /* a buffer-size argument is too small                 */
+    LCD_ERR_INDEX_RANGE = 6, /* host packer: an index is >= 2^bits                  */
+    LCD_ERR_ALIGN = 7,       /* a device pointer is not 16-byte aligned             */
+    LCD_ERR_HIP = 8          /* the HIP runtime reported an error at launch         */
+} lcd_status;
+
+/* Library version (major*10000 + minor*100 + patch) and the packed-layout revision. */
+int lcd_version(void);
+int lcd_layout_revision(void);
+
+/* Message of the last failed call on this thread ("" if none), and a fixed name per status. */
+const char *lcd_last_error_string(void);
+const char *lcd_status_string(lcd_status st);
+
+/* ---- sizes (pure host functions; 0 on invalid arguments) -------------------------------- */
+
+/* Bytes of the packed index matrix: exactly N*K*bits/8 (Sec. 4.2: compact low-bit indices). */
+size_t lcd_packed_bytes(int N, int K, int bits);
+/* Bytes of the per-layer table lcd_build_lut writes (24*N for 2 bits, 48*N for 3 bits). */
+size_t lcd_lut_bytes(int N, int bits);
+/* Bytes of scratch lcd_lut_gemv / lcd_lut_gemm need for this problem (a multiple of 256). */
+size_t lcd_workspace_bytes(int M, int N, int K, int bits);
+
+/* ---- index packing (offline, once per layer; Sec. 4.1 "constructed ahead of time") ------- *
+ *
+ * Input:  idx[N][K], row-major, one index per byte.
+ * Output: the packed layout (revision 1), made for 16-byte-per-lane, 1 KiB-per-wavefront
+ * contiguous loads.  The matrix is cut into tiles of 16 rows x 256 columns; tile
+ * (t = n/16, c = k/256) starts at byte (t*(K/256) + c) * T with T = 1024 (2 bits) or 1536
+ * (3 bits).  Inside a tile, "lane" l = 16*q + i covers row i = n%16 and the 64 columns
+ * k%256 in [64q, 64q+64); let w = k%64.
+ *   - bytes [16*l, 16*l+16) of the tile are a 128-bit little-endian word whose bits
+ *     [2w+1 : 2w] hold idx & 3;
+ *   - 3 bits only: bytes [1024 + 8*l, 1024 + 8*l + 8) are two 32-bit little-endian words.
+ *     With w = 16*d + 8*a + e (d<4, a<2, e<8), bit (idx >> 2) is stored in word a at bit
+ *     8*((e>>2) + 2*(e&1)) + 2*d + ((e&3)>>1).
+ * The mapping is a bijection: lcd_unpack_indices(lcd_pack_indices(idx)) == idx, and the
+ * device and host packers produce identical bytes.
+ *
+ * Device packer: idx and packed are DEVICE pointers.  Indices are taken modulo 2^bits (the
+ * device cannot report a range error without a sync; use the host twin to validate).
+ */
+lcd_status lcd_pack_indices(const uint8_t *idx /*DEVICE [N][K]*/, int N, int K, int bits,
+                            void *packed /*DEVICE*/, size_t packed_bytes, void *stream);
+lcd_status lcd_unpack_indices(const void *packed /*DEVICE*/, int N, int K, int bits,
+                              uint8_t *idx /*DEVICE [N][K]*/, void *stream);
+/* Host twins (HOST pointers, no GPU needed, no alignment requirement).  The host packer
+ * returns LCD_ERR_INDEX_RANGE if any index is >= 2^bits and then leaves `packed` untouched. */
+lcd_status lcd_pack_indices_host(const uint8_t *idx /*HOST*/, int N, int K, int bits,
+                                 void *packed /*HOST*/, size_t packed_bytes);
+lcd_status lcd_unpack_indices_host(const void *packed /*HOST*/, int N, int K, int bits,
+                                   uint8_t *idx /*HOST*/);
+
+/* ---- table build (offline, once per layer; Sec. 4.1 / 4.2 "pre-computed values") --------- *
+ *
+ * codebook: DEVICE, fp16 bit patterns, [N][2^bits] row-major.
+ * lut:      DEVICE, lcd_lut_bytes(N,bits) bytes, opaque.  It holds the codebook re-laid out
+ *           for the kernels: fp32 per-bucket multipliers in accumulator order for the decode
+ *           path (Sec. 4.2: one bucket per weight centroid), and byte-split tables for the
+ *           register dequantiser of the batched paths.
+ */
+lcd_status lcd_build_lut(const uint16_t *codebook /*DEVICE*/, int N, int bits,
+                         void *lut /*DEVICE*/, size_t lut_bytes, void *stream);
+
+/* ---- the product (Sec. 4.2 lookup + accumulation, with Sec. 3.4's division by s) --------- *
+ *
+ * packed  DEVICE, from lcd_pack_indices;     lut  DEVICE, from lcd_build_lut
+ * x       DEVICE fp16 [M][K] row-major;      s    DEVICE fp32 [K], every s[k] > 0 and finite
+ *                                                 (not checked); |x/s| must fit fp16
+ * y       DEVICE fp16 [M][N] row-major (written, never read)
+ * workspace  DEVICE, >= lcd_workspace_bytes(M,N,K,bits) bytes, contents ignored on entry.
+ *
+ * lcd_lut_gemv: decode path, 1 <= M <= 16.  Bandwidth-bound on the packed indices.
+ * lcd_lut_gemm: prefill path, any M >= 1 (tuned for M >= 64): register dequantisation into
+ *               fp16 MFMA operands.
+ * Both give bit-identical results from run to run (fixed reduction order).
+ */
+lcd_status lcd_lut_gemv(const void *packed, const void *lut, const uint16_t *x, const float *s,
+                        uint16_t *y, int M, int N, int K, int bits,
+                        void *workspace, size_t workspace_bytes, void *stream);
+lcd_status lcd_lut_gemm(const void *packed, const void *lut, const uint16_t *x, const float *s,
+                        uint16_t *y, int M, int N, int K, int bits,
+                        void *workspace, size_t workspace_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LCD_H */

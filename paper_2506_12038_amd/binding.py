@@ -1,0 +1,196 @@
+"""Thin Python binding of the C ABI in include/lcd.h: argument marshalling only.
+
+Every step of the path runs in the HIP library; this file only turns torch tensors into
+pointers and sizes, allocates outputs with torch (device memory is PyTorch's job here), and
+turns a status code into an exception.  There is no CPU fallback: if liblcd.so is missing
+the import of a function fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes
+from pathlib import Path
+from typing import Optional
+
+_PKG = Path(__file__).resolve().parent
+LIB_PATH = _PKG / "liblcd.so"
+_lib = None
+
+EXPORTS = (
+    "lcd_version", "lcd_layout_revision", "lcd_last_error_string", "lcd_status_string",
+    "lcd_packed_bytes", "lcd_lut_bytes", "lcd_workspace_bytes",
+    "lcd_pack_indices", "lcd_unpack_indices", "lcd_pack_indices_host", "lcd_unpack_indices_host",
+    "lcd_build_lut", "lcd_lut_gemv", "lcd_lut_gemm",
+)
+
+
+class LcdError(RuntimeError):
+    def __init__(self, status: int, name: str, message: str):
+        super().__init__(f"{name} ({status}): {message}")
+        self.status = status
+        self.name = name
+
+
+def load_library():
+    """dlopen liblcd.so (built by paper_2506_12038_amd/build.py).  Raises if it is absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not LIB_PATH.exists():
+        raise FileNotFoundError(
+            f"{LIB_PATH} not found: build it with `python -m paper_2506_12038_amd.build` "
+            "(there is no fallback path)")
+    lib = ctypes.CDLL(str(LIB_PATH))
+    vp, ci, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    lib.lcd_version.restype = ci
+    lib.lcd_layout_revision.restype = ci
+    lib.lcd_last_error_string.restype = ctypes.c_char_p
+    lib.lcd_status_string.restype = ctypes.c_char_p
+    lib.lcd_status_string.argtypes = [ci]
+    lib.lcd_packed_bytes.restype = sz
+    lib.lcd_packed_bytes.argtypes = [ci, ci, ci]
+    lib.lcd_lut_bytes.restype = sz
+    lib.lcd_lut_bytes.argtypes = [ci, ci]
+    lib.lcd_workspace_bytes.restype = sz
+    lib.lcd_workspace_bytes.argtypes = [ci, ci, ci, ci]
+    lib.lcd_pack_indices.restype = ci
+    lib.lcd_pack_indices.argtypes = [vp, ci, ci, ci, vp, sz, vp]
+    lib.lcd_unpack_indices.restype = ci
+    lib.lcd_unpack_indices.argtypes = [vp, ci, ci, ci, vp, vp]
+    lib.lcd_pack_indices_host.restype = ci
+    lib.lcd_pack_indices_host.argtypes = [vp, ci, ci, ci, vp, sz]
+    lib.lcd_unpack_indices_host.restype = ci
+    lib.lcd_unpack_indices_host.argtypes = [vp, ci, ci, ci, vp]
+    lib.lcd_build_lut.restype = ci
+    lib.lcd_build_lut.argtypes = [vp, ci, ci, vp, sz, vp]
+    for name in ("lcd_lut_gemv", "lcd_lut_gemm"):
+        fn = getattr(lib, name)
+        fn.restype = ci
+        fn.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, vp, sz, vp]
+    _lib = lib
+    return lib
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        lib = load_library()
+        raise LcdError(status, lib.lcd_status_string(status).decode(), lib.lcd_last_error_string().decode())
+
+
+def _stream(stream) -> Optional[int]:
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _dev(t, dtype, name):
+    if not t.is_cuda or not t.is_contiguous() or t.dtype != dtype:
+        raise TypeError(f"{name}: expected a contiguous CUDA tensor of dtype {dtype}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def lcd_version() -> int:
+    return load_library().lcd_version()
+
+
+def lcd_layout_revision() -> int:
+    return load_library().lcd_layout_revision()
+
+
+def lcd_packed_bytes(N: int, K: int, bits: int) -> int:
+    return load_library().lcd_packed_bytes(N, K, bits)
+
+
+def lcd_lut_bytes(N: int, bits: int) -> int:
+    return load_library().lcd_lut_bytes(N, bits)
+
+
+def lcd_workspace_bytes(M: int, N: int, K: int, bits: int) -> int:
+    return load_library().lcd_workspace_bytes(M, N, K, bits)
+
+
+def lcd_pack_indices(idx, bits: int, out=None, stream=None):
+    """idx: CUDA uint8 [N, K] -> packed CUDA uint8 [N*K*bits/8]."""
+    import torch
+    lib = load_library()
+    N, K = idx.shape
+    nbytes = lib.lcd_packed_bytes(N, K, bits)
+    if out is None:
+        out = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=idx.device)
+    _check(lib.lcd_pack_indices(_dev(idx, torch.uint8, "idx"), N, K, bits, _dev(out, torch.uint8, "packed"),
+                                out.numel(), _stream(stream)))
+    return out[:nbytes] if nbytes else out[:0]
+
+
+def lcd_unpack_indices(packed, N: int, K: int, bits: int, stream=None):
+    import torch
+    lib = load_library()
+    idx = torch.empty((N, K), dtype=torch.uint8, device=packed.device)
+    _check(lib.lcd_unpack_indices(_dev(packed, torch.uint8, "packed"), N, K, bits, _dev(idx, torch.uint8, "idx"),
+                                  _stream(stream)))
+    return idx
+
+
+def lcd_pack_indices_host(idx, bits: int):
+    """numpy uint8 [N, K] -> numpy uint8 packed bytes (no GPU needed)."""
+    import numpy as np
+    lib = load_library()
+    idx = np.ascontiguousarray(idx, dtype=np.uint8)
+    N, K = idx.shape
+    nbytes = lib.lcd_packed_bytes(N, K, bits)
+    out = np.zeros(max(nbytes, 1), dtype=np.uint8)
+    _check(lib.lcd_pack_indices_host(idx.ctypes.data_as(ctypes.c_void_p), N, K, bits,
+                                     out.ctypes.data_as(ctypes.c_void_p), nbytes))
+    return out[:nbytes]
+
+
+def lcd_unpack_indices_host(packed, N: int, K: int, bits: int):
+    import numpy as np
+    lib = load_library()
+    packed = np.ascontiguousarray(packed, dtype=np.uint8)
+    need = lib.lcd_packed_bytes(N, K, bits)
+    if need and packed.size < need:
+        raise ValueError("packed buffer too small")
+    idx = np.empty((N, K), dtype=np.uint8)
+    _check(lib.lcd_unpack_indices_host(packed.ctypes.data_as(ctypes.c_void_p), N, K, bits,
+                                       idx.ctypes.data_as(ctypes.c_void_p)))
+    return idx
+
+
+def lcd_build_lut(codebook, bits: int, stream=None):
+    """codebook: CUDA float16 [N, 2**bits] -> opaque CUDA uint8 table."""
+    import torch
+    lib = load_library()
+    N = codebook.shape[0]
+    if codebook.shape[1] != (1 << bits):
+        raise ValueError("codebook must be [N, 2**bits]")
+    nbytes = lib.lcd_lut_bytes(N, bits)
+    lut = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=codebook.device)
+    _check(lib.lcd_build_lut(_dev(codebook, torch.float16, "codebook"), N, bits, _dev(lut, torch.uint8, "lut"),
+                             lut.numel(), _stream(stream)))
+    return lut
+
+
+def _product(fn_name, packed, lut, x, s, N, bits, y, workspace, stream):
+    import torch
+    lib = load_library()
+    M, K = x.shape
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.float16, device=x.device)
+    if workspace is None:
+        workspace = torch.empty(max(lib.lcd_workspace_bytes(M, N, K, bits), 256), dtype=torch.uint8, device=x.device)
+    _check(getattr(lib, fn_name)(
+        _dev(packed, torch.uint8, "packed"), _dev(lut, torch.uint8, "lut"), _dev(x, torch.float16, "x"),
+        _dev(s, torch.float32, "s"), _dev(y, torch.float16, "y"), M, N, K, bits,
+        _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream)))
+    return y
+
+
+def lcd_lut_gemv(packed, lut, x, s, N: int, bits: int, y=None, workspace=None, stream=None):
+    """Decode path, x: CUDA float16 [M<=16, K] -> y float16 [M, N]."""
+    return _product("lcd_lut_gemv", packed, lut, x, s, N, bits, y, workspace, stream)
+
+
+def lcd_lut_gemm(packed, lut, x, s, N: int, bits: int, y=None, workspace=None, stream=None):
+    """Prefill path, x: CUDA float16 [M, K] -> y float16 [M, N]."""
+    return _product("lcd_lut_gemm", packed, lut, x, s, N, bits, y, workspace, stream)

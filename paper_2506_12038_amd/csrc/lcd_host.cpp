@@ -1,0 +1,265 @@
+// Host side of the C ABI: argument validation, error strings, size arithmetic and the host
+// twins of the index packer.  Nothing here touches the GPU.
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <vector>
+#include "lcd_internal.h"
+
+namespace lcd {
+
+static thread_local char g_err[512] = "";
+
+lcd_status fail(lcd_status st, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+static lcd_status check_shape(int N, int K, int bits)
+{
+    if (bits != 2 && bits != 3) return fail(LCD_ERR_BAD_BITS, "bits=%d: only 2 and 3 are supported", bits);
+    if (N <= 0 || K <= 0 || N % kTileRows != 0 || K % kTileCols != 0)
+        return fail(LCD_ERR_BAD_SHAPE, "N=%d must be a positive multiple of %d and K=%d of %d", N, kTileRows, K, kTileCols);
+    if ((long long)N * (long long)K > (1ll << 40)) return fail(LCD_ERR_BAD_SHAPE, "N*K too large");
+    return LCD_OK;
+}
+
+static lcd_status check_aligned(const void *p, const char *name)
+{
+    if (!p) return fail(LCD_ERR_NULL, "%s is NULL", name);
+    if (reinterpret_cast<uintptr_t>(p) % 16 != 0) return fail(LCD_ERR_ALIGN, "%s is not 16-byte aligned", name);
+    return LCD_OK;
+}
+
+static size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+GemvPlan plan_gemv(int M, int N, int K, int bits)
+{
+    GemvPlan p{};
+    const int kc = K / kTileCols;
+    // A wave keeps the smoothed activations of `ch` chunks in registers (32 VGPRs per chunk;
+    // the 3-bit single-token path also keeps their negation).
+    p.ch = (M == 1 && bits == 3) ? 2 : 4;
+    const int kwaves = (kc + p.ch - 1) / p.ch;      // waves needed to cover K once
+    const int max_waves = 8;                        // keeps 2 waves per SIMD at <= 256 VGPRs
+    p.splits = (kwaves + max_waves - 1) / max_waves;
+    p.waves = (kwaves + p.splits - 1) / p.splits;
+    p.chunks_per_split = p.waves * p.ch;
+    const int row_tiles = N / kTileRows;
+    p.grid_x = row_tiles;
+    const int cap = 2048 / (p.waves * p.splits) > 0 ? 2048 / (p.waves * p.splits) : 1;  // ~2 waves per SIMD resident
+    if (p.grid_x > cap) p.grid_x = cap;
+    p.xs_bytes = (M > 1) ? round_up((size_t)M * K * 2, 256) : 0;
+    p.partial_bytes = (p.splits > 1) ? round_up((size_t)p.splits * M * N * 4, 256) : 0;
+    return p;
+}
+
+GemmPlan plan_gemm(int M, int N, int K, int bits)
+{
+    (void)N; (void)bits;
+    GemmPlan p{};
+    p.xs_bytes = round_up((size_t)M * K * 2, 256);
+    return p;
+}
+
+// ---- host packer: walks tiles and lanes, builds each lane's words -----------------------
+static void lane_words(const uint8_t *row64, int bits, uint32_t lo[4], uint32_t hi[2])
+{
+    lo[0] = lo[1] = lo[2] = lo[3] = 0;
+    hi[0] = hi[1] = 0;
+    for (int w = 0; w < 64; ++w) {
+        const uint32_t v = row64[w];
+        lo[w >> 4] |= (v & 3u) << (2 * (w & 15));
+        if (bits == 3) {
+            const int d = w >> 4, a = (w >> 3) & 1, e = w & 7;
+            const int bit = 8 * ((e >> 2) + 2 * (e & 1)) + 2 * d + ((e & 3) >> 1);
+            hi[a] |= ((v >> 2) & 1u) << bit;
+        }
+    }
+}
+
+static void put32(uint8_t *p, uint32_t v) { p[0] = v & 255; p[1] = (v >> 8) & 255; p[2] = (v >> 16) & 255; p[3] = v >> 24; }
+static uint32_t get32(const uint8_t *p) { return (uint32_t)p[0] | ((uint32_t)p[1] << 8) | ((uint32_t)p[2] << 16) | ((uint32_t)p[3] << 24); }
+
+}  // namespace lcd
+
+using namespace lcd;
+
+extern "C" {
+
+int lcd_version(void) { return LCD_VERSION; }
+int lcd_layout_revision(void) { return LCD_LAYOUT_REVISION; }
+const char *lcd_last_error_string(void) { return g_err; }
+
+const char *lcd_status_string(lcd_status st)
+{
+    switch (st) {
+    case LCD_OK: return "LCD_OK";
+    case LCD_ERR_NULL: return "LCD_ERR_NULL";
+    case LCD_ERR_BAD_BITS: return "LCD_ERR_BAD_BITS";
+    case LCD_ERR_BAD_SHAPE: return "LCD_ERR_BAD_SHAPE";
+    case LCD_ERR_BAD_M: return "LCD_ERR_BAD_M";
+    case LCD_ERR_SIZE: return "LCD_ERR_SIZE";
+    case LCD_ERR_INDEX_RANGE: return "LCD_ERR_INDEX_RANGE";
+    case LCD_ERR_ALIGN: return "LCD_ERR_ALIGN";
+    case LCD_ERR_HIP: return "LCD_ERR_HIP";
+    }
+    return "LCD_ERR_UNKNOWN";
+}
+
+size_t lcd_packed_bytes(int N, int K, int bits)
+{
+    if (check_shape(N, K, bits) != LCD_OK) return 0;
+    return (size_t)N * (size_t)K * (size_t)bits / 8;
+}
+
+size_t lcd_lut_bytes(int N, int bits)
+{
+    if ((bits != 2 && bits != 3) || N <= 0 || N % kTileRows != 0) return 0;
+    return (size_t)N * (bits == 2 ? 24 : 48);
+}
+
+size_t lcd_workspace_bytes(int M, int N, int K, int bits)
+{
+    if (check_shape(N, K, bits) != LCD_OK || M < 1) return 0;
+    size_t need = 256;
+    if (M <= 16) {
+        const GemvPlan g = plan_gemv(M, N, K, bits);
+        need = g.xs_bytes + g.partial_bytes;
+    }
+    const GemmPlan m = plan_gemm(M, N, K, bits);
+    if (m.xs_bytes > need) need = m.xs_bytes;
+    return need < 256 ? 256 : need;
+}
+
+lcd_status lcd_pack_indices_host(const uint8_t *idx, int N, int K, int bits, void *packed, size_t packed_bytes)
+{
+    if (lcd_status st = check_shape(N, K, bits)) return st;
+    if (!idx) return fail(LCD_ERR_NULL, "idx is NULL");
+    if (!packed) return fail(LCD_ERR_NULL, "packed is NULL");
+    const size_t need = lcd_packed_bytes(N, K, bits);
+    if (packed_bytes < need) return fail(LCD_ERR_SIZE, "packed_bytes=%zu < %zu", packed_bytes, need);
+    const int lim = 1 << bits;
+    for (size_t e = 0, n = (size_t)N * K; e < n; ++e)
+        if (idx[e] >= lim) return fail(LCD_ERR_INDEX_RANGE, "idx[%zu]=%d >= %d", e, (int)idx[e], lim);
+    uint8_t *out = static_cast<uint8_t *>(packed);
+    const int kc = K / kTileCols;
+    const size_t tb = tile_bytes(bits);
+    for (int t = 0; t < N / kTileRows; ++t)
+        for (int c = 0; c < kc; ++c) {
+            uint8_t *tile = out + ((size_t)t * kc + c) * tb;
+            for (int l = 0; l < 64; ++l) {
+                const int q = l >> 4, i = l & 15;
+                uint32_t lo[4], hi[2];
+                lane_words(idx + (size_t)(t * kTileRows + i) * K + (size_t)c * kTileCols + q * kLaneCols, bits, lo, hi);
+                for (int d = 0; d < 4; ++d) put32(tile + 16 * l + 4 * d, lo[d]);
+                if (bits == 3) { put32(tile + 1024 + 8 * l, hi[0]); put32(tile + 1024 + 8 * l + 4, hi[1]); }
+            }
+        }
+    return LCD_OK;
+}
+
+lcd_status lcd_unpack_indices_host(const void *packed, int N, int K, int bits, uint8_t *idx)
+{
+    if (lcd_status st = check_shape(N, K, bits)) return st;
+    if (!idx) return fail(LCD_ERR_NULL, "idx is NULL");
+    if (!packed) return fail(LCD_ERR_NULL, "packed is NULL");
+    const uint8_t *in = static_cast<const uint8_t *>(packed);
+    const int kc = K / kTileCols;
+    const size_t tb = tile_bytes(bits);
+    for (int t = 0; t < N / kTileRows; ++t)
+        for (int c = 0; c < kc; ++c) {
+            const uint8_t *tile = in + ((size_t)t * kc + c) * tb;
+            for (int l = 0; l < 64; ++l) {
+                const int q = l >> 4, i = l & 15;
+                uint8_t *row64 = idx + (size_t)(t * kTileRows + i) * K + (size_t)c * kTileCols + q * kLaneCols;
+                uint32_t hi[2] = {0, 0};
+                if (bits == 3) { hi[0] = get32(tile + 1024 + 8 * l); hi[1] = get32(tile + 1024 + 8 * l + 4); }
+                for (int w = 0; w < 64; ++w) {
+                    uint32_t v = (get32(tile + 16 * l + 4 * (w >> 4)) >> (2 * (w & 15))) & 3u;
+                    if (bits == 3) {
+                        const int d = w >> 4, a = (w >> 3) & 1, e = w & 7;
+                        const int bit = 8 * ((e >> 2) + 2 * (e & 1)) + 2 * d + ((e & 3) >> 1);
+                        v |= ((hi[a] >> bit) & 1u) << 2;
+                    }
+                    row64[w] = (uint8_t)v;
+                }
+            }
+        }
+    return LCD_OK;
+}
+
+lcd_status lcd_pack_indices(const uint8_t *idx, int N, int K, int bits, void *packed, size_t packed_bytes, void *stream)
+{
+    if (lcd_status st = check_shape(N, K, bits)) return st;
+    if (lcd_status st = check_aligned(idx, "idx")) return st;
+    if (lcd_status st = check_aligned(packed, "packed")) return st;
+    const size_t need = lcd_packed_bytes(N, K, bits);
+    if (packed_bytes < need) return fail(LCD_ERR_SIZE, "packed_bytes=%zu < %zu", packed_bytes, need);
+    if (int e = launch_pack(idx, N, K, bits, packed, stream)) return fail(LCD_ERR_HIP, "pack launch: %s", hip_error_name(e));
+    return LCD_OK;
+}
+
+lcd_status lcd_unpack_indices(const void *packed, int N, int K, int bits, uint8_t *idx, void *stream)
+{
+    if (lcd_status st = check_shape(N, K, bits)) return st;
+    if (lcd_status st = check_aligned(packed, "packed")) return st;
+    if (lcd_status st = check_aligned(idx, "idx")) return st;
+    if (int e = launch_unpack(packed, N, K, bits, idx, stream)) return fail(LCD_ERR_HIP, "unpack launch: %s", hip_error_name(e));
+    return LCD_OK;
+}
+
+lcd_status lcd_build_lut(const uint16_t *codebook, int N, int bits, void *lut, size_t lut_bytes, void *stream)
+{
+    if (bits != 2 && bits != 3) return fail(LCD_ERR_BAD_BITS, "bits=%d: only 2 and 3 are supported", bits);
+    if (N <= 0 || N % kTileRows != 0) return fail(LCD_ERR_BAD_SHAPE, "N=%d must be a positive multiple of %d", N, kTileRows);
+    if (lcd_status st = check_aligned(codebook, "codebook")) return st;
+    if (lcd_status st = check_aligned(lut, "lut")) return st;
+    const size_t need = lcd_lut_bytes(N, bits);
+    if (lut_bytes < need) return fail(LCD_ERR_SIZE, "lut_bytes=%zu < %zu", lut_bytes, need);
+    if (int e = launch_build_lut(codebook, N, bits, lut, stream)) return fail(LCD_ERR_HIP, "build_lut launch: %s", hip_error_name(e));
+    return LCD_OK;
+}
+
+static lcd_status check_product(const void *packed, const void *lut, const uint16_t *x, const float *s, uint16_t *y,
+                                int M, int N, int K, int bits, void *workspace, size_t workspace_bytes)
+{
+    if (lcd_status st = check_shape(N, K, bits)) return st;
+    if (M < 1) return fail(LCD_ERR_BAD_M, "M=%d must be >= 1", M);
+    if (lcd_status st = check_aligned(packed, "packed")) return st;
+    if (lcd_status st = check_aligned(lut, "lut")) return st;
+    if (lcd_status st = check_aligned(x, "x")) return st;
+    if (lcd_status st = check_aligned(s, "s")) return st;
+    if (lcd_status st = check_aligned(y, "y")) return st;
+    if (lcd_status st = check_aligned(workspace, "workspace")) return st;
+    const size_t need = lcd_workspace_bytes(M, N, K, bits);
+    if (workspace_bytes < need) return fail(LCD_ERR_SIZE, "workspace_bytes=%zu < %zu", workspace_bytes, need);
+    return LCD_OK;
+}
+
+lcd_status lcd_lut_gemv(const void *packed, const void *lut, const uint16_t *x, const float *s, uint16_t *y,
+                        int M, int N, int K, int bits, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (M > 16) return fail(LCD_ERR_BAD_M, "lcd_lut_gemv: M=%d > 16 (use lcd_lut_gemm)", M);
+    if (lcd_status st = check_product(packed, lut, x, s, y, M, N, K, bits, workspace, workspace_bytes)) return st;
+    const GemvPlan plan = plan_gemv(M, N, K, bits);
+    if (int e = launch_gemv(packed, lut, x, s, y, M, N, K, bits, workspace, plan, stream))
+        return fail(LCD_ERR_HIP, "gemv launch: %s", hip_error_name(e));
+    return LCD_OK;
+}
+
+lcd_status lcd_lut_gemm(const void *packed, const void *lut, const uint16_t *x, const float *s, uint16_t *y,
+                        int M, int N, int K, int bits, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (lcd_status st = check_product(packed, lut, x, s, y, M, N, K, bits, workspace, workspace_bytes)) return st;
+    const GemmPlan plan = plan_gemm(M, N, K, bits);
+    if (int e = launch_gemm(packed, lut, x, s, y, M, N, K, bits, workspace, plan, stream))
+        return fail(LCD_ERR_HIP, "gemm launch: %s", hip_error_name(e));
+    return LCD_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,216 @@
+// Offline kernels: index packing / unpacking, table build, and the small helper kernels
+// (activation smoothing, split-K reduction).  Layout: see include/lcd.h.
+#include <hip/hip_runtime.h>
+#include "lcd_internal.h"
+#include "lcd_device.h"
+
+namespace lcd {
+
+// ---- pack: one thread per (tile, lane); reads the lane's 64 index bytes, writes its words ----
+template <int BITS>
+__global__ void __launch_bounds__(256) pack_kernel(const uint8_t *__restrict__ idx, uint8_t *__restrict__ packed,
+                                                   int N, int K, long long total)
+{
+    const long long g = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (g >= total) return;
+    const int kc = K / kTileCols;
+    const int l = (int)(g & 63);
+    const long long tile = g >> 6;
+    const int c = (int)(tile % kc);
+    const long long t = tile / kc;
+    const int q = l >> 4, i = l & 15;
+    const uint4v *src = reinterpret_cast<const uint4v *>(idx + (size_t)(t * kTileRows + i) * K + (size_t)c * kTileCols + q * kLaneCols);
+    uint32_t lo[4] = {0, 0, 0, 0}, hi[2] = {0, 0};
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        const uint4v v = src[d];  // 16 indices, one per byte
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t word = v[j];
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const int e16 = 4 * j + b;                 // position inside this group of 16
+                const uint32_t val = (word >> (8 * b)) & ((1u << BITS) - 1u);
+                lo[d] |= (val & 3u) << (2 * e16);
+                if (BITS == 3) {
+                    const int a = e16 >> 3, e = e16 & 7;
+                    const int bit = 8 * ((e >> 2) + 2 * (e & 1)) + 2 * d + ((e & 3) >> 1);
+                    hi[a] |= (val >> 2) << bit;
+                }
+            }
+        }
+    }
+    uint8_t *tile_ptr = packed + (size_t)tile * (BITS == 2 ? 1024 : 1536);
+    uint4v o = {lo[0], lo[1], lo[2], lo[3]};
+    *reinterpret_cast<uint4v *>(tile_ptr + 16 * l) = o;
+    if (BITS == 3) {
+        uint2v h = {hi[0], hi[1]};
+        *reinterpret_cast<uint2v *>(tile_ptr + 1024 + 8 * l) = h;
+    }
+}
+
+template <int BITS>
+__global__ void __launch_bounds__(256) unpack_kernel(const uint8_t *__restrict__ packed, uint8_t *__restrict__ idx,
+                                                     int N, int K, long long total)
+{
+    const long long g = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (g >= total) return;
+    const int kc = K / kTileCols;
+    const int l = (int)(g & 63);
+    const long long tile = g >> 6;
+    const int c = (int)(tile % kc);
+    const long long t = tile / kc;
+    const int q = l >> 4, i = l & 15;
+    const uint8_t *tile_ptr = packed + (size_t)tile * (BITS == 2 ? 1024 : 1536);
+    const uint4v lo = *reinterpret_cast<const uint4v *>(tile_ptr + 16 * l);
+    uint2v hi = {0, 0};
+    if (BITS == 3) hi = *reinterpret_cast<const uint2v *>(tile_ptr + 1024 + 8 * l);
+    uint4v *dst = reinterpret_cast<uint4v *>(idx + (size_t)(t * kTileRows + i) * K + (size_t)c * kTileCols + q * kLaneCols);
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        uint4v out;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            uint32_t word = 0;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const int e16 = 4 * j + b;
+                uint32_t val = (lo[d] >> (2 * e16)) & 3u;
+                if (BITS == 3) {
+                    const int a = e16 >> 3, e = e16 & 7;
+                    const int bit = 8 * ((e >> 2) + 2 * (e & 1)) + 2 * d + ((e & 3) >> 1);
+                    val |= ((hi[a] >> bit) & 1u) << 2;
+                }
+                word |= val << (8 * b);
+            }
+            out[j] = word;
+        }
+        dst[d] = out;
+    }
+}
+
+// ---- table build: one thread per output row -----------------------------------------------
+// Section A (fp32, accumulator order): element ((n/4)*NC + j)*4 + n%4, NC = 4 (2 bits) or 8.
+//   2 bits: A[j] = C[n][j].   3 bits: A[j] = (C[n][j] + C[n][4+j])/2, A[4+j] = (C[n][j] - C[n][4+j])/2,
+//   so that C[n][4h+l] = A[l] + (1-2h) * A[4+l].
+// Section B (byte-split tables for v_perm_b32), starting at byte N*NC*4:
+//   2 bits: per row {low bytes of C[n][0..3], high bytes of C[n][0..3]}            (8 bytes)
+//   3 bits: per row {low 0..3, low 4..7, high 0..3, high 4..7}                      (16 bytes)
+template <int BITS>
+__global__ void __launch_bounds__(256) build_lut_kernel(const uint16_t *__restrict__ codebook, uint8_t *__restrict__ lut, int N)
+{
+    const int n = blockIdx.x * blockDim.x + threadIdx.x;
+    if (n >= N) return;
+    constexpr int NCENT = 1 << BITS;
+    constexpr int NC = BITS == 2 ? 4 : 8;
+    uint16_t c[NCENT];
+#pragma unroll
+    for (int j = 0; j < NCENT; ++j) c[j] = codebook[(size_t)n * NCENT + j];
+    float *secA = reinterpret_cast<float *>(lut);
+    const size_t baseA = (size_t)(n >> 2) * NC * 4 + (n & 3);
+    if (BITS == 2) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) secA[baseA + 4 * j] = (float)__builtin_bit_cast(_Float16, c[j]);
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float c0 = (float)__builtin_bit_cast(_Float16, c[j]);
+            const float c1 = (float)__builtin_bit_cast(_Float16, c[4 + j]);
+            secA[baseA + 4 * j] = 0.5f * (c0 + c1);
+            secA[baseA + 4 * (4 + j)] = 0.5f * (c0 - c1);
+        }
+    }
+    uint32_t *secB = reinterpret_cast<uint32_t *>(lut + (size_t)N * NC * 4);
+    if (BITS == 2) {
+        uint32_t lo = 0, hi = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { lo |= (uint32_t)(c[j] & 255) << (8 * j); hi |= (uint32_t)(c[j] >> 8) << (8 * j); }
+        secB[2 * (size_t)n] = lo;
+        secB[2 * (size_t)n + 1] = hi;
+    } else {
+        uint32_t lo0 = 0, lo1 = 0, hi0 = 0, hi1 = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            lo0 |= (uint32_t)(c[j] & 255) << (8 * j);      hi0 |= (uint32_t)(c[j] >> 8) << (8 * j);
+            lo1 |= (uint32_t)(c[4 + j] & 255) << (8 * j);  hi1 |= (uint32_t)(c[4 + j] >> 8) << (8 * j);
+        }
+        uint4v o = {lo0, lo1, hi0, hi1};
+        reinterpret_cast<uint4v *>(secB)[n] = o;
+    }
+}
+
+// ---- activation smoothing: xs[m][k] = fp16( x[m][k] / s[k] )  (paper Sec. 3.4) -------------
+__global__ void __launch_bounds__(256) smooth_kernel(const uint16_t *__restrict__ x, const float *__restrict__ s,
+                                                     _Float16 *__restrict__ xs, int K, long long total)
+{
+    long long e = ((long long)blockIdx.x * blockDim.x + threadIdx.x) * 8;
+    if (e >= total) return;  // total = M*K, K % 256 == 0 so groups of 8 never straddle rows
+    const int k = (int)(e % K);
+    const uint4v xv = *reinterpret_cast<const uint4v *>(x + e);
+    const float4v s0 = *reinterpret_cast<const float4v *>(s + k);
+    const float4v s1 = *reinterpret_cast<const float4v *>(s + k + 4);
+    half8 o;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const uint16_t xb = (uint16_t)(xv[j >> 1] >> (16 * (j & 1)));
+        o[j] = smooth_one(xb, j < 4 ? s0[j] : s1[j - 4]);
+    }
+    *reinterpret_cast<half8 *>(xs + e) = o;
+}
+
+// ---- split-K reduction: y = fp16( sum_s partial[s] ), fixed order --------------------------
+__global__ void __launch_bounds__(256) reduce_kernel(const float *__restrict__ partial, uint16_t *__restrict__ y,
+                                                     int splits, long long total)
+{
+    const long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= total) return;
+    float acc = 0.f;
+    for (int sidx = 0; sidx < splits; ++sidx) acc += partial[(size_t)sidx * total + e];
+    y[e] = __builtin_bit_cast(uint16_t, (_Float16)acc);
+}
+
+int launch_smooth(const uint16_t *x, const float *s, void *xs, int M, int K, void *stream)
+{
+    const long long total = (long long)M * K;
+    const long long threads = total / 8;
+    hipLaunchKernelGGL(smooth_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
+                       x, s, (_Float16 *)xs, K, total);
+    return (int)hipGetLastError();
+}
+
+int launch_reduce(const float *partial, uint16_t *y, int splits, long long total, void *stream)
+{
+    hipLaunchKernelGGL(reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
+                       partial, y, splits, total);
+    return (int)hipGetLastError();
+}
+
+int launch_pack(const uint8_t *idx, int N, int K, int bits, void *packed, void *stream)
+{
+    const long long total = (long long)(N / kTileRows) * (K / kTileCols) * 64;
+    const dim3 grid((unsigned)((total + 255) / 256)), block(256);
+    if (bits == 2) hipLaunchKernelGGL(pack_kernel<2>, grid, block, 0, (hipStream_t)stream, idx, (uint8_t *)packed, N, K, total);
+    else hipLaunchKernelGGL(pack_kernel<3>, grid, block, 0, (hipStream_t)stream, idx, (uint8_t *)packed, N, K, total);
+    return (int)hipGetLastError();
+}
+
+int launch_unpack(const void *packed, int N, int K, int bits, uint8_t *idx, void *stream)
+{
+    const long long total = (long long)(N / kTileRows) * (K / kTileCols) * 64;
+    const dim3 grid((unsigned)((total + 255) / 256)), block(256);
+    if (bits == 2) hipLaunchKernelGGL(unpack_kernel<2>, grid, block, 0, (hipStream_t)stream, (const uint8_t *)packed, idx, N, K, total);
+    else hipLaunchKernelGGL(unpack_kernel<3>, grid, block, 0, (hipStream_t)stream, (const uint8_t *)packed, idx, N, K, total);
+    return (int)hipGetLastError();
+}
+
+int launch_build_lut(const uint16_t *codebook, int N, int bits, void *lut, void *stream)
+{
+    const dim3 grid((unsigned)((N + 255) / 256)), block(256);
+    if (bits == 2) hipLaunchKernelGGL(build_lut_kernel<2>, grid, block, 0, (hipStream_t)stream, codebook, (uint8_t *)lut, N);
+    else hipLaunchKernelGGL(build_lut_kernel<3>, grid, block, 0, (hipStream_t)stream, codebook, (uint8_t *)lut, N);
+    return (int)hipGetLastError();
+}
+
+const char *hip_error_name(int err) { return hipGetErrorString((hipError_t)err); }
+
+}  // namespace lcd

@@ -1,0 +1,120 @@
+"""CPU-only tests of the C-ABI library: exports, size arithmetic, host packer, error paths."""
+import ctypes
+import re
+from pathlib import Path
+
+import numpy as np
+import pytest
+
+import paper_2506_12038_amd as lcd
+from oracle.pack_ref import pack_ref, unpack_ref
+
+ROOT = Path(__file__).resolve().parent.parent
+
+
+def declared_functions():
+    text = (ROOT / "include" / "lcd.h").read_text()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(lcd_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = lcd.load_library()
+    names = declared_functions()
+    assert "lcd_lut_gemv" in names and "lcd_pack_indices" in names and len(names) >= 14
+    for name in names:
+        assert hasattr(lib, name), f"{name} declared in lcd.h but not exported"
+    assert set(lcd.EXPORTS) == set(names)
+    assert lcd.lcd_version() >= 100 and lcd.lcd_layout_revision() == 1
+
+
+def test_size_functions():
+    assert lcd.lcd_packed_bytes(4096, 4096, 2) == 4194304
+    assert lcd.lcd_packed_bytes(4096, 4096, 3) == 6291456
+    assert lcd.lcd_packed_bytes(11008, 4096, 3) == 16908288
+    assert lcd.lcd_packed_bytes(28672, 8192, 2) == 58720256
+    assert lcd.lcd_packed_bytes(4096, 4096, 4) == 0
+    assert lcd.lcd_packed_bytes(4100, 4096, 2) == 0 and lcd.lcd_packed_bytes(4096, 4100, 2) == 0
+    assert lcd.lcd_lut_bytes(4096, 2) == 4096 * 24 and lcd.lcd_lut_bytes(4096, 3) == 4096 * 48
+    for M, N, K, bits in [(1, 4096, 4096, 2), (16, 11008, 4096, 2), (2048, 4096, 11008, 3), (8, 8192, 28672, 2)]:
+        w = lcd.lcd_workspace_bytes(M, N, K, bits)
+        assert w >= 256 and w % 256 == 0
+    assert lcd.lcd_workspace_bytes(0, 4096, 4096, 2) == 0
+
+
+@pytest.mark.parametrize("bits", [2, 3])
+@pytest.mark.parametrize("shape", [(16, 256), (48, 768), (32, 1024)])
+def test_host_packer_matches_layout_definition(bits, shape):
+    N, K = shape
+    idx = np.random.default_rng(10 * bits + N).integers(0, 1 << bits, size=(N, K), dtype=np.uint8)
+    packed = lcd.lcd_pack_indices_host(idx, bits)
+    assert packed.size == N * K * bits // 8
+    assert np.array_equal(packed, pack_ref(idx, bits))
+    assert np.array_equal(lcd.lcd_unpack_indices_host(packed, N, K, bits), idx)
+    assert np.array_equal(unpack_ref(packed, N, K, bits), idx)
+
+
+def test_golden_bytes_hand_worked():
+    # One 16x256 tile, all zero except four entries; byte positions worked by hand from the
+    # layout text in lcd.h:
+    #  (n=0,k=0)=3   -> lane 0, w=0: bits [1:0] of tile byte 0            -> byte 0 = 0x03
+    #  (n=1,k=5)=2   -> lane 1, w=5: bits [11:10] of the word at byte 16  -> byte 17 = 0x08
+    #  (n=2,k=64)=1  -> lane 16+2, w=0: word at byte 288                  -> byte 288 = 0x01
+    #  (n=15,k=255)=3-> lane 48+15=63, w=63: bits [127:126] at byte 1008  -> byte 1023 = 0xC0
+    idx = np.zeros((16, 256), dtype=np.uint8)
+    idx[0, 0] = 3; idx[1, 5] = 2; idx[2, 64] = 1; idx[15, 255] = 3
+    p = lcd.lcd_pack_indices_host(idx, 2)
+    expect = np.zeros(1024, dtype=np.uint8)
+    expect[0] = 0x03; expect[17] = 0x08; expect[288] = 0x01; expect[1023] = 0xC0
+    assert np.array_equal(p, expect)
+    # 3-bit: same low fields plus the third-bit plane.
+    #  (n=0,k=0)=7:  w=0 -> d=0,a=0,e=0 -> word 0 of lane 0, bit 0        -> byte 1024 = 0x01
+    #  (n=1,k=5)=6:  w=5 -> d=0,a=0,e=5 -> bit 8*(1+2)+0+0 = 24           -> byte 1024+8+3 = 0x01
+    #  (n=2,k=64+27)=4: lane 18, w=27 -> d=1,a=1,e=3 -> word 1, bit 8*(0+2)+2+1 = 19 -> byte 1024+144+4+2 = 0x08
+    idx3 = np.zeros((16, 256), dtype=np.uint8)
+    idx3[0, 0] = 7; idx3[1, 5] = 6; idx3[2, 91] = 4
+    p3 = lcd.lcd_pack_indices_host(idx3, 3)
+    e3 = np.zeros(1536, dtype=np.uint8)
+    e3[0] = 0x03; e3[17] = 0x08
+    e3[1024] = 0x01; e3[1024 + 8 + 3] = 0x01; e3[1024 + 144 + 4 + 2] = 0x08
+    assert np.array_equal(p3, e3)
+
+
+def test_host_packer_rejects_out_of_range_and_bad_shapes():
+    idx = np.zeros((16, 256), dtype=np.uint8)
+    idx[3, 7] = 4
+    with pytest.raises(lcd.LcdError) as ei:
+        lcd.lcd_pack_indices_host(idx, 2)
+    assert ei.value.name == "LCD_ERR_INDEX_RANGE"
+    lcd.lcd_pack_indices_host(idx, 3)  # 4 is fine for 3 bits
+    lib = lcd.load_library()
+    buf = np.zeros(4096, dtype=np.uint8)
+    ok_idx = np.zeros((16, 256), dtype=np.uint8)
+    ip, bp = ok_idx.ctypes.data_as(ctypes.c_void_p), buf.ctypes.data_as(ctypes.c_void_p)
+    assert lib.lcd_status_string(lib.lcd_pack_indices_host(ip, 16, 256, 5, bp, 4096)) == b"LCD_ERR_BAD_BITS"
+    assert lib.lcd_status_string(lib.lcd_pack_indices_host(ip, 15, 256, 2, bp, 4096)) == b"LCD_ERR_BAD_SHAPE"
+    assert lib.lcd_status_string(lib.lcd_pack_indices_host(ip, 16, 128, 2, bp, 4096)) == b"LCD_ERR_BAD_SHAPE"
+    assert lib.lcd_status_string(lib.lcd_pack_indices_host(ip, 16, 256, 2, bp, 100)) == b"LCD_ERR_SIZE"
+    assert lib.lcd_status_string(lib.lcd_pack_indices_host(None, 16, 256, 2, bp, 4096)) == b"LCD_ERR_NULL"
+    assert b"packed_bytes" in lib.lcd_last_error_string() or b"NULL" in lib.lcd_last_error_string()
+
+
+def test_device_entry_points_validate_before_launch():
+    # Host-side validation fails before any HIP call, so these run without a GPU.
+    lib = lcd.load_library()
+    a = ctypes.c_void_p(0x1000)       # fake, aligned, never dereferenced: validation fails first
+    odd = ctypes.c_void_p(0x1004)
+    st = lambda code: lib.lcd_status_string(code)
+    assert st(lib.lcd_pack_indices(None, 16, 256, 2, a, 1024, None)) == b"LCD_ERR_NULL"
+    assert st(lib.lcd_pack_indices(odd, 16, 256, 2, a, 1024, None)) == b"LCD_ERR_ALIGN"
+    assert st(lib.lcd_pack_indices(a, 16, 256, 2, a, 1000, None)) == b"LCD_ERR_SIZE"
+    assert st(lib.lcd_unpack_indices(a, 16, 250, 2, a, None)) == b"LCD_ERR_BAD_SHAPE"
+    assert st(lib.lcd_build_lut(a, 16, 4, a, 4096, None)) == b"LCD_ERR_BAD_BITS"
+    assert st(lib.lcd_build_lut(a, 16, 2, a, 10, None)) == b"LCD_ERR_SIZE"
+    big = 1 << 30
+    assert st(lib.lcd_lut_gemv(a, a, a, a, a, 17, 16, 256, 2, a, big, None)) == b"LCD_ERR_BAD_M"
+    assert st(lib.lcd_lut_gemv(a, a, a, a, a, 0, 16, 256, 2, a, big, None)) == b"LCD_ERR_BAD_M"
+    assert st(lib.lcd_lut_gemv(a, a, a, a, a, 1, 16, 256, 2, a, 0, None)) == b"LCD_ERR_SIZE"
+    assert st(lib.lcd_lut_gemv(a, a, a, odd, a, 1, 16, 256, 2, a, big, None)) == b"LCD_ERR_ALIGN"
+    assert st(lib.lcd_lut_gemm(a, a, None, a, a, 64, 16, 256, 3, a, big, None)) == b"LCD_ERR_NULL"
+    assert st(lib.lcd_lut_gemm(a, a, a, a, a, 64, 16, 256, 1, a, big, None)) == b"LCD_ERR_BAD_BITS"
