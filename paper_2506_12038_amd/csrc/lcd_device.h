@@ -38,3 +38,49 @@ __device__ __forceinline__ _Float16 smooth_one(uint16_t xbits, float s)
 }
 
 }  // namespace lcd
+
+namespace lcd {
+
+// ---- register dequantiser: 16 packed indices -> two fp16 MFMA A operands ------------------
+// v_perm_b32(hi4, lo4, sel): result byte b = byte sel[b] of the 8-byte pool {hi4 (4..7), lo4 (0..3)}.
+__device__ __forceinline__ uint32_t perm(uint32_t hi4, uint32_t lo4, uint32_t sel) { return __builtin_amdgcn_perm(hi4, lo4, sel); }
+
+// Per-row byte-split codebook: lo[0]/hi[0] hold the low/high bytes of centroids 0..3,
+// lo[1]/hi[1] those of centroids 4..7 (3 bits only).
+struct RowTables { uint32_t lo[2]; uint32_t hi[2]; };
+
+// 3-bit only: the lane's two high-bit words, regrouped once per 64 weights so that the bits
+// of selector t sit at one in-byte position of four bytes.
+struct HighBits { uint32_t even, odd; };
+__device__ __forceinline__ HighBits regroup_high(uint2v h)
+{
+    HighBits r;
+    r.even = perm(h[1], h[0], 0x05040100u);
+    r.odd = perm(h[1], h[0], 0x07060302u);
+    return r;
+}
+
+// Decode low-plane word `p` (word d of the lane: 16 weights) into operand a=0 (weights
+// 16d + [0,8)) and operand a=1 (weights 16d + [8,16)).  Register v of an operand holds the
+// fp16 pair (weight v, weight 4+v) of its 8 weights, so the activation operand must use the
+// slot order 0,4,1,5,2,6,3,7.
+template <int BITS, int D>
+__device__ __forceinline__ void decode_word(uint32_t p, const HighBits &hb, const RowTables &tb, uint4v &op0, uint4v &op1)
+{
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        uint32_t sel = (p >> (2 * t)) & 0x03030303u;
+        if (BITS == 3) {
+            const int beta = 2 * D + (t >> 1);            // in-byte position of the high bit
+            const uint32_t r = (t & 1) ? hb.odd : hb.even;
+            const uint32_t sh = beta >= 2 ? (r >> (beta - 2)) : (r << (2 - beta));
+            sel |= sh & 0x04040404u;
+        }
+        const uint32_t lo = perm(BITS == 3 ? tb.lo[1] : 0u, tb.lo[0], sel);
+        const uint32_t hi = perm(BITS == 3 ? tb.hi[1] : 0u, tb.hi[0], sel);
+        op0[t] = perm(hi, lo, 0x05010400u);
+        op1[t] = perm(hi, lo, 0x07030602u);
+    }
+}
+
+}  // namespace lcd

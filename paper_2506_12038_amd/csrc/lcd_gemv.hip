@@ -25,8 +25,6 @@
 
 namespace lcd {
 
-int launch_smooth(const uint16_t *x, const float *s, void *xs, int M, int K, void *stream);
-int launch_reduce(const float *partial, uint16_t *y, int splits, long long total, void *stream);
 
 constexpr int kMaxWaves = 8;
 
@@ -170,6 +168,126 @@ gemv_bucket_kernel(const uint8_t *__restrict__ packed, const float *__restrict__
     }
 }
 
+// ---- batched decode kernel (2 <= M <= 16) ---------------------------------------------------
+// Same work split as the bucket kernel, but the 16 columns of the matrix core's output tile are
+// the tokens: the packed indices are dequantised in registers (v_perm_b32 through per-row
+// byte-split codebook tables) into the A operand of v_mfma_f32_16x16x32_f16, and the smoothed
+// activations of the wave's K range stay in registers as B operands.
+template <int BITS, int CH>
+struct DenseTileRegs {
+    uint4v lo[CH];
+    uint2v hi[CH];
+    RowTables tb;
+};
+
+template <int BITS, int CH>
+__device__ __forceinline__ void load_dense_tile(DenseTileRegs<BITS, CH> &r, const uint8_t *__restrict__ packed,
+                                                const uint8_t *__restrict__ lutB, int t, int kc, int c_begin, int nch, int lane)
+{
+    constexpr size_t TB = BITS == 2 ? 1024 : 1536;
+    const uint8_t *base = packed + ((size_t)t * kc + c_begin) * TB;
+#pragma unroll
+    for (int ch = 0; ch < CH; ++ch) {
+        if (ch < nch) {
+            r.lo[ch] = __builtin_nontemporal_load(reinterpret_cast<const uint4v *>(base + ch * TB + 16 * lane));
+            if (BITS == 3) r.hi[ch] = __builtin_nontemporal_load(reinterpret_cast<const uint2v *>(base + ch * TB + 1024 + 8 * lane));
+        }
+    }
+    const size_t row = (size_t)t * kTileRows + (lane & 15);
+    if (BITS == 2) {
+        const uint2v v = *reinterpret_cast<const uint2v *>(lutB + row * 8);
+        r.tb.lo[0] = v[0]; r.tb.hi[0] = v[1]; r.tb.lo[1] = 0; r.tb.hi[1] = 0;
+    } else {
+        const uint4v v = *reinterpret_cast<const uint4v *>(lutB + row * 16);
+        r.tb.lo[0] = v[0]; r.tb.lo[1] = v[1]; r.tb.hi[0] = v[2]; r.tb.hi[1] = v[3];
+    }
+}
+
+template <int BITS, int CH, int D>
+__device__ __forceinline__ void dense_word(const DenseTileRegs<BITS, CH> &r, int ch, const HighBits &hb,
+                                           const uint4v (&Bx)[CH][8], float4v (&acc)[2])
+{
+    uint4v op0, op1;
+    decode_word<BITS, D>(r.lo[ch][D], hb, r.tb, op0, op1);
+    acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(op0), as_half8(Bx[ch][2 * D]), acc[0], 0, 0, 0);
+    acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(op1), as_half8(Bx[ch][2 * D + 1]), acc[1], 0, 0, 0);
+}
+
+template <int BITS, int CH>
+__global__ void __launch_bounds__(kMaxWaves * 64, 1)
+gemv_dense_kernel(const uint8_t *__restrict__ packed, const uint8_t *__restrict__ lutB, const _Float16 *__restrict__ xs,
+                  uint16_t *__restrict__ y, float *__restrict__ partial, int M, int N, int K, int chunks_per_split, int splits)
+{
+    __shared__ __attribute__((aligned(16))) float part[2][kMaxWaves][16][16];  // [buf][wave][token][row]
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+    const int q = lane >> 4, j = lane & 15, bq = lane >> 4;
+    const int kc = K / kTileCols, nt = N / kTileRows;
+    const int split = blockIdx.y;
+    const int split_c0 = split * chunks_per_split;
+    const int split_c1 = min(kc, split_c0 + chunks_per_split);
+    const int c_begin = split_c0 + wave * CH;
+    const int nch = max(0, min(CH, split_c1 - c_begin));
+
+    DenseTileRegs<BITS, CH> r0, r1;
+    int t = blockIdx.x;
+    if (t < nt) load_dense_tile<BITS, CH>(r0, packed, lutB, t, kc, c_begin, nch, lane);
+
+    // B operands: lane (q, token j) keeps xs[j][chunk*256 + 64q + 8g + 0..7] for every chunk it owns
+    uint4v Bx[CH][8];
+#pragma unroll
+    for (int ch = 0; ch < CH; ++ch)
+#pragma unroll
+        for (int g = 0; g < 8; ++g) {
+            uint4v v = {0u, 0u, 0u, 0u};
+            if (ch < nch && j < M)
+                v = *reinterpret_cast<const uint4v *>(xs + (size_t)j * K + (size_t)(c_begin + ch) * kTileCols + 64 * q + 8 * g);
+            Bx[ch][g] = v;
+        }
+
+    auto process = [&](const DenseTileRegs<BITS, CH> &r, int tile, int buf) {
+        float4v acc[2] = {float4v{0.f, 0.f, 0.f, 0.f}, float4v{0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+        for (int ch = 0; ch < CH; ++ch) {
+            if (ch < nch) {
+                HighBits hb{0u, 0u};
+                if (BITS == 3) hb = regroup_high(r.hi[ch]);
+                dense_word<BITS, CH, 0>(r, ch, hb, Bx, acc);
+                dense_word<BITS, CH, 1>(r, ch, hb, Bx, acc);
+                dense_word<BITS, CH, 2>(r, ch, hb, Bx, acc);
+                dense_word<BITS, CH, 3>(r, ch, hb, Bx, acc);
+            }
+        }
+        // accumulator: lane (bq, j) holds rows 4bq..4bq+3 of token j
+        const float4v p = acc[0] + acc[1];
+        *reinterpret_cast<float4v *>(&part[buf][wave][j][4 * bq]) = p;
+        __syncthreads();
+        {
+            const int e = threadIdx.x;
+            for (int o = e; o < 16 * M; o += blockDim.x) {
+                const int m = o >> 4, row = o & 15;
+                float sum = 0.f;
+                for (int w = 0; w < nwaves; ++w) sum += part[buf][w][m][row];
+                const size_t dst = (size_t)m * N + (size_t)tile * kTileRows + row;
+                if (splits == 1) y[dst] = __builtin_bit_cast(uint16_t, (_Float16)sum);
+                else partial[(size_t)split * M * N + dst] = sum;
+            }
+        }
+    };
+
+    const int stride = gridDim.x;
+    while (t < nt) {
+        const int t1 = t + stride;
+        if (t1 < nt) load_dense_tile<BITS, CH>(r1, packed, lutB, t1, kc, c_begin, nch, lane);
+        process(r0, t, 0);
+        if (t1 >= nt) break;
+        const int t2 = t1 + stride;
+        if (t2 < nt) load_dense_tile<BITS, CH>(r0, packed, lutB, t2, kc, c_begin, nch, lane);
+        process(r1, t1, 1);
+        t = t2;
+    }
+}
+
 template <int BITS, int CH>
 static int launch_bucket(const void *packed, const void *lut, const uint16_t *x, const float *s, uint16_t *y,
                          float *partial, int N, int K, const GemvPlan &plan, hipStream_t stream)
@@ -191,13 +309,20 @@ int launch_gemv(const void *packed, const void *lut, const uint16_t *x, const fl
         if (plan.splits > 1) return launch_reduce(partial, y, plan.splits, (long long)N, stream);
         return 0;
     }
-    return (int)hipErrorNotSupported;
-}
-
-int launch_gemm(const void *, const void *, const uint16_t *, const float *, uint16_t *, int, int, int, int, void *,
-                const GemmPlan &, void *)
-{
-    return (int)hipErrorNotSupported;
+    // batched: smooth once into the workspace (dequantiser slot order), then the dense kernel
+    _Float16 *xs = reinterpret_cast<_Float16 *>(workspace);
+    if (int e = launch_smooth(x, s, xs, M, M, K, 0, stream)) return e;
+    const uint8_t *lutB = static_cast<const uint8_t *>(lut) + (size_t)N * (bits == 2 ? 4 : 8) * 4;
+    const dim3 grid(plan.grid_x, plan.splits), block(plan.waves * 64);
+    if (bits == 2)
+        hipLaunchKernelGGL((gemv_dense_kernel<2, 4>), grid, block, 0, stream, (const uint8_t *)packed, lutB, xs, y, partial,
+                           M, N, K, plan.chunks_per_split, plan.splits);
+    else
+        hipLaunchKernelGGL((gemv_dense_kernel<3, 4>), grid, block, 0, stream, (const uint8_t *)packed, lutB, xs, y, partial,
+                           M, N, K, plan.chunks_per_split, plan.splits);
+    if (int e = (int)hipGetLastError()) return e;
+    if (plan.splits > 1) return launch_reduce(partial, y, plan.splits, (long long)M * N, stream);
+    return 0;
 }
 
 }  // namespace lcd

@@ -62,7 +62,8 @@ GemmPlan plan_gemm(int M, int N, int K, int bits)
 {
     (void)N; (void)bits;
     GemmPlan p{};
-    p.xs_bytes = round_up((size_t)M * K * 2, 256);
+    p.m_pad = (M + 127) / 128 * 128;
+    p.xs_bytes = round_up((size_t)p.m_pad * K * 2, 256);
     return p;
 }
 

@@ -30,7 +30,8 @@ struct GemvPlan {
 GemvPlan plan_gemv(int M, int N, int K, int bits);
 
 struct GemmPlan {
-    size_t xs_bytes;       // workspace: smoothed activations fp16 [M][K]
+    int m_pad;             // tokens rounded up to the workgroup tile (128)
+    size_t xs_bytes;       // workspace: smoothed activations fp16, operand order, m_pad x K
 };
 GemmPlan plan_gemm(int M, int N, int K, int bits);
 
@@ -43,7 +44,7 @@ int launch_gemv(const void *packed, const void *lut, const uint16_t *x, const fl
 int launch_gemm(const void *packed, const void *lut, const uint16_t *x, const float *s, uint16_t *y,
                 int M, int N, int K, int bits, void *workspace, const GemmPlan &plan, void *stream);
 const char *hip_error_name(int err);
-int launch_smooth(const uint16_t *x, const float *s, void *xs, int M, int K, void *stream);
+int launch_smooth(const uint16_t *x, const float *s, void *xs, int M, int Mpad, int K, int layout, void *stream);
 int launch_reduce(const float *partial, uint16_t *y, int splits, long long total, void *stream);
 
 }  // namespace lcd

@@ -140,22 +140,45 @@ __global__ void __launch_bounds__(256) build_lut_kernel(const uint16_t *__restri
 }
 
 // ---- activation smoothing: xs[m][k] = fp16( x[m][k] / s[k] )  (paper Sec. 3.4) -------------
+// One thread per group of 8 consecutive k.  Output order:
+//   LAYOUT 0: [M][K], inside each group of 8 the slot order 0,4,1,5,2,6,3,7 that the register
+//             dequantiser produces (batched decode path);
+//   LAYOUT 1: MFMA-operand order for the prefill path:
+//             [chunk k/256][token tile m/16][step g=(k%64)/8][m%16][q=(k%256)/64][8 slots], tokens
+//             padded with zeros up to Mpad (a multiple of 128).
+template <int LAYOUT>
 __global__ void __launch_bounds__(256) smooth_kernel(const uint16_t *__restrict__ x, const float *__restrict__ s,
-                                                     _Float16 *__restrict__ xs, int K, long long total)
+                                                     _Float16 *__restrict__ xs, int M, int Mpad, int K)
 {
-    long long e = ((long long)blockIdx.x * blockDim.x + threadIdx.x) * 8;
-    if (e >= total) return;  // total = M*K, K % 256 == 0 so groups of 8 never straddle rows
-    const int k = (int)(e % K);
-    const uint4v xv = *reinterpret_cast<const uint4v *>(x + e);
-    const float4v s0 = *reinterpret_cast<const float4v *>(s + k);
-    const float4v s1 = *reinterpret_cast<const float4v *>(s + k + 4);
+    const long long grp = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const int kg = K / 8;
+    const long long total = (long long)(LAYOUT == 0 ? M : Mpad) * kg;
+    if (grp >= total) return;
+    const int m = (int)(grp / kg);
+    const int k = (int)(grp % kg) * 8;
     half8 o;
+    if (m < M) {
+        const uint4v xv = *reinterpret_cast<const uint4v *>(x + (size_t)m * K + k);
+        const float4v s0 = *reinterpret_cast<const float4v *>(s + k);
+        const float4v s1 = *reinterpret_cast<const float4v *>(s + k + 4);
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const uint16_t xb = (uint16_t)(xv[j >> 1] >> (16 * (j & 1)));
-        o[j] = smooth_one(xb, j < 4 ? s0[j] : s1[j - 4]);
+        for (int e = 0; e < 8; ++e) {
+            const uint16_t xb = (uint16_t)(xv[e >> 1] >> (16 * (e & 1)));
+            const int slot = e < 4 ? 2 * e : 2 * (e - 4) + 1;
+            o[slot] = smooth_one(xb, e < 4 ? s0[e] : s1[e - 4]);
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = (_Float16)0.0f;
     }
-    *reinterpret_cast<half8 *>(xs + e) = o;
+    size_t dst;
+    if (LAYOUT == 0) {
+        dst = (size_t)m * K + k;
+    } else {
+        const int c = k >> 8, q = (k >> 6) & 3, g = (k >> 3) & 7;
+        dst = ((((size_t)c * (Mpad >> 4) + (m >> 4)) * 8 + g) * 16 + (m & 15)) * 32 + q * 8;
+    }
+    *reinterpret_cast<half8 *>(xs + dst) = o;
 }
 
 // ---- split-K reduction: y = fp16( sum_s partial[s] ), fixed order --------------------------
@@ -169,12 +192,12 @@ __global__ void __launch_bounds__(256) reduce_kernel(const float *__restrict__ p
     y[e] = __builtin_bit_cast(uint16_t, (_Float16)acc);
 }
 
-int launch_smooth(const uint16_t *x, const float *s, void *xs, int M, int K, void *stream)
+int launch_smooth(const uint16_t *x, const float *s, void *xs, int M, int Mpad, int K, int layout, void *stream)
 {
-    const long long total = (long long)M * K;
-    const long long threads = total / 8;
-    hipLaunchKernelGGL(smooth_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
-                       x, s, (_Float16 *)xs, K, total);
+    const long long threads = (long long)(layout == 0 ? M : Mpad) * (K / 8);
+    const dim3 grid((unsigned)((threads + 255) / 256)), block(256);
+    if (layout == 0) hipLaunchKernelGGL(smooth_kernel<0>, grid, block, 0, (hipStream_t)stream, x, s, (_Float16 *)xs, M, Mpad, K);
+    else hipLaunchKernelGGL(smooth_kernel<1>, grid, block, 0, (hipStream_t)stream, x, s, (_Float16 *)xs, M, Mpad, K);
     return (int)hipGetLastError();
 }
 

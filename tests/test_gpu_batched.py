@@ -1,0 +1,97 @@
+"""GPU: batched decode (2 <= M <= 16) and prefill (lcd_lut_gemm) against the fp64 CPU oracle."""
+import numpy as np
+import pytest
+
+import oracle
+import synth
+import paper_2506_12038_amd as lcd
+from gpu_common import TOL, check_layer, run_hip, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("bits", [2, 3])
+@pytest.mark.parametrize("M", [2, 3, 8, 16])
+@pytest.mark.parametrize("shape", [(16, 256), (48, 768), (80, 2304), (64, 11008), (32, 28672)])
+def test_gemv_batched_small(bits, M, shape):
+    N, K = shape
+    layer = synth.make_layer(2, 0, N, K, bits, M, seed_offset=N + K + M)
+    check_layer(layer, bits, "gemv")
+
+
+@pytest.mark.parametrize("bits", [2, 3])
+@pytest.mark.parametrize("M", [1, 5, 64, 130, 257])
+@pytest.mark.parametrize("shape", [(16, 256), (48, 768), (272, 1024), (1040, 512)])
+def test_gemm_small(bits, M, shape):
+    N, K = shape
+    layer = synth.make_layer(3, 0, N, K, bits, M, seed_offset=N + K + M)
+    check_layer(layer, bits, "gemm")
+
+
+@pytest.mark.parametrize("bits", [2, 3])
+@pytest.mark.parametrize("entry", ["gemv", "gemm"])
+def test_batched_one_hot_rows_are_exact(bits, entry):
+    # token m has x = e_{k_m}, s = 1: y[m][n] = C[n][idx[n][k_m]] exactly
+    import torch
+    N, K, M = 32, 512, 16
+    layer = synth.make_layer(0, 0, N, K, bits, 1, seed_offset=9)
+    packed = lcd.lcd_pack_indices(to_dev(layer["idx"]), bits)
+    lut = lcd.lcd_build_lut(to_dev(layer["codebook"]), bits)
+    s = torch.ones(K, dtype=torch.float32, device="cuda")
+    fn = lcd.lcd_lut_gemv if entry == "gemv" else lcd.lcd_lut_gemm
+    for base in range(0, 256, 16):
+        ks = [base + m for m in range(M)]
+        x = torch.zeros((M, K), dtype=torch.float16, device="cuda")
+        for m, k in enumerate(ks):
+            x[m, k] = 1.0
+        y = fn(packed, lut, x, s, N, bits).cpu().numpy()
+        for m, k in enumerate(ks):
+            assert np.array_equal(y[m], layer["codebook"][np.arange(N), layer["idx"][:, k]]), (m, k)
+
+
+def _sampled_check(cfg, mid, spec, bits, M, entry, rows=192, toks=24):
+    """Full-size matrix on the GPU; the oracle evaluates a seeded sample of rows and tokens."""
+    layer = synth.make_layer(cfg, mid, spec.N, spec.K, bits, M)
+    y = run_hip(layer, bits, entry)
+    rng = np.random.default_rng(99 + mid)
+    rs = np.sort(rng.choice(spec.N, size=min(rows, spec.N), replace=False))
+    rs[-1] = spec.N - 1; rs[0] = 0
+    ms = np.sort(rng.choice(M, size=min(toks, M), replace=False))
+    Y = oracle.lut_matmul(layer["codebook"][rs], layer["idx"][rs], layer["x"][ms], layer["s"], bits)
+    Yfull_rows = y[np.ix_(ms, rs)]
+    # rms over the sampled rows stands in for the row rms (rows are i.i.d. by construction)
+    err = oracle.parity_errors(Yfull_rows, Y)
+    assert np.all(np.isfinite(y.astype(np.float32)))
+    assert err["max_rel_floored"] <= TOL, (spec, err)
+    return err
+
+
+def test_config2_batched_decode_full_size():
+    config = synth.get_config(2)
+    seen = set()
+    for mid, spec in config.matrices():
+        if (spec.N, spec.K) in seen:
+            continue
+        seen.add((spec.N, spec.K))
+        _sampled_check(2, mid, spec, config.bits, 16, "gemv")
+
+
+def test_config3_prefill_full_size():
+    config = synth.get_config(3)
+    seen = set()
+    for mid, spec in config.matrices():
+        if (spec.N, spec.K) in seen:
+            continue
+        seen.add((spec.N, spec.K))
+        _sampled_check(3, mid, spec, config.bits, 2048, "gemm", rows=96, toks=16)
+
+
+@pytest.mark.parametrize("M", [1, 8])
+def test_config4_70b_mlp_full_size(M):
+    config = synth.get_config(4)
+    seen = set()
+    for mid, spec in config.matrices():
+        if (spec.N, spec.K) in seen:
+            continue
+        seen.add((spec.N, spec.K))
+        _sampled_check(4, mid, spec, config.bits, M, "gemv", rows=128, toks=8)
