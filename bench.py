@@ -1,0 +1,229 @@
+#!/usr/bin/env python3
+"""Benchmark of the LCD table-lookup linear layer on one MI355X.
+
+Workload (N=1): the LLaMA-7B-shaped decoder linear set at M=1 with 3-bit indices
+(q/k/v/o 4096x4096, gate/up 11008x4096, down 4096x11008), synthetic seeded inputs.  A step is
+one pass of the decode hot path over the whole set: activation smoothing, table lookup +
+accumulation and the row reduction for all seven matrices (index packing and table build are
+offline, once per layer, and happen before the timed region).  The metric is effective GB/s on
+the packed-index bytes (N*K*bits/8 summed over the set) with inputs resident in HBM.
+
+Every timed step streams a different replica of the packed matrices (>= 600 MB in rotation), so
+the 256 MB last-level cache cannot serve them; steps are replayed from a HIP graph so that the
+host's launch cost is not what is measured.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from pathlib import Path
+
+ROOT = Path(__file__).resolve().parent
+if str(ROOT) not in sys.path:
+    sys.path.insert(0, str(ROOT))
+
+HBM_PEAK_GBS = 8000.0
+MFMA_F16_PEAK_TFLOPS = 2500.0
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=1, help="benchmark config index (1 = the metric's workload)")
+    ap.add_argument("--m", type=int, default=None, help="token count (default: the config's first M)")
+    ap.add_argument("--replicas", type=int, default=0, help="packed-matrix replicas in rotation (0 = enough for 600 MB)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra", action="store_true", help="skip the secondary measurements (other configs)")
+    ap.add_argument("--eager", action="store_true", help="launch every step from Python instead of replaying a HIP graph")
+    return ap.parse_args()
+
+
+class LayerSet:
+    """Device-resident inputs of one config: per matrix R replicas of (packed, lut), x, s, y, workspace."""
+
+    def __init__(self, cfg_index, M, replicas, keep_host=False):
+        import numpy as np
+        import torch
+        import synth
+        import paper_2506_12038_amd as lcd
+
+        self.cfg = synth.get_config(cfg_index)
+        self.bits = self.cfg.bits
+        self.M = M
+        self.entry = lcd.lcd_lut_gemv if M <= 16 else lcd.lcd_lut_gemm
+        self.mats = []
+        self.host = []
+        cache = {}
+        for mid, spec in self.cfg.matrices():
+            layer = synth.make_layer(cfg_index, mid, spec.N, spec.K, self.bits, M)
+            dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+            packed0 = lcd.lcd_pack_indices(dev(layer["idx"]), self.bits)
+            lut0 = lcd.lcd_build_lut(dev(layer["codebook"]), self.bits)
+            packed = [packed0] + [packed0.clone() for _ in range(replicas - 1)]
+            luts = [lut0] + [lut0.clone() for _ in range(replicas - 1)]
+            ws = torch.empty(lcd.lcd_workspace_bytes(M, spec.N, spec.K, self.bits), dtype=torch.uint8, device="cuda")
+            self.mats.append(dict(spec=spec, packed=packed, lut=luts, x=dev(layer["x"]), s=dev(layer["s"]),
+                                  y=torch.empty((M, spec.N), dtype=torch.float16, device="cuda"), ws=ws))
+            if keep_host:
+                self.host.append(layer)
+            del layer
+        torch.cuda.synchronize()
+        self.index_bytes = sum(m["spec"].N * m["spec"].K * self.bits // 8 for m in self.mats)
+        self.flops = sum(2 * M * m["spec"].N * m["spec"].K for m in self.mats)
+        self.total_bytes = self.index_bytes + sum(
+            m["spec"].N * (1 << self.bits) * 2 + M * m["spec"].K * 2 + m["spec"].K * 4 + M * m["spec"].N * 2 for m in self.mats)
+
+    def step(self, replica):
+        for m in self.mats:
+            self.entry(m["packed"][replica], m["lut"][replica], m["x"], m["s"], m["spec"].N, self.bits,
+                       y=m["y"], workspace=m["ws"])
+
+
+def time_steps(ls, replicas, steps, warmup, eager):
+    """Returns (wall ms per step, event ms per step).  Exactly `steps` timed steps."""
+    import torch
+
+    stream = torch.cuda.Stream()
+    graphs = {}
+
+    def run(n_steps, first):
+        """Enqueue n_steps on `stream`, rotating replicas starting at `first`."""
+        if eager:
+            with torch.cuda.stream(stream):
+                for i in range(n_steps):
+                    ls.step((first + i) % replicas)
+            return
+        done = 0
+        while done < n_steps:
+            chunk = min(replicas, n_steps - done)
+            key = chunk
+            if key not in graphs:
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=stream):
+                    for r in range(chunk):
+                        ls.step(r)
+                graphs[key] = g
+            with torch.cuda.stream(stream):
+                graphs[key].replay()
+            done += chunk
+
+    with torch.cuda.stream(stream):
+        ls.step(0)                     # first call outside capture (lazy module load)
+    torch.cuda.synchronize()
+    if not eager:                      # build every graph the timed loop needs before timing
+        run(replicas, 0)
+        if steps % replicas:
+            run(steps % replicas, 0)
+        if warmup % replicas and warmup > 0:
+            run(warmup % replicas, 0)
+    torch.cuda.synchronize()
+    run(warmup, 0)
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    with torch.cuda.stream(stream):
+        e0.record(stream)
+    run(steps, 0)
+    with torch.cuda.stream(stream):
+        e1.record(stream)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    return (t1 - t0) * 1e3 / steps, e0.elapsed_time(e1) / steps
+
+
+def cpu_baseline(cfg_index, M):
+    """The oracle as it stands, on this machine's host cores, on a bounded sample of the workload."""
+    import numpy as np
+    import oracle
+    import synth
+
+    cfg = synth.get_config(cfg_index)
+    # sample: every distinct matrix shape of the set once, rows capped so the run stays ~10-30 s
+    budget_weights = 6.0e8 / max(M, 1)
+    seen, total_bytes, total_s, desc = set(), 0, 0.0, []
+    for mid, spec in cfg.matrices():
+        if (spec.N, spec.K) in seen:
+            continue
+        seen.add((spec.N, spec.K))
+        rows = int(min(spec.N, max(16, budget_weights / 3 // spec.K // 16 * 16)))
+        layer = synth.make_layer(cfg_index, mid, rows, spec.K, cfg.bits, M)
+        best = None
+        for _ in range(2):
+            t0 = time.perf_counter()
+            oracle.lut_matmul(layer["codebook"], layer["idx"], layer["x"], layer["s"], cfg.bits)
+            dt = time.perf_counter() - t0
+            best = dt if best is None else min(best, dt)
+        total_bytes += rows * spec.K * cfg.bits // 8
+        total_s += best
+        desc.append(f"{rows}x{spec.K}")
+    return {
+        "value": total_bytes / total_s / 1e9, "unit": "GB/s", "cores": oracle.num_threads(), "kind": "oracle",
+        "sample": f"config {cfg_index} at M={M}: first {', '.join(desc)} rows x K of each distinct matrix shape, "
+                  f"fp64 oracle, best of 2, {total_s:.2f} s",
+    }
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import synth
+    import paper_2506_12038_amd as lcd
+
+    lcd.load_library()  # fail loudly if the HIP library is missing
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    cfg = synth.get_config(args.config)
+    M = args.m if args.m is not None else cfg.Ms[0]
+    replicas = args.replicas or max(2, -(-600_000_000 // cfg.index_bytes()))
+    ls = LayerSet(args.config, M, replicas)
+    wall_ms, event_ms = time_steps(ls, replicas, args.steps, args.warmup, args.eager)
+
+    decode = M <= 16
+    n_launch = len(ls.mats)
+    if decode:
+        metric, unit = "lut_gemv_effective_bandwidth_packed_index_bytes", "GB/s"
+        value = ls.index_bytes / (wall_ms * 1e-3) / 1e9
+        roofline = {
+            "bound": "hbm", "achieved": ls.index_bytes / (event_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": ls.index_bytes / (event_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None,
+            "kernel": "gemv_bucket_kernel" if M == 1 else "gemv_dense_kernel",
+            "launches_per_step": n_launch, "algorithmic_bytes_per_step": ls.index_bytes,
+            "avg_launch_us": event_ms * 1e3 / n_launch,
+        }
+    else:
+        metric, unit = "lut_gemm_throughput", "TFLOP/s"
+        value = ls.flops / (wall_ms * 1e-3) / 1e12
+        roofline = {
+            "bound": "mfma", "achieved": ls.flops / (event_ms * 1e-3) / 1e12, "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": ls.flops / (event_ms * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS, "traffic": None,
+            "kernel": "gemm_kernel", "launches_per_step": n_launch, "algorithmic_flops_per_step": ls.flops,
+            "avg_launch_us": event_ms * 1e3 / n_launch,
+        }
+    out = {
+        "metric": metric, "value": value, "unit": unit, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": wall_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16 operands, f32 accumulate", "data": "synthetic",
+        "config": {"workload": f"config {args.config}: {cfg.label}", "M": M, "bits": cfg.bits,
+                   "matrices": [f"{m['spec'].N}x{m['spec'].K}" for m in ls.mats],
+                   "index_bytes_per_step": ls.index_bytes, "replicas_in_rotation": replicas,
+                   "launch": "eager" if args.eager else "hip graph replay"},
+        "roofline": roofline,
+    }
+    del ls
+    torch.cuda.empty_cache()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.config, M)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -28,6 +28,14 @@ namespace lcd {
 
 constexpr int kMaxWaves = 8;
 
+// Buffer resources give branch-free predication: a lane whose offset is past the end of the
+// buffer reads zeros and touches no memory.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, bytes, 0x00020000);
+}
+constexpr uint32_t kOob = 0xFFFFFFF0u;
+
 template <int BITS, int CH>
 struct TileRegs {
     uint4v lo[CH];   // 2-bit plane: the lane's 64 low index pairs per chunk
@@ -35,33 +43,34 @@ struct TileRegs {
     float4v cf;      // per-bucket multipliers of this lane's 4 rows (lanes j < NC), else 0
 };
 
+// Issue the loads of row tile t (nothing is read if t >= nt or a chunk is not this wave's).
 template <int BITS, int CH>
-__device__ __forceinline__ void load_tile(TileRegs<BITS, CH> &r, const uint8_t *__restrict__ packed,
-                                          const float *__restrict__ lutA, int t, int kc, int c_begin, int nch, int lane)
+__device__ __forceinline__ void load_tile(TileRegs<BITS, CH> &r, __amdgpu_buffer_rsrc_t packed, __amdgpu_buffer_rsrc_t lutA,
+                                          int t, int nt, uint32_t tile_stride, const uint32_t (&choff)[CH], int lane)
 {
-    constexpr size_t TB = BITS == 2 ? 1024 : 1536;
     constexpr int NC = BITS == 2 ? 4 : 8;
-    const uint8_t *base = packed + ((size_t)t * kc + c_begin) * TB;
+    const bool tv = t < nt;
+    const uint32_t toff = (uint32_t)t * tile_stride;
 #pragma unroll
     for (int ch = 0; ch < CH; ++ch) {
-        if (ch < nch) {
-            r.lo[ch] = __builtin_nontemporal_load(reinterpret_cast<const uint4v *>(base + ch * TB + 16 * lane));
-            if (BITS == 3) r.hi[ch] = __builtin_nontemporal_load(reinterpret_cast<const uint2v *>(base + ch * TB + 1024 + 8 * lane));
-        }
+        const bool v = tv && choff[ch] != kOob;
+        const uint32_t o = toff + choff[ch];
+        r.lo[ch] = __builtin_amdgcn_raw_buffer_load_b128(packed, v ? o + 16 * lane : kOob, 0, 0);
+        if (BITS == 3) r.hi[ch] = __builtin_amdgcn_raw_buffer_load_b64(packed, v ? o + 1024 + 8 * lane : kOob, 0, 0);
     }
     const int j = lane & 15, bq = lane >> 4;
-    float4v cf = {0.f, 0.f, 0.f, 0.f};
-    if (j < NC) cf = *reinterpret_cast<const float4v *>(lutA + ((size_t)(4 * t + bq) * NC + j) * 4);
-    r.cf = cf;
+    const uint32_t lo = ((uint32_t)(4 * t + bq) * NC + j) * 16;
+    r.cf = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(lutA, (tv && j < NC) ? lo : kOob, 0, 0));
 }
 
 template <int BITS, int CH>
 __global__ void __launch_bounds__(kMaxWaves * 64, 1)
-gemv_bucket_kernel(const uint8_t *__restrict__ packed, const float *__restrict__ lutA, const uint16_t *__restrict__ x,
+gemv_bucket_kernel(const uint8_t *__restrict__ packed_, const float *__restrict__ lutA_, const uint16_t *__restrict__ x,
                    const float *__restrict__ s, uint16_t *__restrict__ y, float *__restrict__ partial,
                    int N, int K, int chunks_per_split, int splits)
 {
     constexpr int NC = BITS == 2 ? 4 : 8;
+    constexpr uint32_t TB = BITS == 2 ? 1024 : 1536;
     __shared__ __attribute__((aligned(16))) _Float16 xs_lds[kMaxWaves * CH * 256];
     __shared__ __attribute__((aligned(16))) float part[2][kMaxWaves][16];
 
@@ -72,17 +81,33 @@ gemv_bucket_kernel(const uint8_t *__restrict__ packed, const float *__restrict__
     const int split_c0 = split * chunks_per_split;
     const int split_c1 = min(kc, split_c0 + chunks_per_split);
     const int c_begin = split_c0 + wave * CH;
-    const int nch = max(0, min(CH, split_c1 - c_begin));
+    const __amdgpu_buffer_rsrc_t packed = make_rsrc(packed_, (uint32_t)nt * (uint32_t)kc * TB);
+    const __amdgpu_buffer_rsrc_t lutA = make_rsrc(lutA_, (uint32_t)N * NC * 4);
+    const uint32_t tile_stride = (uint32_t)kc * TB;
+    uint32_t choff[CH];
+#pragma unroll
+    for (int ch = 0; ch < CH; ++ch) choff[ch] = (c_begin + ch < split_c1) ? (uint32_t)(c_begin + ch) * TB : kOob;
 
-    TileRegs<BITS, CH> r0, r1;
+    // ---- prologue: smoothed activations of this workgroup's K range -> LDS -> registers.
+    // Its loads go first (they head the longest dependency chain), then the first tiles'.
+    const int stride = gridDim.x;
     int t = blockIdx.x;
-    if (t < nt) load_tile<BITS, CH>(r0, packed, lutA, t, kc, c_begin, nch, lane);
-
-    // ---- prologue: smoothed activations of this workgroup's K range -> LDS -> registers ----
+    TileRegs<BITS, CH> r0, r1, r2;
     {
-        const int k0 = split_c0 * kTileCols, klen = (split_c1 - split_c0) * kTileCols;
-        for (int e = threadIdx.x; e < klen; e += blockDim.x) xs_lds[e] = smooth_one(x[k0 + e], s[k0 + e]);
+        const int k0 = split_c0 * kTileCols, groups = (split_c1 - split_c0) * (kTileCols / 8);
+        for (int g = threadIdx.x; g < groups; g += blockDim.x) {
+            const uint4v xv = *reinterpret_cast<const uint4v *>(x + k0 + 8 * g);
+            const float4v s0 = *reinterpret_cast<const float4v *>(s + k0 + 8 * g);
+            const float4v s1 = *reinterpret_cast<const float4v *>(s + k0 + 8 * g + 4);
+            half8 o;
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                o[e] = smooth_one((uint16_t)(xv[e >> 1] >> (16 * (e & 1))), e < 4 ? s0[e] : s1[e - 4]);
+            *reinterpret_cast<half8 *>(&xs_lds[8 * g]) = o;
+        }
     }
+    load_tile<BITS, CH>(r0, packed, lutA, t, nt, tile_stride, choff, lane);
+    load_tile<BITS, CH>(r1, packed, lutA, t + stride, nt, tile_stride, choff, lane);
     __syncthreads();
     uint4v A[CH][8];
     uint4v nA[BITS == 3 ? CH : 1][8];
@@ -91,7 +116,7 @@ gemv_bucket_kernel(const uint8_t *__restrict__ packed, const float *__restrict__
 #pragma unroll
         for (int g = 0; g < 8; ++g) {
             uint4v v = {0u, 0u, 0u, 0u};
-            if (ch < nch) v = *reinterpret_cast<const uint4v *>(&xs_lds[(wave * CH + ch) * 256 + 64 * q + 8 * g]);
+            if (choff[ch] != kOob) v = *reinterpret_cast<const uint4v *>(&xs_lds[(wave * CH + ch) * 256 + 64 * q + 8 * g]);
             A[ch][g] = v;
             if (BITS == 3) nA[ch][g] = v ^ 0x80008000u;
         }
@@ -109,27 +134,28 @@ gemv_bucket_kernel(const uint8_t *__restrict__ packed, const float *__restrict__
         for (int u = 0; u < 4; ++u) acc[u] = float4v{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ch = 0; ch < CH; ++ch) {
-            if (ch < nch) {
 #pragma unroll
-                for (int d = 0; d < 4; ++d) {
-                    const int idxreg = (int)r.lo[ch][d];
-                    // half a = 0 uses index bits [15:0], a = 1 bits [31:16]
+            for (int d = 0; d < 4; ++d) {
+                const int idxreg = (int)r.lo[ch][d];
+                // half a = 0 uses index bits [15:0], a = 1 bits [31:16]
+                if (BITS == 2) {
+                    acc[(2 * d) & 3] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(A[ch][2 * d]), B1, acc[(2 * d) & 3], idxreg, 0, 0);
+                    acc[(2 * d + 1) & 3] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(A[ch][2 * d + 1]), B1, acc[(2 * d + 1) & 3], idxreg, 0, 1);
+                } else {
                     acc[0] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(A[ch][2 * d]), B1, acc[0], idxreg, 0, 0);
                     acc[1] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(A[ch][2 * d + 1]), B1, acc[1], idxreg, 0, 1);
-                    if (BITS == 3) {
 #pragma unroll
-                        for (int a = 0; a < 2; ++a) {
-                            const uint32_t hp = r.hi[ch][a];
-                            uint4v f;
+                    for (int a = 0; a < 2; ++a) {
+                        const uint32_t hp = r.hi[ch][a];
+                        uint4v f;
 #pragma unroll
-                            for (int v = 0; v < 4; ++v) {
-                                // pair v of this operand: high bits sit 16 apart; move them to bits 15 / 31
-                                const int sh = 15 - (8 * (v >> 1) + 2 * d + (v & 1));
-                                f[v] = bfi(hp << sh, nA[ch][2 * d + a][v], A[ch][2 * d + a][v]);
-                            }
-                            if (a == 0) acc[2] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(f), B2, acc[2], idxreg, 0, 0);
-                            else        acc[3] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(f), B2, acc[3], idxreg, 0, 1);
+                        for (int v = 0; v < 4; ++v) {
+                            // pair v of this operand: high bits sit 16 apart; move them to bits 15 / 31
+                            const int sh = 15 - (8 * (v >> 1) + 2 * d + (v & 1));
+                            f[v] = bfi(hp << sh, nA[ch][2 * d + a][v], A[ch][2 * d + a][v]);
                         }
+                        if (a == 0) acc[2] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(f), B2, acc[2], idxreg, 0, 0);
+                        else        acc[3] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(f), B2, acc[3], idxreg, 0, 1);
                     }
                 }
             }
@@ -155,16 +181,32 @@ gemv_bucket_kernel(const uint8_t *__restrict__ packed, const float *__restrict__
         }
     };
 
-    const int stride = gridDim.x;
-    while (t < nt) {
-        const int t1 = t + stride;
-        if (t1 < nt) load_tile<BITS, CH>(r1, packed, lutA, t1, kc, c_begin, nch, lane);
+    // three register sets rotate: two tiles are always in flight behind the one being consumed
+    while (true) {
+        load_tile<BITS, CH>(r2, packed, lutA, t + 2 * stride, nt, tile_stride, choff, lane);
         process(r0, t, 0);
-        if (t1 >= nt) break;
-        const int t2 = t1 + stride;
-        if (t2 < nt) load_tile<BITS, CH>(r0, packed, lutA, t2, kc, c_begin, nch, lane);
-        process(r1, t1, 1);
-        t = t2;
+        t += stride;
+        if (t >= nt) break;
+        load_tile<BITS, CH>(r0, packed, lutA, t + 2 * stride, nt, tile_stride, choff, lane);
+        process(r1, t, 1);
+        t += stride;
+        if (t >= nt) break;
+        load_tile<BITS, CH>(r1, packed, lutA, t + 2 * stride, nt, tile_stride, choff, lane);
+        process(r2, t, 0);
+        t += stride;
+        if (t >= nt) break;
+        load_tile<BITS, CH>(r2, packed, lutA, t + 2 * stride, nt, tile_stride, choff, lane);
+        process(r0, t, 1);
+        t += stride;
+        if (t >= nt) break;
+        load_tile<BITS, CH>(r0, packed, lutA, t + 2 * stride, nt, tile_stride, choff, lane);
+        process(r1, t, 0);
+        t += stride;
+        if (t >= nt) break;
+        load_tile<BITS, CH>(r1, packed, lutA, t + 2 * stride, nt, tile_stride, choff, lane);
+        process(r2, t, 1);
+        t += stride;
+        if (t >= nt) break;
     }
 }
 
