@@ -39,6 +39,7 @@ def parse_args():
     ap.add_argument("--replicas", type=int, default=0, help="packed-matrix replicas in rotation (0 = enough for 600 MB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the secondary measurements (other configs)")
+    ap.add_argument("--per-layer", action="store_true", help="one lcd_lut_gemv call per matrix instead of one grouped call per step")
     ap.add_argument("--eager", action="store_true", help="launch every step from Python instead of replaying a HIP graph")
     return ap.parse_args()
 
@@ -46,13 +47,14 @@ def parse_args():
 class LayerSet:
     """Device-resident inputs of one config: per matrix R replicas of (packed, lut), x, s, y, workspace."""
 
-    def __init__(self, cfg_index, M, replicas, keep_host=False):
+    def __init__(self, cfg_index, M, replicas, keep_host=False, per_layer=False):
         import numpy as np
         import torch
         import synth
         import paper_2506_12038_amd as lcd
 
         self.cfg = synth.get_config(cfg_index)
+        self.per_layer = per_layer
         self.bits = self.cfg.bits
         self.M = M
         self.entry = lcd.lcd_lut_gemv if M <= 16 else lcd.lcd_lut_gemm
@@ -78,7 +80,15 @@ class LayerSet:
         self.total_bytes = self.index_bytes + sum(
             m["spec"].N * (1 << self.bits) * 2 + M * m["spec"].K * 2 + m["spec"].K * 4 + M * m["spec"].N * 2 for m in self.mats)
 
+        self.groups = None
+        if M <= 16:
+            self.groups = [lcd.GemvGroup([(m["packed"][r], m["lut"][r], m["x"], m["s"], m["y"], m["spec"].N) for m in self.mats],
+                                         self.bits) for r in range(replicas)]
+
     def step(self, replica):
+        if self.groups is not None and not self.per_layer:
+            self.groups[replica]()
+            return
         for m in self.mats:
             self.entry(m["packed"][replica], m["lut"][replica], m["x"], m["s"], m["spec"].N, self.bits,
                        y=m["y"], workspace=m["ws"])
@@ -184,11 +194,11 @@ def main():
     cfg = synth.get_config(args.config)
     M = args.m if args.m is not None else cfg.Ms[0]
     replicas = args.replicas or max(2, -(-600_000_000 // cfg.index_bytes()))
-    ls = LayerSet(args.config, M, replicas)
+    ls = LayerSet(args.config, M, replicas, per_layer=args.per_layer)
     wall_ms, event_ms = time_steps(ls, replicas, args.steps, args.warmup, args.eager)
 
     decode = M <= 16
-    n_launch = len(ls.mats)
+    n_launch = 1 if (decode_group := (M == 1 and not args.per_layer)) else len(ls.mats)
     if decode:
         metric, unit = "lut_gemv_effective_bandwidth_packed_index_bytes", "GB/s"
         value = ls.index_bytes / (wall_ms * 1e-3) / 1e9
@@ -215,7 +225,7 @@ def main():
         "config": {"workload": f"config {args.config}: {cfg.label}", "M": M, "bits": cfg.bits,
                    "matrices": [f"{m['spec'].N}x{m['spec'].K}" for m in ls.mats],
                    "index_bytes_per_step": ls.index_bytes, "replicas_in_rotation": replicas,
-                   "launch": "eager" if args.eager else "hip graph replay"},
+                   "launch": ("eager" if args.eager else "hip graph replay") + (", one grouped launch per step" if n_launch == 1 else ", one call per matrix")},
         "roofline": roofline,
     }
     del ls

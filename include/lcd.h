@@ -127,6 +127,29 @@ lcd_status lcd_lut_gemm(const void *packed, const void *lut, const uint16_t *x, 
                         uint16_t *y, int M, int N, int K, int bits,
                         void *workspace, size_t workspace_bytes, void *stream);
 
+/* ---- grouped decode: several independent layers in ONE launch ---------------------------- *
+ *
+ * A decoder block applies several table-lookup linear layers per token (Sec. 5 evaluates whole
+ * models); each is only a few MB of packed indices, so launching them one by one leaves the
+ * GPU mostly idle.  lcd_lut_gemv_grouped runs `count` (1..16) independent products
+ *     y_i = (x_i / s_i) . What_i^T            (same M and bits for all, any N_i, K_i)
+ * with every argument of problems[i] as in lcd_lut_gemv.  `problems` is a HOST array, read
+ * during the call only.  The layers' outputs must not overlap.  Workspace: at least
+ * lcd_workspace_bytes_grouped(problems, count, M, bits) bytes (DEVICE).
+ */
+typedef struct lcd_gemv_problem {
+    const void *packed;   /* DEVICE */
+    const void *lut;      /* DEVICE */
+    const uint16_t *x;    /* DEVICE fp16 [M][K] */
+    const float *s;       /* DEVICE fp32 [K]    */
+    uint16_t *y;          /* DEVICE fp16 [M][N] */
+    int N, K;
+} lcd_gemv_problem;
+
+size_t lcd_workspace_bytes_grouped(const lcd_gemv_problem *problems /*HOST*/, int count, int M, int bits);
+lcd_status lcd_lut_gemv_grouped(const lcd_gemv_problem *problems /*HOST*/, int count, int M, int bits,
+                                void *workspace, size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

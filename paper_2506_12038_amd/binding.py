@@ -20,7 +20,13 @@ EXPORTS = (
     "lcd_packed_bytes", "lcd_lut_bytes", "lcd_workspace_bytes",
     "lcd_pack_indices", "lcd_unpack_indices", "lcd_pack_indices_host", "lcd_unpack_indices_host",
     "lcd_build_lut", "lcd_lut_gemv", "lcd_lut_gemm",
+    "lcd_workspace_bytes_grouped", "lcd_lut_gemv_grouped",
 )
+
+
+class _Problem(ctypes.Structure):
+    _fields_ = [("packed", ctypes.c_void_p), ("lut", ctypes.c_void_p), ("x", ctypes.c_void_p), ("s", ctypes.c_void_p),
+                ("y", ctypes.c_void_p), ("N", ctypes.c_int), ("K", ctypes.c_int)]
 
 
 class LcdError(RuntimeError):
@@ -66,6 +72,10 @@ def load_library():
         fn = getattr(lib, name)
         fn.restype = ci
         fn.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, vp, sz, vp]
+    lib.lcd_workspace_bytes_grouped.restype = sz
+    lib.lcd_workspace_bytes_grouped.argtypes = [ctypes.POINTER(_Problem), ci, ci, ci]
+    lib.lcd_lut_gemv_grouped.restype = ci
+    lib.lcd_lut_gemv_grouped.argtypes = [ctypes.POINTER(_Problem), ci, ci, ci, vp, sz, vp]
     _lib = lib
     return lib
 
@@ -194,3 +204,47 @@ def lcd_lut_gemv(packed, lut, x, s, N: int, bits: int, y=None, workspace=None, s
 def lcd_lut_gemm(packed, lut, x, s, N: int, bits: int, y=None, workspace=None, stream=None):
     """Prefill path, x: CUDA float16 [M, K] -> y float16 [M, N]."""
     return _product("lcd_lut_gemm", packed, lut, x, s, N, bits, y, workspace, stream)
+
+
+class GemvGroup:
+    """Marshalled argument block of lcd_lut_gemv_grouped: build once per layer set, call many times.
+
+    problems: sequence of (packed, lut, x, s, y, N) with CUDA tensors as in lcd_lut_gemv.
+    """
+
+    def __init__(self, problems, bits: int, workspace=None):
+        import torch
+        lib = load_library()
+        self.bits = bits
+        self.count = len(problems)
+        self._keep = list(problems)
+        M = problems[0][2].shape[0]
+        self.M = M
+        arr = (_Problem * self.count)()
+        for i, (packed, lut, x, s, y, N) in enumerate(problems):
+            if x.shape[0] != M:
+                raise ValueError("all problems of a group share M")
+            K = x.shape[1]
+            arr[i] = _Problem(_dev(packed, torch.uint8, "packed").value, _dev(lut, torch.uint8, "lut").value,
+                              _dev(x, torch.float16, "x").value, _dev(s, torch.float32, "s").value,
+                              _dev(y, torch.float16, "y").value, N, K)
+        self._arr = arr
+        need = lib.lcd_workspace_bytes_grouped(arr, self.count, M, bits)
+        if need == 0:
+            raise ValueError("invalid group (shapes, M or bits)")
+        self.workspace = workspace if workspace is not None else torch.empty(need, dtype=torch.uint8, device=problems[0][2].device)
+
+    def __call__(self, stream=None):
+        import torch
+        _check(load_library().lcd_lut_gemv_grouped(self._arr, self.count, self.M, self.bits,
+                                                   _dev(self.workspace, torch.uint8, "workspace"), self.workspace.numel(),
+                                                   _stream(stream)))
+
+
+def lcd_workspace_bytes_grouped(problems, bits: int) -> int:
+    return GemvGroup(problems, bits).workspace.numel()
+
+
+def lcd_lut_gemv_grouped(problems, bits: int, workspace=None, stream=None):
+    """One launch for several layers: problems = [(packed, lut, x, s, y, N), ...]; writes every y."""
+    GemvGroup(problems, bits, workspace)(stream)

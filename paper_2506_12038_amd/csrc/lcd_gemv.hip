@@ -36,177 +36,280 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, ui
 }
 constexpr uint32_t kOob = 0xFFFFFFF0u;
 
-template <int BITS, int CH>
-struct TileRegs {
-    uint4v lo[CH];   // 2-bit plane: the lane's 64 low index pairs per chunk
-    uint2v hi[CH];   // 3-bit only: the lane's 64 high bits per chunk
-    float4v cf;      // per-bucket multipliers of this lane's 4 rows (lanes j < NC), else 0
+// ---- single-token bucket kernel: persistent workgroups over a group of layers ---------------
+//
+// The host gives every layer of the group a number of workgroups proportional to its packed
+// bytes; a workgroup owns a contiguous run of row tiles of ONE layer and walks it in "visits"
+// of up to kVisitTiles row tiles.  Per visit:
+//   prologue   smoothed activations of the layer (all K, first visit only) and the visit's
+//              per-bucket multipliers go to LDS; one barrier;
+//   segments   the 8 waves split K into segments of 16 chunks (2 chunks per wave).  For each
+//              segment a wave loads its activations LDS -> registers once, then streams the
+//              visit's row tiles: 2-3 KiB of packed indices per tile, 16-32 sparse MFMAs, and a
+//              few VALU ops that turn bucket sums into 16 partial outputs which the wave adds
+//              into its own LDS slot (no synchronisation: the slot is private to the wave);
+//   epilogue   one barrier; the workgroup adds the 8 waves' slots in a fixed order and stores y.
+// Loads of packed indices run kSets-1 steps ahead of the arithmetic, across segment and visit
+// boundaries, and start before the prologue.
+constexpr int kBW = 8;            // waves per workgroup
+constexpr int kBCH = 2;           // chunks per wave per segment (activations kept in registers)
+constexpr int kBSeg = kBW * kBCH; // chunks per segment (one pass of the workgroup over K)
+constexpr int kSets = 4;          // register sets in rotation (loads run kSets-1 steps ahead)
+constexpr int kVisitTiles = 32;   // row tiles per visit
+
+struct BucketProblem {
+    const uint8_t *packed;
+    const float *lutA;
+    const uint16_t *x;
+    const float *s;
+    uint16_t *y;
+    int nt, kc;
+    int tiles_base, tiles_extra;  // workgroup i of this layer owns tiles_base (+1 if i < tiles_extra) row tiles
+};
+struct BucketBatch {
+    BucketProblem p[kMaxGroup];
+    int wg_begin[kMaxGroup + 1];  // first workgroup of every layer
+    int count;
+    int kc_max;
+#ifdef LCD_TRACE
+    unsigned long long *trace;   // debug builds only: 8 timestamps per workgroup
+#endif
+};
+#ifdef LCD_TRACE
+#define LCD_STAMP(slot) do { if (threadIdx.x == 0 && batch.trace) batch.trace[blockIdx.x * 16 + (slot)] = __builtin_amdgcn_s_memrealtime(); } while (0)
+#else
+#define LCD_STAMP(slot) do { } while (0)
+#endif
+
+// Walks the (visit, segment, tile) sequence of one workgroup.  Everything is wave-uniform.
+// Each (visit, segment) run is padded to a multiple of kSets steps so that the register-set
+// rotation is static; padding steps load nothing and compute nothing.
+struct Cursor {
+    int v0, v1, range_end, sg, i, steps;
+    bool done;
 };
 
-// Issue the loads of row tile t (nothing is read if t >= nt or a chunk is not this wave's).
-template <int BITS, int CH>
-__device__ __forceinline__ void load_tile(TileRegs<BITS, CH> &r, __amdgpu_buffer_rsrc_t packed, __amdgpu_buffer_rsrc_t lutA,
-                                          int t, int nt, uint32_t tile_stride, const uint32_t (&choff)[CH], int lane)
+__device__ __forceinline__ int pad_sets(int n) { return (n + kSets - 1) / kSets * kSets; }
+
+__device__ __forceinline__ void cursor_begin(Cursor &c, int ta, int tb)
 {
-    constexpr int NC = BITS == 2 ? 4 : 8;
-    const bool tv = t < nt;
-    const uint32_t toff = (uint32_t)t * tile_stride;
-#pragma unroll
-    for (int ch = 0; ch < CH; ++ch) {
-        const bool v = tv && choff[ch] != kOob;
-        const uint32_t o = toff + choff[ch];
-        r.lo[ch] = __builtin_amdgcn_raw_buffer_load_b128(packed, v ? o + 16 * lane : kOob, 0, 0);
-        if (BITS == 3) r.hi[ch] = __builtin_amdgcn_raw_buffer_load_b64(packed, v ? o + 1024 + 8 * lane : kOob, 0, 0);
-    }
-    const int j = lane & 15, bq = lane >> 4;
-    const uint32_t lo = ((uint32_t)(4 * t + bq) * NC + j) * 16;
-    r.cf = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(lutA, (tv && j < NC) ? lo : kOob, 0, 0));
+    c.v0 = ta; c.range_end = tb; c.v1 = min(tb, ta + kVisitTiles);
+    c.sg = 0; c.i = 0; c.steps = pad_sets(c.v1 - c.v0); c.done = ta >= tb;
 }
 
-template <int BITS, int CH>
-__global__ void __launch_bounds__(kMaxWaves * 64, 1)
-gemv_bucket_kernel(const uint8_t *__restrict__ packed_, const float *__restrict__ lutA_, const uint16_t *__restrict__ x,
-                   const float *__restrict__ s, uint16_t *__restrict__ y, float *__restrict__ partial,
-                   int N, int K, int chunks_per_split, int splits)
+__device__ __forceinline__ void cursor_next_visit(Cursor &c)
+{
+    c.sg = 0; c.i = 0;
+    if (c.v1 < c.range_end) {
+        c.v0 = c.v1; c.v1 = min(c.range_end, c.v0 + kVisitTiles); c.steps = pad_sets(c.v1 - c.v0);
+    } else {
+        c.done = true;
+    }
+}
+
+__device__ __forceinline__ void cursor_advance(Cursor &c, int nseg)
+{
+    if (c.done) return;
+    if (++c.i < c.steps) return;
+    c.i = 0;
+    if (++c.sg < nseg) return;
+    cursor_next_visit(c);
+}
+
+template <int BITS>
+struct StepRegs {
+    uint4v lo[kBCH];
+    uint2v hi[kBCH];
+};
+
+template <int BITS>
+__device__ __forceinline__ void issue_step_loads(StepRegs<BITS> &r, const Cursor &c, __amdgpu_buffer_rsrc_t rs, int kc, int wave, int lane)
+{
+    constexpr uint32_t TB = BITS == 2 ? 1024 : 1536;
+    // a finished cursor or a padding step issues loads that are out of range: zeros, no traffic
+    const int tile = c.v0 + c.i;
+    const bool tv = !c.done && tile < c.v1;
+#pragma unroll
+    for (int ch = 0; ch < kBCH; ++ch) {
+        const int chunk = c.sg * kBSeg + wave * kBCH + ch;
+        const bool v = tv && chunk < kc;
+        const uint32_t o = ((uint32_t)tile * (uint32_t)kc + (uint32_t)chunk) * TB;
+        r.lo[ch] = __builtin_amdgcn_raw_buffer_load_b128(rs, v ? o + 16 * lane : kOob, 0, 0);
+        if (BITS == 3) r.hi[ch] = __builtin_amdgcn_raw_buffer_load_b64(rs, v ? o + 1024 + 8 * lane : kOob, 0, 0);
+    }
+}
+
+template <int BITS>
+__global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const BucketBatch batch)
 {
     constexpr int NC = BITS == 2 ? 4 : 8;
     constexpr uint32_t TB = BITS == 2 ? 1024 : 1536;
-    __shared__ __attribute__((aligned(16))) _Float16 xs_lds[kMaxWaves * CH * 256];
-    __shared__ __attribute__((aligned(16))) float part[2][kMaxWaves][16];
+    constexpr int NT = kBW * 64;
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+    // LDS: [ xs: kc_max*256 halfs ][ cf: kVisitTiles*16*NC floats ][ part: kBW*kVisitTiles*16 floats ]
+    _Float16 *xs_lds = reinterpret_cast<_Float16 *>(smem);
+    float *cf_lds = reinterpret_cast<float *>(smem + (size_t)batch.kc_max * kTileCols * 2);
+    float *part = cf_lds + kVisitTiles * 16 * NC;
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int q = lane >> 4, j = lane & 15, bq = lane >> 4;
-    const int kc = K / kTileCols, nt = N / kTileRows;
-    const int split = blockIdx.y;
-    const int split_c0 = split * chunks_per_split;
-    const int split_c1 = min(kc, split_c0 + chunks_per_split);
-    const int c_begin = split_c0 + wave * CH;
-    const __amdgpu_buffer_rsrc_t packed = make_rsrc(packed_, (uint32_t)nt * (uint32_t)kc * TB);
-    const __amdgpu_buffer_rsrc_t lutA = make_rsrc(lutA_, (uint32_t)N * NC * 4);
-    const uint32_t tile_stride = (uint32_t)kc * TB;
-    uint32_t choff[CH];
-#pragma unroll
-    for (int ch = 0; ch < CH; ++ch) choff[ch] = (c_begin + ch < split_c1) ? (uint32_t)(c_begin + ch) * TB : kOob;
+    LCD_STAMP(0);
 
-    // ---- prologue: smoothed activations of this workgroup's K range -> LDS -> registers.
-    // Its loads go first (they head the longest dependency chain), then the first tiles'.
-    const int stride = gridDim.x;
-    int t = blockIdx.x;
-    TileRegs<BITS, CH> r0, r1, r2;
-    {
-        const int k0 = split_c0 * kTileCols, groups = (split_c1 - split_c0) * (kTileCols / 8);
-        for (int g = threadIdx.x; g < groups; g += blockDim.x) {
-            const uint4v xv = *reinterpret_cast<const uint4v *>(x + k0 + 8 * g);
-            const float4v s0 = *reinterpret_cast<const float4v *>(s + k0 + 8 * g);
-            const float4v s1 = *reinterpret_cast<const float4v *>(s + k0 + 8 * g + 4);
-            half8 o;
-#pragma unroll
-            for (int e = 0; e < 8; ++e)
-                o[e] = smooth_one((uint16_t)(xv[e >> 1] >> (16 * (e & 1))), e < 4 ? s0[e] : s1[e - 4]);
-            *reinterpret_cast<half8 *>(&xs_lds[8 * g]) = o;
-        }
-    }
-    load_tile<BITS, CH>(r0, packed, lutA, t, nt, tile_stride, choff, lane);
-    load_tile<BITS, CH>(r1, packed, lutA, t + stride, nt, tile_stride, choff, lane);
-    __syncthreads();
-    uint4v A[CH][8];
-    uint4v nA[BITS == 3 ? CH : 1][8];
-#pragma unroll
-    for (int ch = 0; ch < CH; ++ch)
-#pragma unroll
-        for (int g = 0; g < 8; ++g) {
-            uint4v v = {0u, 0u, 0u, 0u};
-            if (choff[ch] != kOob) v = *reinterpret_cast<const uint4v *>(&xs_lds[(wave * CH + ch) * 256 + 64 * q + 8 * g]);
-            A[ch][g] = v;
-            if (BITS == 3) nA[ch][g] = v ^ 0x80008000u;
-        }
-    // constant routing matrices: B1 sends index c to column c, B2 to column 4 + c
+    // which layer, which row tiles
+    int pi = 0;
+    for (int i = 1; i < batch.count; ++i) pi += ((int)blockIdx.x >= batch.wg_begin[i]) ? 1 : 0;
+    const BucketProblem pb = batch.p[pi];
+    const int li = (int)blockIdx.x - batch.wg_begin[pi];
+    const int ta = li * pb.tiles_base + min(li, pb.tiles_extra);
+    const int tb = ta + pb.tiles_base + (li < pb.tiles_extra ? 1 : 0);
+    const int kc = pb.kc, nseg = (kc + kBSeg - 1) / kBSeg;
+    const __amdgpu_buffer_rsrc_t rs_packed = make_rsrc(pb.packed, (uint32_t)pb.nt * (uint32_t)kc * TB);
+    const __amdgpu_buffer_rsrc_t rs_x = make_rsrc(pb.x, (uint32_t)kc * kTileCols * 2);
+    const __amdgpu_buffer_rsrc_t rs_s = make_rsrc(pb.s, (uint32_t)kc * kTileCols * 4);
+    const __amdgpu_buffer_rsrc_t rs_lut = make_rsrc(pb.lutA, (uint32_t)pb.nt * 16 * NC * 4);
+
+    Cursor pf{}, cur{};
+    cursor_begin(pf, ta, tb);
+    cur = pf;
+    if (cur.done) return;
+
+    // the activation loads head the longest dependency chain: issue them first, then the tiles
+    const int groups = kc * (kTileCols / 8);
+    uint4v xv = __builtin_amdgcn_raw_buffer_load_b128(rs_x, (int)threadIdx.x < groups ? threadIdx.x * 16 : kOob, 0, 0);
+    float4v s0 = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(rs_s, (int)threadIdx.x < groups ? threadIdx.x * 32 : kOob, 0, 0));
+    float4v s1 = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(rs_s, (int)threadIdx.x < groups ? threadIdx.x * 32 + 16 : kOob, 0, 0));
+    StepRegs<BITS> r0, r1, r2, r3;
+    issue_step_loads<BITS>(r0, pf, rs_packed, kc, wave, lane); cursor_advance(pf, nseg);
+
+    issue_step_loads<BITS>(r1, pf, rs_packed, kc, wave, lane); cursor_advance(pf, nseg);
+    issue_step_loads<BITS>(r2, pf, rs_packed, kc, wave, lane); cursor_advance(pf, nseg);
+
+    uint4v A[kBCH][8];
+    uint4v nA[BITS == 3 ? kBCH : 1][8];
     half16 B1, B2;
 #pragma unroll
     for (int b = 0; b < 16; ++b) {
-        B1[b] = ((b & 3) == j) ? (_Float16)1.0f : (_Float16)0.0f;
-        B2[b] = ((b & 3) + 4 == j) ? (_Float16)1.0f : (_Float16)0.0f;
+        B1[b] = ((b & 3) == j) ? (_Float16)1.0f : (_Float16)0.0f;       // index c -> column c
+        B2[b] = ((b & 3) + 4 == j) ? (_Float16)1.0f : (_Float16)0.0f;   // index c -> column 4 + c
     }
+    float *my_part = part + wave * (kVisitTiles * 16);
+    LCD_STAMP(1);
 
-    auto process = [&](const TileRegs<BITS, CH> &r, int tile, int buf) {
-        float4v acc[4];
+    // one step: prefetch into the set freed by the previous step, then consume set r
+    auto step = [&](StepRegs<BITS> &r, StepRegs<BITS> &rfree) {
+        issue_step_loads<BITS>(rfree, pf, rs_packed, kc, wave, lane);
+        cursor_advance(pf, nseg);
+        const int tl = cur.i;                       // tile index inside the visit
+        if (cur.v0 + tl < cur.v1) {
+            float4v acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int u = 0; u < 4; ++u) acc[u] = float4v{0.f, 0.f, 0.f, 0.f};
+            for (int ch = 0; ch < kBCH; ++ch) {
 #pragma unroll
-        for (int ch = 0; ch < CH; ++ch) {
+                for (int d = 0; d < 4; ++d) {
+                    const int idxreg = (int)r.lo[ch][d];
+                    // half a = 0 uses index bits [15:0], a = 1 bits [31:16]
+                    acc0 = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(A[ch][2 * d]), B1, acc0, idxreg, 0, 0);
+                    if (BITS == 2) {
+                        acc1 = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(A[ch][2 * d + 1]), B1, acc1, idxreg, 0, 1);
+                    } else {
 #pragma unroll
-            for (int d = 0; d < 4; ++d) {
-                const int idxreg = (int)r.lo[ch][d];
-                // half a = 0 uses index bits [15:0], a = 1 bits [31:16]
-                if (BITS == 2) {
-                    acc[(2 * d) & 3] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(A[ch][2 * d]), B1, acc[(2 * d) & 3], idxreg, 0, 0);
-                    acc[(2 * d + 1) & 3] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(A[ch][2 * d + 1]), B1, acc[(2 * d + 1) & 3], idxreg, 0, 1);
-                } else {
-                    acc[0] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(A[ch][2 * d]), B1, acc[0], idxreg, 0, 0);
-                    acc[1] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(A[ch][2 * d + 1]), B1, acc[1], idxreg, 0, 1);
+                        for (int a = 0; a < 2; ++a) {
+                            const uint32_t hp = r.hi[ch][a];
+                            uint4v f;
 #pragma unroll
-                    for (int a = 0; a < 2; ++a) {
-                        const uint32_t hp = r.hi[ch][a];
-                        uint4v f;
-#pragma unroll
-                        for (int v = 0; v < 4; ++v) {
-                            // pair v of this operand: high bits sit 16 apart; move them to bits 15 / 31
-                            const int sh = 15 - (8 * (v >> 1) + 2 * d + (v & 1));
-                            f[v] = bfi(hp << sh, nA[ch][2 * d + a][v], A[ch][2 * d + a][v]);
+                            for (int v = 0; v < 4; ++v) {
+                                // pair v of this operand: high bits sit 16 apart; move them to bits 15 / 31
+                                const int sh = 15 - (8 * (v >> 1) + 2 * d + (v & 1));
+                                f[v] = bfi(hp << sh, nA[ch][2 * d + a][v], A[ch][2 * d + a][v]);
+                            }
+                            if (a == 0) {
+                                acc1 = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(f), B2, acc1, idxreg, 0, 0);
+                                acc0 = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(A[ch][2 * d + 1]), B1, acc0, idxreg, 0, 1);
+                            } else {
+                                acc1 = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(f), B2, acc1, idxreg, 0, 1);
+                            }
                         }
-                        if (a == 0) acc[2] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(f), B2, acc[2], idxreg, 0, 0);
-                        else        acc[3] = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(f), B2, acc[3], idxreg, 0, 1);
                     }
                 }
             }
-        }
-        // bucket sums -> outputs: multiply by the codebook-derived factors, add the NC columns
-        float4v p;
+            // bucket sums -> 16 partial outputs: multiply by the per-bucket factors, add the NC columns
+            float4v cf = {0.f, 0.f, 0.f, 0.f};
+            if (j < NC) cf = *reinterpret_cast<const float4v *>(&cf_lds[((tl * 4 + bq) * NC + j) * 4]);
+            float4v pv;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            float v = ((acc[0][u] + acc[1][u]) + (acc[2][u] + acc[3][u])) * r.cf[u];
-            v += dpp_f32<kDppQuadXor1>(v);
-            v += dpp_f32<kDppQuadXor2>(v);
-            if (NC == 8) v += dpp_f32<kDppRowHalfMirror>(v);
-            p[u] = v;
+            for (int u = 0; u < 4; ++u) {
+                float v = (acc0[u] + acc1[u]) * cf[u];
+                v += dpp_f32<kDppQuadXor1>(v);
+                v += dpp_f32<kDppQuadXor2>(v);
+                if (NC == 8) v += dpp_f32<kDppRowHalfMirror>(v);
+                pv[u] = v;
+            }
+            if (j == 0) {
+                float4v *slot = reinterpret_cast<float4v *>(&my_part[tl * 16 + 4 * bq]);
+                if (cur.sg > 0) pv += *slot;
+                *slot = pv;
+            }
         }
-        if (j == 0) *reinterpret_cast<float4v *>(&part[buf][wave][4 * bq]) = p;
-        __syncthreads();
-        if (threadIdx.x < 16) {
-            float sum = 0.f;
-            for (int w = 0; w < nwaves; ++w) sum += part[buf][w][threadIdx.x];
-            const size_t o = (size_t)tile * kTileRows + threadIdx.x;
-            if (splits == 1) y[o] = __builtin_bit_cast(uint16_t, (_Float16)sum);
-            else partial[(size_t)split * N + o] = sum;
-        }
+        ++cur.i;
     };
 
-    // three register sets rotate: two tiles are always in flight behind the one being consumed
-    while (true) {
-        load_tile<BITS, CH>(r2, packed, lutA, t + 2 * stride, nt, tile_stride, choff, lane);
-        process(r0, t, 0);
-        t += stride;
-        if (t >= nt) break;
-        load_tile<BITS, CH>(r0, packed, lutA, t + 2 * stride, nt, tile_stride, choff, lane);
-        process(r1, t, 1);
-        t += stride;
-        if (t >= nt) break;
-        load_tile<BITS, CH>(r1, packed, lutA, t + 2 * stride, nt, tile_stride, choff, lane);
-        process(r2, t, 0);
-        t += stride;
-        if (t >= nt) break;
-        load_tile<BITS, CH>(r2, packed, lutA, t + 2 * stride, nt, tile_stride, choff, lane);
-        process(r0, t, 1);
-        t += stride;
-        if (t >= nt) break;
-        load_tile<BITS, CH>(r0, packed, lutA, t + 2 * stride, nt, tile_stride, choff, lane);
-        process(r1, t, 0);
-        t += stride;
-        if (t >= nt) break;
-        load_tile<BITS, CH>(r1, packed, lutA, t + 2 * stride, nt, tile_stride, choff, lane);
-        process(r2, t, 1);
-        t += stride;
-        if (t >= nt) break;
+    bool first_visit = true;
+    while (!cur.done) {
+        // ---- visit prologue (the barrier that ended the previous visit protects the LDS reuse)
+        {
+            const int nf4 = (cur.v1 - cur.v0) * 4 * NC;   // float4 count of the visit's multipliers
+            for (int e = threadIdx.x; e < nf4; e += NT)
+                reinterpret_cast<uint4v *>(cf_lds)[e] = __builtin_amdgcn_raw_buffer_load_b128(rs_lut, ((uint32_t)cur.v0 * 4 * NC + e) * 16, 0, 0);
+        }
+        if (first_visit) {
+            for (int g = threadIdx.x; g < groups; g += NT) {
+                if (g >= NT) {
+                    xv = __builtin_amdgcn_raw_buffer_load_b128(rs_x, g * 16, 0, 0);
+                    s0 = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(rs_s, g * 32, 0, 0));
+                    s1 = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(rs_s, g * 32 + 16, 0, 0));
+                }
+                half8 o;
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    o[e] = smooth_one((uint16_t)(xv[e >> 1] >> (16 * (e & 1))), e < 4 ? s0[e] : s1[e - 4]);
+                *reinterpret_cast<half8 *>(&xs_lds[8 * g]) = o;
+            }
+            first_visit = false;
+        }
+        LCD_STAMP(2);
+        __syncthreads();
+        LCD_STAMP(3);
+        for (cur.sg = 0; cur.sg < nseg; ++cur.sg) {
+#pragma unroll
+            for (int ch = 0; ch < kBCH; ++ch) {
+                const int chunk = cur.sg * kBSeg + wave * kBCH + ch;
+#pragma unroll
+                for (int g = 0; g < 8; ++g) {
+                    uint4v v = {0u, 0u, 0u, 0u};
+                    if (chunk < kc) v = *reinterpret_cast<const uint4v *>(&xs_lds[chunk * 256 + 64 * q + 8 * g]);
+                    A[ch][g] = v;
+                    if (BITS == 3) nA[ch][g] = v ^ 0x80008000u;
+                }
+            }
+            for (cur.i = 0; cur.i < cur.steps;) {
+                step(r0, r3);
+                step(r1, r0);
+                step(r2, r1);
+                step(r3, r2);
+            }
+        }
+        LCD_STAMP(4);
+        __syncthreads();
+        LCD_STAMP(5);
+        // ---- visit epilogue: add the waves' slots in a fixed order, round once, store
+        for (int e = threadIdx.x; e < (cur.v1 - cur.v0) * 16; e += NT) {
+            float sum = 0.f;
+#pragma unroll
+            for (int w = 0; w < kBW; ++w) sum += part[w * (kVisitTiles * 16) + e];
+            pb.y[(size_t)cur.v0 * kTileRows + e] = __builtin_bit_cast(uint16_t, (_Float16)sum);
+        }
+        cursor_next_visit(cur);
+        LCD_STAMP(6);
     }
 }
 
@@ -330,12 +433,88 @@ gemv_dense_kernel(const uint8_t *__restrict__ packed, const uint8_t *__restrict_
     }
 }
 
-template <int BITS, int CH>
-static int launch_bucket(const void *packed, const void *lut, const uint16_t *x, const float *s, uint16_t *y,
-                         float *partial, int N, int K, const GemvPlan &plan, hipStream_t stream)
+#ifdef LCD_TRACE
+unsigned long long *g_trace = nullptr;
+extern "C" void lcd_debug_set_trace(unsigned long long *p) { g_trace = p; }
+#endif
+static int g_num_cus = 0;
+static int num_cus()
 {
-    hipLaunchKernelGGL((gemv_bucket_kernel<BITS, CH>), dim3(plan.grid_x, plan.splits), dim3(plan.waves * 64), 0, stream,
-                       (const uint8_t *)packed, (const float *)lut, x, s, y, partial, N, K, plan.chunks_per_split, plan.splits);
+    if (g_num_cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        g_num_cus = n;
+    }
+    return g_num_cus;
+}
+
+// One launch for a group of single-token problems.
+int launch_bucket_group(const GroupItem *items, int count, int bits, void *stream_)
+{
+    hipStream_t stream = (hipStream_t)stream_;
+    BucketBatch batch{};
+    long long cost[kMaxGroup], total = 0;
+    int kmax = 0, tiles = 0;
+    for (int i = 0; i < count; ++i) {
+        BucketProblem &p = batch.p[i];
+        p.packed = (const uint8_t *)items[i].packed;
+        p.lutA = (const float *)items[i].lut;
+        p.x = items[i].x; p.s = items[i].s; p.y = items[i].y;
+        p.nt = items[i].N / kTileRows; p.kc = items[i].K / kTileCols;
+        cost[i] = (long long)p.nt * p.kc;
+        total += cost[i];
+        tiles += p.nt;
+        if (p.kc > kmax) kmax = p.kc;
+    }
+    // workgroups per layer: proportional to its packed bytes, at least 1, at most its row tiles
+    int grid = num_cus();
+    if (grid > tiles) grid = tiles;
+    if (grid < count) grid = count;
+    int nwg[kMaxGroup], used = 0;
+    for (int i = 0; i < count; ++i) {
+        long long n = cost[i] * grid / total;
+        if (n < 1) n = 1;
+        if (n > batch.p[i].nt) n = batch.p[i].nt;
+        nwg[i] = (int)n;
+        used += nwg[i];
+    }
+    while (used < grid) {  // hand the remaining workgroups to the layers with the most work per workgroup
+        int best = -1;
+        double best_load = 0.0;
+        for (int i = 0; i < count; ++i) {
+            if (nwg[i] >= batch.p[i].nt) continue;
+            // time of a layer ~ its slowest workgroup: ceil(nt / nwg) row tiles of kc chunks
+            const double load = (double)((batch.p[i].nt + nwg[i] - 1) / nwg[i]) * batch.p[i].kc;
+            if (load > best_load) { best_load = load; best = i; }
+        }
+        if (best < 0) break;
+        ++nwg[best];
+        ++used;
+    }
+    grid = used;
+    int acc = 0;
+    for (int i = 0; i < count; ++i) {
+        batch.wg_begin[i] = acc;
+        acc += nwg[i];
+        batch.p[i].tiles_base = batch.p[i].nt / nwg[i];
+        batch.p[i].tiles_extra = batch.p[i].nt % nwg[i];
+    }
+    for (int i = count; i <= kMaxGroup; ++i) batch.wg_begin[i] = acc;
+    batch.count = count;
+    batch.kc_max = kmax;
+#ifdef LCD_TRACE
+    batch.trace = g_trace;
+#endif
+    const int NC = bits == 2 ? 4 : 8;
+    const size_t lds = (size_t)kmax * kTileCols * 2 + (size_t)kVisitTiles * 16 * NC * 4 + (size_t)kBW * kVisitTiles * 16 * 4;
+    static size_t lds_set[2] = {0, 0};
+    const void *fn = bits == 2 ? (const void *)gemv_bucket_kernel<2> : (const void *)gemv_bucket_kernel<3>;
+    if (lds > lds_set[bits - 2]) {
+        if (hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)) return (int)e;
+        lds_set[bits - 2] = lds;
+    }
+    if (bits == 2) hipLaunchKernelGGL(gemv_bucket_kernel<2>, dim3(grid), dim3(kBW * 64), lds, stream, batch);
+    else hipLaunchKernelGGL(gemv_bucket_kernel<3>, dim3(grid), dim3(kBW * 64), lds, stream, batch);
     return (int)hipGetLastError();
 }
 
@@ -345,11 +524,8 @@ int launch_gemv(const void *packed, const void *lut, const uint16_t *x, const fl
     hipStream_t stream = (hipStream_t)stream_;
     float *partial = reinterpret_cast<float *>(static_cast<uint8_t *>(workspace) + plan.xs_bytes);
     if (M == 1) {
-        int e = bits == 2 ? launch_bucket<2, 4>(packed, lut, x, s, y, partial, N, K, plan, stream)
-                          : launch_bucket<3, 2>(packed, lut, x, s, y, partial, N, K, plan, stream);
-        if (e) return e;
-        if (plan.splits > 1) return launch_reduce(partial, y, plan.splits, (long long)N, stream);
-        return 0;
+        GroupItem it{packed, lut, x, s, y, N, K};
+        return launch_bucket_group(&it, 1, bits, stream_);
     }
     // batched: smooth once into the workspace (dequantiser slot order), then the dense kernel
     _Float16 *xs = reinterpret_cast<_Float16 *>(workspace);

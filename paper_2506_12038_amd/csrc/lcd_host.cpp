@@ -24,7 +24,7 @@ static lcd_status check_shape(int N, int K, int bits)
     if (bits != 2 && bits != 3) return fail(LCD_ERR_BAD_BITS, "bits=%d: only 2 and 3 are supported", bits);
     if (N <= 0 || K <= 0 || N % kTileRows != 0 || K % kTileCols != 0)
         return fail(LCD_ERR_BAD_SHAPE, "N=%d must be a positive multiple of %d and K=%d of %d", N, kTileRows, K, kTileCols);
-    if ((long long)N * (long long)K > (1ll << 40)) return fail(LCD_ERR_BAD_SHAPE, "N*K too large");
+    if ((long long)N * (long long)K * bits / 8 >= (1ll << 32)) return fail(LCD_ERR_BAD_SHAPE, "packed matrix must be smaller than 4 GiB");
     return LCD_OK;
 }
 
@@ -247,9 +247,50 @@ lcd_status lcd_lut_gemv(const void *packed, const void *lut, const uint16_t *x, 
 {
     if (M > 16) return fail(LCD_ERR_BAD_M, "lcd_lut_gemv: M=%d > 16 (use lcd_lut_gemm)", M);
     if (lcd_status st = check_product(packed, lut, x, s, y, M, N, K, bits, workspace, workspace_bytes)) return st;
+    if (M == 1 && K > kMaxBucketK) return fail(LCD_ERR_BAD_SHAPE, "K=%d > %d is not supported at M=1", K, kMaxBucketK);
     const GemvPlan plan = plan_gemv(M, N, K, bits);
     if (int e = launch_gemv(packed, lut, x, s, y, M, N, K, bits, workspace, plan, stream))
         return fail(LCD_ERR_HIP, "gemv launch: %s", hip_error_name(e));
+    return LCD_OK;
+}
+
+size_t lcd_workspace_bytes_grouped(const lcd_gemv_problem *problems, int count, int M, int bits)
+{
+    if (!problems || count < 1 || count > kMaxGroup || M < 1 || M > 16) return 0;
+    size_t need = 256;
+    for (int i = 0; i < count; ++i) {
+        const size_t w = lcd_workspace_bytes(M, problems[i].N, problems[i].K, bits);
+        if (w == 0) return 0;
+        if (w > need) need = w;
+    }
+    return need;
+}
+
+lcd_status lcd_lut_gemv_grouped(const lcd_gemv_problem *problems, int count, int M, int bits,
+                                void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!problems) return fail(LCD_ERR_NULL, "problems is NULL");
+    if (count < 1 || count > kMaxGroup) return fail(LCD_ERR_SIZE, "count=%d must be in 1..%d", count, kMaxGroup);
+    if (M > 16) return fail(LCD_ERR_BAD_M, "lcd_lut_gemv_grouped: M=%d > 16", M);
+    for (int i = 0; i < count; ++i) {
+        const lcd_gemv_problem &p = problems[i];
+        if (lcd_status st = check_product(p.packed, p.lut, p.x, p.s, p.y, M, p.N, p.K, bits, workspace, workspace_bytes)) return st;
+        if (M == 1 && p.K > kMaxBucketK) return fail(LCD_ERR_BAD_SHAPE, "K=%d > %d is not supported at M=1", p.K, kMaxBucketK);
+    }
+    if (M == 1) {
+        GroupItem items[kMaxGroup];
+        for (int i = 0; i < count; ++i)
+            items[i] = GroupItem{problems[i].packed, problems[i].lut, problems[i].x, problems[i].s, problems[i].y, problems[i].N, problems[i].K};
+        if (int e = launch_bucket_group(items, count, bits, stream)) return fail(LCD_ERR_HIP, "grouped gemv launch: %s", hip_error_name(e));
+        return LCD_OK;
+    }
+    // batched tokens: the layers run one after the other on the stream and share the workspace
+    for (int i = 0; i < count; ++i) {
+        const lcd_gemv_problem &p = problems[i];
+        const GemvPlan plan = plan_gemv(M, p.N, p.K, bits);
+        if (int e = launch_gemv(p.packed, p.lut, p.x, p.s, p.y, M, p.N, p.K, bits, workspace, plan, stream))
+            return fail(LCD_ERR_HIP, "gemv launch: %s", hip_error_name(e));
+    }
     return LCD_OK;
 }
 

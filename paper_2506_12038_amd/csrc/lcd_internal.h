@@ -35,6 +35,14 @@ struct GemmPlan {
 };
 GemmPlan plan_gemm(int M, int N, int K, int bits);
 
+constexpr int kMaxGroup = 16;     // problems per grouped launch
+constexpr int kMaxBucketK = 65536;  // single-token kernel keeps one token's activations in LDS
+
+struct GroupItem {
+    const void *packed; const void *lut; const uint16_t *x; const float *s; uint16_t *y; int N, K;
+};
+int launch_bucket_group(const GroupItem *items, int count, int bits, void *stream);
+
 // Launchers implemented in the .hip files.  All return hipError_t as int (0 = success).
 int launch_pack(const uint8_t *idx, int N, int K, int bits, void *packed, void *stream);
 int launch_unpack(const void *packed, int N, int K, int bits, uint8_t *idx, void *stream);

@@ -54,3 +54,48 @@ def test_gemv_is_deterministic():
     y1 = run_hip(layer, 3)
     y2 = run_hip(layer, 3)
     assert np.array_equal(y1.view(np.uint16), y2.view(np.uint16))
+
+
+@pytest.mark.parametrize("bits,M", [(3, 1), (2, 1), (2, 4)])
+def test_grouped_launch_matches_oracle_and_single_calls(bits, M):
+    # a mixed group: different N and K per layer, one launch
+    import torch
+    shapes = [(64, 1024), (208, 512), (48, 2816), (16, 256), (96, 4352)]
+    problems, layers, singles = [], [], []
+    for i, (N, K) in enumerate(shapes):
+        layer = synth.make_layer(1, i, N, K, bits, M, seed_offset=3 * i + bits)
+        packed = lcd.lcd_pack_indices(to_dev(layer["idx"]), bits)
+        lut = lcd.lcd_build_lut(to_dev(layer["codebook"]), bits)
+        x, s = to_dev(layer["x"]), to_dev(layer["s"])
+        y = torch.full((M, N), float("nan"), dtype=torch.float16, device="cuda")
+        problems.append((packed, lut, x, s, y, N))
+        layers.append(layer)
+        singles.append(lcd.lcd_lut_gemv(packed, lut, x, s, N, bits))
+    lcd.lcd_lut_gemv_grouped(problems, bits)
+    torch.cuda.synchronize()
+    for (packed, lut, x, s, y, N), layer, single in zip(problems, layers, singles):
+        Y = oracle.lut_matmul(layer["codebook"], layer["idx"], layer["x"], layer["s"], bits)
+        err = oracle.parity_errors(y.cpu().numpy(), Y)
+        assert err["max_rel_floored"] <= TOL, err
+        assert torch.equal(y, single)  # same kernel, same reduction order: bit-identical
+
+
+def test_grouped_config1_full_size_sampled():
+    import torch
+    config = synth.get_config(1)
+    problems, layers = [], []
+    for mid, spec in config.matrices():
+        layer = synth.make_layer(1, mid, spec.N, spec.K, config.bits, 1)
+        packed = lcd.lcd_pack_indices(to_dev(layer["idx"]), config.bits)
+        lut = lcd.lcd_build_lut(to_dev(layer["codebook"]), config.bits)
+        y = torch.empty((1, spec.N), dtype=torch.float16, device="cuda")
+        problems.append((packed, lut, to_dev(layer["x"]), to_dev(layer["s"]), y, spec.N))
+        rs = np.sort(np.random.default_rng(mid).choice(spec.N, size=256, replace=False))
+        rs[0] = 0; rs[-1] = spec.N - 1
+        layers.append((rs, oracle.lut_matmul(layer["codebook"][rs], layer["idx"][rs], layer["x"], layer["s"], config.bits)))
+        del layer
+    lcd.lcd_lut_gemv_grouped(problems, config.bits)
+    torch.cuda.synchronize()
+    for (packed, lut, x, s, y, N), (rs, Y) in zip(problems, layers):
+        err = oracle.parity_errors(y.cpu().numpy()[:, rs], Y)
+        assert err["max_rel_floored"] <= TOL, err

@@ -118,3 +118,27 @@ def test_device_entry_points_validate_before_launch():
     assert st(lib.lcd_lut_gemv(a, a, a, odd, a, 1, 16, 256, 2, a, big, None)) == b"LCD_ERR_ALIGN"
     assert st(lib.lcd_lut_gemm(a, a, None, a, a, 64, 16, 256, 3, a, big, None)) == b"LCD_ERR_NULL"
     assert st(lib.lcd_lut_gemm(a, a, a, a, a, 64, 16, 256, 1, a, big, None)) == b"LCD_ERR_BAD_BITS"
+
+
+def test_grouped_entry_point_validates_on_host():
+    from paper_2506_12038_amd.binding import _Problem
+    lib = lcd.load_library()
+    a = 0x1000
+    arr = (_Problem * 2)(_Problem(a, a, a, a, a, 16, 256), _Problem(a, a, a, a, a, 32, 512))
+    st = lambda code: lib.lcd_status_string(code)
+    big = 1 << 30
+    assert lib.lcd_workspace_bytes_grouped(arr, 2, 1, 2) >= 256
+    assert lib.lcd_workspace_bytes_grouped(arr, 0, 1, 2) == 0
+    assert lib.lcd_workspace_bytes_grouped(arr, 2, 17, 2) == 0
+    assert st(lib.lcd_lut_gemv_grouped(None, 2, 1, 2, ctypes.c_void_p(a), big, None)) == b"LCD_ERR_NULL"
+    assert st(lib.lcd_lut_gemv_grouped(arr, 17, 1, 2, ctypes.c_void_p(a), big, None)) == b"LCD_ERR_SIZE"
+    assert st(lib.lcd_lut_gemv_grouped(arr, 2, 20, 2, ctypes.c_void_p(a), big, None)) == b"LCD_ERR_BAD_M"
+    assert st(lib.lcd_lut_gemv_grouped(arr, 2, 1, 5, ctypes.c_void_p(a), big, None)) == b"LCD_ERR_BAD_BITS"
+    arr[1].K = 500
+    assert st(lib.lcd_lut_gemv_grouped(arr, 2, 1, 2, ctypes.c_void_p(a), big, None)) == b"LCD_ERR_BAD_SHAPE"
+    arr[1].K = 512
+    arr[1].y = 0x1002
+    assert st(lib.lcd_lut_gemv_grouped(arr, 2, 1, 2, ctypes.c_void_p(a), big, None)) == b"LCD_ERR_ALIGN"
+    # single-token path keeps one token's activations in LDS: K is bounded
+    assert st(lib.lcd_lut_gemv(ctypes.c_void_p(a), ctypes.c_void_p(a), ctypes.c_void_p(a), ctypes.c_void_p(a),
+                               ctypes.c_void_p(a), 1, 16, 65536 + 256, 2, ctypes.c_void_p(a), big, None)) == b"LCD_ERR_BAD_SHAPE"
