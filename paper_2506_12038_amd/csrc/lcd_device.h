@@ -30,12 +30,17 @@ __device__ __forceinline__ uint32_t bfi(uint32_t mask, uint32_t a, uint32_t b) {
 __device__ __forceinline__ half8 as_half8(uint4v v) { return __builtin_bit_cast(half8, v); }
 __device__ __forceinline__ uint4v as_uint4(half8 v) { return __builtin_bit_cast(uint4v, v); }
 
-// x / s in fp32 with IEEE division, rounded once more to fp16 (round to nearest even).
+// Smoothing of one activation: x * (1/s) in fp32 (the reciprocal is accurate to 1 ulp; paper
+// Sec. 4.1 folds the division into one multiplication by a stored reciprocal), rounded once
+// more to fp16 (round to nearest even).  Exact when s is a power of two.
 __device__ __forceinline__ _Float16 smooth_one(uint16_t xbits, float s)
 {
     const float xf = (float)__builtin_bit_cast(_Float16, xbits);
-    return (_Float16)__fdiv_rn(xf, s);
+    return (_Float16)(xf * __builtin_amdgcn_rcpf(s));
 }
+
+// a ^ (b & c): one v_bitop3_b32.
+__device__ __forceinline__ uint32_t xor_and(uint32_t a, uint32_t b, uint32_t c) { return a ^ (b & c); }
 
 }  // namespace lcd
 

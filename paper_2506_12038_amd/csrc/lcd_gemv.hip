@@ -38,21 +38,22 @@ constexpr uint32_t kOob = 0xFFFFFFF0u;
 
 // ---- single-token bucket kernel: persistent workgroups over a group of layers ---------------
 //
-// The host gives every layer of the group a number of workgroups proportional to its packed
-// bytes; a workgroup owns a contiguous run of row tiles of ONE layer and walks it in "visits"
-// of up to kVisitTiles row tiles.  Per visit:
+// The host gives every layer of the group a number of workgroups proportional to its work; a
+// workgroup owns a contiguous run of row tiles of ONE layer and walks it in "visits" of up to
+// kVisitTiles row tiles.  Per visit:
 //   prologue   smoothed activations of the layer (all K, first visit only) and the visit's
 //              per-bucket multipliers go to LDS; one barrier;
-//   segments   the 8 waves split K into segments of 16 chunks (2 chunks per wave).  For each
-//              segment a wave loads its activations LDS -> registers once, then streams the
-//              visit's row tiles: 2-3 KiB of packed indices per tile, 16-32 sparse MFMAs, and a
-//              few VALU ops that turn bucket sums into 16 partial outputs which the wave adds
-//              into its own LDS slot (no synchronisation: the slot is private to the wave);
-//   epilogue   one barrier; the workgroup adds the 8 waves' slots in a fixed order and stores y.
+//   segments   the 8 waves split K into segments of 16 chunks (two 256-column chunks per wave).
+//              For each segment a wave loads its activations LDS -> registers once, then streams
+//              the visit's row tiles: 2-3 KiB of packed indices per tile, 16-32 sparse MFMAs,
+//              and (once per 2 or 4 tiles) a few VALU ops that turn bucket sums into partial
+//              outputs, which the wave adds into its own LDS slot (no synchronisation);
+//   epilogue   one barrier; the workgroup adds the 8 waves' slots in a fixed order, stores y.
 // Loads of packed indices run kSets-1 steps ahead of the arithmetic, across segment and visit
-// boundaries, and start before the prologue.
+// boundaries.  Matrix and vector instructions of one SIMD do not overlap in time (measured), so
+// the instruction count per byte is what matters, not the number of waves.
 constexpr int kBW = 8;            // waves per workgroup
-constexpr int kBCH = 2;           // chunks per wave per segment (activations kept in registers)
+constexpr int kBCH = 2;           // chunks per wave per segment (their activations stay in registers)
 constexpr int kBSeg = kBW * kBCH; // chunks per segment (one pass of the workgroup over K)
 constexpr int kSets = 4;          // register sets in rotation (loads run kSets-1 steps ahead)
 constexpr int kVisitTiles = 32;   // row tiles per visit
@@ -72,7 +73,7 @@ struct BucketBatch {
     int count;
     int kc_max;
 #ifdef LCD_TRACE
-    unsigned long long *trace;   // debug builds only: 8 timestamps per workgroup
+    unsigned long long *trace;   // debug builds only: 16 timestamps per workgroup
 #endif
 };
 #ifdef LCD_TRACE
@@ -118,8 +119,8 @@ __device__ __forceinline__ void cursor_advance(Cursor &c, int nseg)
 
 template <int BITS>
 struct StepRegs {
-    uint4v lo[kBCH];
-    uint2v hi[kBCH];
+    uint4v lo[kBCH];   // the lane's 64 two-bit fields of this (tile, chunk)
+    uint2v hi[kBCH];   // 3 bits only: its 64 third bits
 };
 
 template <int BITS>
@@ -142,7 +143,8 @@ __device__ __forceinline__ void issue_step_loads(StepRegs<BITS> &r, const Cursor
 template <int BITS>
 __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const BucketBatch batch)
 {
-    constexpr int NC = BITS == 2 ? 4 : 8;
+    constexpr int NC = BITS == 2 ? 4 : 8;        // accumulator columns one row tile uses
+    constexpr int TG = 16 / NC;                  // row tiles that share one reduction (4 or 2)
     constexpr uint32_t TB = BITS == 2 ? 1024 : 1536;
     constexpr int NT = kBW * 64;
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
@@ -173,112 +175,160 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const BucketBa
     cur = pf;
     if (cur.done) return;
 
-    // the activation loads head the longest dependency chain: issue them first, then the tiles
+    // The activation / multiplier loads head the longest dependency chain: every wave issues
+    // them before its tile loads and converts them as soon as they (not the tiles) arrive.
+    constexpr int XR = 1;   // activation groups preloaded per thread (K <= 8192); larger K takes a serial loop
     const int groups = kc * (kTileCols / 8);
-    uint4v xv = __builtin_amdgcn_raw_buffer_load_b128(rs_x, (int)threadIdx.x < groups ? threadIdx.x * 16 : kOob, 0, 0);
-    float4v s0 = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(rs_s, (int)threadIdx.x < groups ? threadIdx.x * 32 : kOob, 0, 0));
-    float4v s1 = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(rs_s, (int)threadIdx.x < groups ? threadIdx.x * 32 + 16 : kOob, 0, 0));
+    uint4v xv[XR];
+    float4v s0[XR], s1[XR];
+#pragma unroll
+    for (int u = 0; u < XR; ++u) {
+        const int g = threadIdx.x + u * NT;
+        xv[u] = __builtin_amdgcn_raw_buffer_load_b128(rs_x, g < groups ? g * 16 : kOob, 0, 0);
+        s0[u] = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(rs_s, g < groups ? g * 32 : kOob, 0, 0));
+        s1[u] = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(rs_s, g < groups ? g * 32 + 16 : kOob, 0, 0));
+    }
+    const int nf4_first = (cur.v1 - cur.v0) * 4 * NC;   // float4 count of the first visit's multipliers (<= NT)
+    const uint4v cfv = __builtin_amdgcn_raw_buffer_load_b128(rs_lut, (int)threadIdx.x < nf4_first ? ((uint32_t)cur.v0 * 4 * NC + threadIdx.x) * 16 : kOob, 0, 0);
     StepRegs<BITS> r0, r1, r2, r3;
     issue_step_loads<BITS>(r0, pf, rs_packed, kc, wave, lane); cursor_advance(pf, nseg);
 
-    issue_step_loads<BITS>(r1, pf, rs_packed, kc, wave, lane); cursor_advance(pf, nseg);
-    issue_step_loads<BITS>(r2, pf, rs_packed, kc, wave, lane); cursor_advance(pf, nseg);
-
-    uint4v A[kBCH][8];
-    uint4v nA[BITS == 3 ? kBCH : 1][8];
-    half16 B1, B2;
-#pragma unroll
-    for (int b = 0; b < 16; ++b) {
-        B1[b] = ((b & 3) == j) ? (_Float16)1.0f : (_Float16)0.0f;       // index c -> column c
-        B2[b] = ((b & 3) + 4 == j) ? (_Float16)1.0f : (_Float16)0.0f;   // index c -> column 4 + c
-    }
+    uint4v A[kBCH][8];   // this wave's smoothed activations of the current segment, 8 operands per chunk
+    half16 B1;        // constant routing matrix (index c -> column c), built after the prologue
     float *my_part = part + wave * (kVisitTiles * 16);
     LCD_STAMP(1);
 
-    // one step: prefetch into the set freed by the previous step, then consume set r
-    auto step = [&](StepRegs<BITS> &r, StepRegs<BITS> &rfree) {
-        issue_step_loads<BITS>(rfree, pf, rs_packed, kc, wave, lane);
-        cursor_advance(pf, nseg);
-        const int tl = cur.i;                       // tile index inside the visit
-        if (cur.v0 + tl < cur.v1) {
-            float4v acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+    // bucket sums of one (tile, chunk): columns [0, NC) of a 16x16 accumulator
+    auto tile_sums = [&](const StepRegs<BITS> &r) -> float4v {
+        float4v accx = {0.f, 0.f, 0.f, 0.f}, accy = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int ch = 0; ch < kBCH; ++ch) {
+        for (int ch = 0; ch < kBCH; ++ch) {
 #pragma unroll
-                for (int d = 0; d < 4; ++d) {
-                    const int idxreg = (int)r.lo[ch][d];
-                    // half a = 0 uses index bits [15:0], a = 1 bits [31:16]
-                    acc0 = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(A[ch][2 * d]), B1, acc0, idxreg, 0, 0);
-                    if (BITS == 2) {
-                        acc1 = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(A[ch][2 * d + 1]), B1, acc1, idxreg, 0, 1);
-                    } else {
+            for (int d = 0; d < 4; ++d) {
+                const int idxreg = (int)r.lo[ch][d];
+                // half a = 0 uses index bits [15:0], a = 1 bits [31:16]
+                if (BITS == 2) {
+                    accx = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(A[ch][2 * d]), B1, accx, idxreg, 0, 0);
+                    accy = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(A[ch][2 * d + 1]), B1, accy, idxreg, 0, 1);
+                } else {
+                    // sign-flipped operands: pair v of half a has its two third bits 16 apart in word a
+                    // of r.hi; one 64-bit shift moves them to bits 15 / 31 of both words, one
+                    // xor-and per word applies them
+                    const unsigned long long h64 = ((unsigned long long)r.hi[ch][1] << 32) | r.hi[ch][0];
+                    uint4v f0, f1;
 #pragma unroll
-                        for (int a = 0; a < 2; ++a) {
-                            const uint32_t hp = r.hi[ch][a];
-                            uint4v f;
-#pragma unroll
-                            for (int v = 0; v < 4; ++v) {
-                                // pair v of this operand: high bits sit 16 apart; move them to bits 15 / 31
-                                const int sh = 15 - (8 * (v >> 1) + 2 * d + (v & 1));
-                                f[v] = bfi(hp << sh, nA[ch][2 * d + a][v], A[ch][2 * d + a][v]);
-                            }
-                            if (a == 0) {
-                                acc1 = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(f), B2, acc1, idxreg, 0, 0);
-                                acc0 = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(A[ch][2 * d + 1]), B1, acc0, idxreg, 0, 1);
-                            } else {
-                                acc1 = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(f), B2, acc1, idxreg, 0, 1);
-                            }
-                        }
+                    for (int v = 0; v < 4; ++v) {
+                        const int sh = 15 - (8 * (v >> 1) + 2 * d + (v & 1));
+                        unsigned long long t = h64;   // one full-rate v_lshlrev_b64 (the compiler would split it in two)
+                        if (sh) asm("v_lshlrev_b64 %0, %1, %2" : "=v"(t) : "n"(sh), "v"(h64));
+                        f0[v] = xor_and(A[ch][2 * d][v], (uint32_t)t, 0x80008000u);
+                        f1[v] = xor_and(A[ch][2 * d + 1][v], (uint32_t)(t >> 32), 0x80008000u);
                     }
+                    accx = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(A[ch][2 * d]), B1, accx, idxreg, 0, 0);
+                    accy = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(f0), B1, accy, idxreg, 0, 0);
+                    accx = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(A[ch][2 * d + 1]), B1, accx, idxreg, 0, 1);
+                    accy = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(f1), B1, accy, idxreg, 0, 1);
                 }
             }
-            // bucket sums -> 16 partial outputs: multiply by the per-bucket factors, add the NC columns
-            float4v cf = {0.f, 0.f, 0.f, 0.f};
-            if (j < NC) cf = *reinterpret_cast<const float4v *>(&cf_lds[((tl * 4 + bq) * NC + j) * 4]);
-            float4v pv;
+        }
+        if (BITS == 2) return accx + accy;
+        // 3 bits: the sign-flipped sums move from columns 0..3 to columns 4..7
+        float4v m;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) m[u] = accx[u] + dpp_f32<0x114>(accy[u]);   // row_shr:4
+        return m;
+    };
+
+    // TG tiles share one multiply-and-reduce: tile u of the group moves to columns [u*NC, (u+1)*NC)
+    auto reduce_group = [&](float4v m, int tl0) {
+        const int tl = tl0 + j / NC;                    // this lane's tile inside the visit
+        float4v cf = {0.f, 0.f, 0.f, 0.f};
+        if (cur.v0 + tl < cur.v1) cf = *reinterpret_cast<const float4v *>(&cf_lds[((tl * 4 + bq) * NC + (j % NC)) * 4]);
+        float4v pv;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            float v = m[u] * cf[u];
+            v += dpp_f32<kDppQuadXor1>(v);
+            v += dpp_f32<kDppQuadXor2>(v);
+            if (NC == 8) v += dpp_f32<kDppRowHalfMirror>(v);
+            pv[u] = v;
+        }
+        if ((j % NC) == 0 && cur.v0 + tl < cur.v1) {
+            float4v *slot = reinterpret_cast<float4v *>(&my_part[tl * 16 + 4 * bq]);
+            if (cur.sg > 0) pv += *slot;
+            *slot = pv;
+        }
+    };
+
+    // four steps = one turn of the register-set rotation; cur.i is the first step's tile
+    auto four_steps = [&]() {
+        float4v t0, t1;
+        issue_step_loads<BITS>(r3, pf, rs_packed, kc, wave, lane); cursor_advance(pf, nseg);
+        t0 = tile_sums(r0);
+        issue_step_loads<BITS>(r0, pf, rs_packed, kc, wave, lane); cursor_advance(pf, nseg);
+        t1 = tile_sums(r1);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) t0[u] += dpp_f32<(TG == 2 ? 0x118 : 0x114)>(t1[u]);   // row_shr:8 / row_shr:4
+        if (TG == 2) reduce_group(t0, cur.i);
+        issue_step_loads<BITS>(r1, pf, rs_packed, kc, wave, lane); cursor_advance(pf, nseg);
+        t1 = tile_sums(r2);
+        issue_step_loads<BITS>(r2, pf, rs_packed, kc, wave, lane); cursor_advance(pf, nseg);
+        float4v t3 = tile_sums(r3);
+        if (TG == 2) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) t1[u] += dpp_f32<0x118>(t3[u]);
+            reduce_group(t1, cur.i + 2);
+        } else {
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                float v = (acc0[u] + acc1[u]) * cf[u];
-                v += dpp_f32<kDppQuadXor1>(v);
-                v += dpp_f32<kDppQuadXor2>(v);
-                if (NC == 8) v += dpp_f32<kDppRowHalfMirror>(v);
-                pv[u] = v;
+                t1[u] += dpp_f32<0x114>(t3[u]);
+                t0[u] += dpp_f32<0x118>(t1[u]);
             }
-            if (j == 0) {
-                float4v *slot = reinterpret_cast<float4v *>(&my_part[tl * 16 + 4 * bq]);
-                if (cur.sg > 0) pv += *slot;
-                *slot = pv;
-            }
+            reduce_group(t0, cur.i);
         }
-        ++cur.i;
+        cur.i += 4;
     };
 
     bool first_visit = true;
     while (!cur.done) {
         // ---- visit prologue (the barrier that ended the previous visit protects the LDS reuse)
-        {
+        if (first_visit) {
+            if ((int)threadIdx.x < nf4_first) reinterpret_cast<uint4v *>(cf_lds)[threadIdx.x] = cfv;
+#pragma unroll
+            for (int u = 0; u < XR; ++u) {
+                if (u * NT >= groups) break;          // uniform: this round is empty for every thread
+                const int g = threadIdx.x + u * NT;
+                half8 o;
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    o[e] = smooth_one((uint16_t)(xv[u][e >> 1] >> (16 * (e & 1))), e < 4 ? s0[u][e] : s1[u][e - 4]);
+                if (g < groups) *reinterpret_cast<half8 *>(&xs_lds[8 * g]) = o;
+            }
+            for (int g = threadIdx.x + XR * NT; g < groups; g += NT) {   // larger K only
+                const uint4v xw = __builtin_amdgcn_raw_buffer_load_b128(rs_x, g * 16, 0, 0);
+                const float4v w0 = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(rs_s, g * 32, 0, 0));
+                const float4v w1 = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(rs_s, g * 32 + 16, 0, 0));
+                half8 o;
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    o[e] = smooth_one((uint16_t)(xw[e >> 1] >> (16 * (e & 1))), e < 4 ? w0[e] : w1[e - 4]);
+                *reinterpret_cast<half8 *>(&xs_lds[8 * g]) = o;
+            }
+            // the remaining two sets of the pipeline go out only now, so that the conversion above
+            // is not stuck behind their issue
+            issue_step_loads<BITS>(r1, pf, rs_packed, kc, wave, lane); cursor_advance(pf, nseg);
+            issue_step_loads<BITS>(r2, pf, rs_packed, kc, wave, lane); cursor_advance(pf, nseg);
+            first_visit = false;
+        } else {
             const int nf4 = (cur.v1 - cur.v0) * 4 * NC;   // float4 count of the visit's multipliers
             for (int e = threadIdx.x; e < nf4; e += NT)
                 reinterpret_cast<uint4v *>(cf_lds)[e] = __builtin_amdgcn_raw_buffer_load_b128(rs_lut, ((uint32_t)cur.v0 * 4 * NC + e) * 16, 0, 0);
         }
-        if (first_visit) {
-            for (int g = threadIdx.x; g < groups; g += NT) {
-                if (g >= NT) {
-                    xv = __builtin_amdgcn_raw_buffer_load_b128(rs_x, g * 16, 0, 0);
-                    s0 = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(rs_s, g * 32, 0, 0));
-                    s1 = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(rs_s, g * 32 + 16, 0, 0));
-                }
-                half8 o;
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    o[e] = smooth_one((uint16_t)(xv[e >> 1] >> (16 * (e & 1))), e < 4 ? s0[e] : s1[e - 4]);
-                *reinterpret_cast<half8 *>(&xs_lds[8 * g]) = o;
-            }
-            first_visit = false;
-        }
         LCD_STAMP(2);
         __syncthreads();
         LCD_STAMP(3);
+#pragma unroll
+        for (int b = 0; b < 16; ++b) B1[b] = ((b & 3) == j) ? (_Float16)1.0f : (_Float16)0.0f;
         for (cur.sg = 0; cur.sg < nseg; ++cur.sg) {
 #pragma unroll
             for (int ch = 0; ch < kBCH; ++ch) {
@@ -288,17 +338,14 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const BucketBa
                     uint4v v = {0u, 0u, 0u, 0u};
                     if (chunk < kc) v = *reinterpret_cast<const uint4v *>(&xs_lds[chunk * 256 + 64 * q + 8 * g]);
                     A[ch][g] = v;
-                    if (BITS == 3) nA[ch][g] = v ^ 0x80008000u;
                 }
             }
-            for (cur.i = 0; cur.i < cur.steps;) {
-                step(r0, r3);
-                step(r1, r0);
-                step(r2, r1);
-                step(r3, r2);
-            }
+            for (cur.i = 0; cur.i < cur.steps;) four_steps();
         }
         LCD_STAMP(4);
+#ifdef LCD_TRACE
+        if (lane == 0 && batch.trace && wave < 8) batch.trace[blockIdx.x * 16 + 8 + wave] = __builtin_amdgcn_s_memrealtime();
+#endif
         __syncthreads();
         LCD_STAMP(5);
         // ---- visit epilogue: add the waves' slots in a fixed order, round once, store
@@ -461,12 +508,12 @@ int launch_bucket_group(const GroupItem *items, int count, int bits, void *strea
         p.lutA = (const float *)items[i].lut;
         p.x = items[i].x; p.s = items[i].s; p.y = items[i].y;
         p.nt = items[i].N / kTileRows; p.kc = items[i].K / kTileCols;
-        cost[i] = (long long)p.nt * p.kc;
+        cost[i] = (long long)p.nt * ((p.kc + kBSeg - 1) / kBSeg);   // steps: every row tile takes one step per segment
         total += cost[i];
         tiles += p.nt;
         if (p.kc > kmax) kmax = p.kc;
     }
-    // workgroups per layer: proportional to its packed bytes, at least 1, at most its row tiles
+    // workgroups per layer: proportional to its step count, at least 1, at most its row tiles
     int grid = num_cus();
     if (grid > tiles) grid = tiles;
     if (grid < count) grid = count;
@@ -484,7 +531,7 @@ int launch_bucket_group(const GroupItem *items, int count, int bits, void *strea
         for (int i = 0; i < count; ++i) {
             if (nwg[i] >= batch.p[i].nt) continue;
             // time of a layer ~ its slowest workgroup: ceil(nt / nwg) row tiles of kc chunks
-            const double load = (double)((batch.p[i].nt + nwg[i] - 1) / nwg[i]) * batch.p[i].kc;
+            const double load = (double)((batch.p[i].nt + nwg[i] - 1) / nwg[i]) * ((batch.p[i].kc + kBSeg - 1) / kBSeg);
             if (load > best_load) { best_load = load; best = i; }
         }
         if (best < 0) break;
