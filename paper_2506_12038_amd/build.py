@@ -22,9 +22,14 @@ FLAGS = [
 ]
 
 
+# lcd_gemm.hip keeps its accumulators in fixed AGPRs through inline assembly: the compiler must not
+# use AGPRs as spill space there.
+EXTRA = {"lcd_gemm.hip": ["-mllvm", "-amdgpu-spill-vgpr-to-agpr=0"]}
+
+
 def _compile(src: str, keep_asm: bool) -> Path:
     obj = BUILD / (src.rsplit(".", 1)[0] + ".o")
-    cmd = [HIPCC, *FLAGS, "-c", str(CSRC / src), "-o", str(obj)]
+    cmd = [HIPCC, *FLAGS, *EXTRA.get(src, []), "-c", str(CSRC / src), "-o", str(obj)]
     if keep_asm and src.endswith(".hip"):
         cmd += ["-save-temps=obj"]
     subprocess.check_call(cmd, cwd=str(BUILD), stderr=subprocess.DEVNULL if not os.environ.get("LCD_BUILD_VERBOSE") else None)

@@ -1,179 +1,475 @@
 // Prefill path (M >= 64; any M >= 1 accepted) of the smoothed table-lookup product, gfx950.
 //
-// This path is a dense contraction, so it runs on v_mfma_f32_16x16x32_f16 with fp32
-// accumulators.  Output tile per workgroup: 256 rows x 128 tokens; wave w owns rows
-// [64w, 64w+64) (4 row tiles) and all 128 tokens (8 token tiles): 32 accumulators.
-//   * A operand = weights.  Each lane dequantises its own packed indices in registers
-//     (v_perm_b32 through the row's byte-split codebook), exactly the lane <-> (row, k) mapping
-//     of the packed layout, so weights never pass through LDS.
-//   * B operand = smoothed activations xs = x / s (fp16), prepared once per call by a small
+// This path is a dense contraction, so it runs on v_mfma_f32_32x32x16_f16 with fp32
+// accumulators (the 32x32 shape reaches the matrix peak from a single wave per SIMD; the 16x16
+// shape does not).  Output tile per workgroup: 256 rows x 128 tokens, 8 waves: wave w owns rows
+// [64*(w%4), +64) as two 32-row pairs, all 128 tokens as four 32-token blocks (8 accumulators of
+// 16 registers, held in fixed accumulation registers) and the half w/4 of every 256-column
+// chunk; the two waves of a row group add their accumulators through LDS at the end.  Two
+// waves per SIMD keep the vector pipe (the dequantiser) near its full issue rate, which a single
+// wave cannot reach.
+//   * A operand = weights.  Lane L of the matrix instruction supplies row L%32 and 8 of the
+//     step's 16 columns; it loads its own 16 bytes of the packed layout (row tile = pair's first
+//     tile + (L>>4)&1) and dequantises them in registers (v_perm_b32 through the row's
+//     byte-split codebook), so weights never pass through LDS.
+//   * B operand = smoothed activations xs = x * rcp(s) (fp16), prepared once per call by a small
 //     kernel in MFMA-operand order, so that the slice one workgroup needs per 256-column chunk
 //     is one contiguous 64 KiB block.  It is copied global -> LDS with direct-to-LDS loads,
-//     double buffered, and every wave reads its B operands from LDS (16 bytes per lane,
-//     conflict-free).
-// Each decoded A operand is used for 8 token tiles, each B operand for 4 row tiles.
+//     double buffered; every wave reads its B operands from LDS (16 bytes per lane,
+//     conflict-free) through a 4-register rotating window.
+// Each decoded A operand is used for 4 token blocks, each B operand for 2 row pairs.
 #include <hip/hip_runtime.h>
 #include "lcd_internal.h"
 #include "lcd_device.h"
 
 namespace lcd {
 
-constexpr int kGemmWaves = 4;
-constexpr int kGemmRowTiles = 4;     // per wave
-constexpr int kGemmTokTiles = 8;     // per workgroup (shared by its waves)
-constexpr int kGemmTokens = 16 * kGemmTokTiles;
-constexpr int kStageBytes = kGemmTokTiles * 8 * 1024;  // 64 KiB: 8 token tiles x 8 k-steps x 1 KiB
+constexpr int kXcds = 8;             // accelerator complex dies of the MI355X, each with its own L2
+constexpr int kGemmRowGroups = 4;   // 64-row groups per workgroup
+constexpr int kGemmWaves = 2 * kGemmRowGroups;   // x the two halves of a chunk
+constexpr int kGemmPairs = 2;        // 32-row pairs per wave
+constexpr int kGemmTokBlks = 4;      // 32-token blocks per workgroup (shared by its waves)
+constexpr int kGemmTokens = 32 * kGemmTokBlks;
+constexpr int kStageBytes = kGemmTokBlks * 16 * 1024;  // 64 KiB: 4 token blocks x 16 k-steps x 1 KiB
 
 typedef __attribute__((address_space(3))) uint32_t lds_u32;
 typedef __attribute__((address_space(1))) const uint32_t glb_u32;
 
+// ---- accumulators in fixed accumulation registers ------------------------------------------------
+// The 8 accumulators of a wave (16 registers each) live in a[0:127] and are touched only by the
+// inline assembly below, so the compiler never copies them (as loop-carried values it would move
+// all 128 registers to VGPRs and back in every iteration).  This file is compiled with AGPR
+// spilling disabled, and uses no MFMA builtins, so the compiler itself never allocates an AGPR.
+template <int IDX> __device__ __forceinline__ void mfma_acc(uint4v a, uint4v b);
+template <int IDX> __device__ __forceinline__ float16v read_acc();
+template <> __device__ __forceinline__ void mfma_acc<0>(uint4v a, uint4v b)
+{
+    asm volatile("v_mfma_f32_32x32x16_f16 a[0:15], %0, %1, a[0:15]" : : "v"(a), "v"(b) : "a0", "a1", "a2", "a3", "a4", "a5", "a6", "a7", "a8", "a9", "a10", "a11", "a12", "a13", "a14", "a15");
+}
+template <> __device__ __forceinline__ float16v read_acc<0>()
+{
+    float16v v;
+    float t0, t1, t2, t3, t4, t5, t6, t7, t8, t9, t10, t11, t12, t13, t14, t15;
+    asm volatile("v_accvgpr_read_b32 %0, a0\n\tv_accvgpr_read_b32 %1, a1\n\tv_accvgpr_read_b32 %2, a2\n\tv_accvgpr_read_b32 %3, a3\n\tv_accvgpr_read_b32 %4, a4\n\tv_accvgpr_read_b32 %5, a5\n\tv_accvgpr_read_b32 %6, a6\n\tv_accvgpr_read_b32 %7, a7\n\tv_accvgpr_read_b32 %8, a8\n\tv_accvgpr_read_b32 %9, a9\n\tv_accvgpr_read_b32 %10, a10\n\tv_accvgpr_read_b32 %11, a11\n\tv_accvgpr_read_b32 %12, a12\n\tv_accvgpr_read_b32 %13, a13\n\tv_accvgpr_read_b32 %14, a14\n\tv_accvgpr_read_b32 %15, a15" : "=v"(t0), "=v"(t1), "=v"(t2), "=v"(t3), "=v"(t4), "=v"(t5), "=v"(t6), "=v"(t7), "=v"(t8), "=v"(t9), "=v"(t10), "=v"(t11), "=v"(t12), "=v"(t13), "=v"(t14), "=v"(t15));
+    v[0] = t0;
+    v[1] = t1;
+    v[2] = t2;
+    v[3] = t3;
+    v[4] = t4;
+    v[5] = t5;
+    v[6] = t6;
+    v[7] = t7;
+    v[8] = t8;
+    v[9] = t9;
+    v[10] = t10;
+    v[11] = t11;
+    v[12] = t12;
+    v[13] = t13;
+    v[14] = t14;
+    v[15] = t15;
+    return v;
+}
+template <> __device__ __forceinline__ void mfma_acc<1>(uint4v a, uint4v b)
+{
+    asm volatile("v_mfma_f32_32x32x16_f16 a[16:31], %0, %1, a[16:31]" : : "v"(a), "v"(b) : "a16", "a17", "a18", "a19", "a20", "a21", "a22", "a23", "a24", "a25", "a26", "a27", "a28", "a29", "a30", "a31");
+}
+template <> __device__ __forceinline__ float16v read_acc<1>()
+{
+    float16v v;
+    float t0, t1, t2, t3, t4, t5, t6, t7, t8, t9, t10, t11, t12, t13, t14, t15;
+    asm volatile("v_accvgpr_read_b32 %0, a16\n\tv_accvgpr_read_b32 %1, a17\n\tv_accvgpr_read_b32 %2, a18\n\tv_accvgpr_read_b32 %3, a19\n\tv_accvgpr_read_b32 %4, a20\n\tv_accvgpr_read_b32 %5, a21\n\tv_accvgpr_read_b32 %6, a22\n\tv_accvgpr_read_b32 %7, a23\n\tv_accvgpr_read_b32 %8, a24\n\tv_accvgpr_read_b32 %9, a25\n\tv_accvgpr_read_b32 %10, a26\n\tv_accvgpr_read_b32 %11, a27\n\tv_accvgpr_read_b32 %12, a28\n\tv_accvgpr_read_b32 %13, a29\n\tv_accvgpr_read_b32 %14, a30\n\tv_accvgpr_read_b32 %15, a31" : "=v"(t0), "=v"(t1), "=v"(t2), "=v"(t3), "=v"(t4), "=v"(t5), "=v"(t6), "=v"(t7), "=v"(t8), "=v"(t9), "=v"(t10), "=v"(t11), "=v"(t12), "=v"(t13), "=v"(t14), "=v"(t15));
+    v[0] = t0;
+    v[1] = t1;
+    v[2] = t2;
+    v[3] = t3;
+    v[4] = t4;
+    v[5] = t5;
+    v[6] = t6;
+    v[7] = t7;
+    v[8] = t8;
+    v[9] = t9;
+    v[10] = t10;
+    v[11] = t11;
+    v[12] = t12;
+    v[13] = t13;
+    v[14] = t14;
+    v[15] = t15;
+    return v;
+}
+template <> __device__ __forceinline__ void mfma_acc<2>(uint4v a, uint4v b)
+{
+    asm volatile("v_mfma_f32_32x32x16_f16 a[32:47], %0, %1, a[32:47]" : : "v"(a), "v"(b) : "a32", "a33", "a34", "a35", "a36", "a37", "a38", "a39", "a40", "a41", "a42", "a43", "a44", "a45", "a46", "a47");
+}
+template <> __device__ __forceinline__ float16v read_acc<2>()
+{
+    float16v v;
+    float t0, t1, t2, t3, t4, t5, t6, t7, t8, t9, t10, t11, t12, t13, t14, t15;
+    asm volatile("v_accvgpr_read_b32 %0, a32\n\tv_accvgpr_read_b32 %1, a33\n\tv_accvgpr_read_b32 %2, a34\n\tv_accvgpr_read_b32 %3, a35\n\tv_accvgpr_read_b32 %4, a36\n\tv_accvgpr_read_b32 %5, a37\n\tv_accvgpr_read_b32 %6, a38\n\tv_accvgpr_read_b32 %7, a39\n\tv_accvgpr_read_b32 %8, a40\n\tv_accvgpr_read_b32 %9, a41\n\tv_accvgpr_read_b32 %10, a42\n\tv_accvgpr_read_b32 %11, a43\n\tv_accvgpr_read_b32 %12, a44\n\tv_accvgpr_read_b32 %13, a45\n\tv_accvgpr_read_b32 %14, a46\n\tv_accvgpr_read_b32 %15, a47" : "=v"(t0), "=v"(t1), "=v"(t2), "=v"(t3), "=v"(t4), "=v"(t5), "=v"(t6), "=v"(t7), "=v"(t8), "=v"(t9), "=v"(t10), "=v"(t11), "=v"(t12), "=v"(t13), "=v"(t14), "=v"(t15));
+    v[0] = t0;
+    v[1] = t1;
+    v[2] = t2;
+    v[3] = t3;
+    v[4] = t4;
+    v[5] = t5;
+    v[6] = t6;
+    v[7] = t7;
+    v[8] = t8;
+    v[9] = t9;
+    v[10] = t10;
+    v[11] = t11;
+    v[12] = t12;
+    v[13] = t13;
+    v[14] = t14;
+    v[15] = t15;
+    return v;
+}
+template <> __device__ __forceinline__ void mfma_acc<3>(uint4v a, uint4v b)
+{
+    asm volatile("v_mfma_f32_32x32x16_f16 a[48:63], %0, %1, a[48:63]" : : "v"(a), "v"(b) : "a48", "a49", "a50", "a51", "a52", "a53", "a54", "a55", "a56", "a57", "a58", "a59", "a60", "a61", "a62", "a63");
+}
+template <> __device__ __forceinline__ float16v read_acc<3>()
+{
+    float16v v;
+    float t0, t1, t2, t3, t4, t5, t6, t7, t8, t9, t10, t11, t12, t13, t14, t15;
+    asm volatile("v_accvgpr_read_b32 %0, a48\n\tv_accvgpr_read_b32 %1, a49\n\tv_accvgpr_read_b32 %2, a50\n\tv_accvgpr_read_b32 %3, a51\n\tv_accvgpr_read_b32 %4, a52\n\tv_accvgpr_read_b32 %5, a53\n\tv_accvgpr_read_b32 %6, a54\n\tv_accvgpr_read_b32 %7, a55\n\tv_accvgpr_read_b32 %8, a56\n\tv_accvgpr_read_b32 %9, a57\n\tv_accvgpr_read_b32 %10, a58\n\tv_accvgpr_read_b32 %11, a59\n\tv_accvgpr_read_b32 %12, a60\n\tv_accvgpr_read_b32 %13, a61\n\tv_accvgpr_read_b32 %14, a62\n\tv_accvgpr_read_b32 %15, a63" : "=v"(t0), "=v"(t1), "=v"(t2), "=v"(t3), "=v"(t4), "=v"(t5), "=v"(t6), "=v"(t7), "=v"(t8), "=v"(t9), "=v"(t10), "=v"(t11), "=v"(t12), "=v"(t13), "=v"(t14), "=v"(t15));
+    v[0] = t0;
+    v[1] = t1;
+    v[2] = t2;
+    v[3] = t3;
+    v[4] = t4;
+    v[5] = t5;
+    v[6] = t6;
+    v[7] = t7;
+    v[8] = t8;
+    v[9] = t9;
+    v[10] = t10;
+    v[11] = t11;
+    v[12] = t12;
+    v[13] = t13;
+    v[14] = t14;
+    v[15] = t15;
+    return v;
+}
+template <> __device__ __forceinline__ void mfma_acc<4>(uint4v a, uint4v b)
+{
+    asm volatile("v_mfma_f32_32x32x16_f16 a[64:79], %0, %1, a[64:79]" : : "v"(a), "v"(b) : "a64", "a65", "a66", "a67", "a68", "a69", "a70", "a71", "a72", "a73", "a74", "a75", "a76", "a77", "a78", "a79");
+}
+template <> __device__ __forceinline__ float16v read_acc<4>()
+{
+    float16v v;
+    float t0, t1, t2, t3, t4, t5, t6, t7, t8, t9, t10, t11, t12, t13, t14, t15;
+    asm volatile("v_accvgpr_read_b32 %0, a64\n\tv_accvgpr_read_b32 %1, a65\n\tv_accvgpr_read_b32 %2, a66\n\tv_accvgpr_read_b32 %3, a67\n\tv_accvgpr_read_b32 %4, a68\n\tv_accvgpr_read_b32 %5, a69\n\tv_accvgpr_read_b32 %6, a70\n\tv_accvgpr_read_b32 %7, a71\n\tv_accvgpr_read_b32 %8, a72\n\tv_accvgpr_read_b32 %9, a73\n\tv_accvgpr_read_b32 %10, a74\n\tv_accvgpr_read_b32 %11, a75\n\tv_accvgpr_read_b32 %12, a76\n\tv_accvgpr_read_b32 %13, a77\n\tv_accvgpr_read_b32 %14, a78\n\tv_accvgpr_read_b32 %15, a79" : "=v"(t0), "=v"(t1), "=v"(t2), "=v"(t3), "=v"(t4), "=v"(t5), "=v"(t6), "=v"(t7), "=v"(t8), "=v"(t9), "=v"(t10), "=v"(t11), "=v"(t12), "=v"(t13), "=v"(t14), "=v"(t15));
+    v[0] = t0;
+    v[1] = t1;
+    v[2] = t2;
+    v[3] = t3;
+    v[4] = t4;
+    v[5] = t5;
+    v[6] = t6;
+    v[7] = t7;
+    v[8] = t8;
+    v[9] = t9;
+    v[10] = t10;
+    v[11] = t11;
+    v[12] = t12;
+    v[13] = t13;
+    v[14] = t14;
+    v[15] = t15;
+    return v;
+}
+template <> __device__ __forceinline__ void mfma_acc<5>(uint4v a, uint4v b)
+{
+    asm volatile("v_mfma_f32_32x32x16_f16 a[80:95], %0, %1, a[80:95]" : : "v"(a), "v"(b) : "a80", "a81", "a82", "a83", "a84", "a85", "a86", "a87", "a88", "a89", "a90", "a91", "a92", "a93", "a94", "a95");
+}
+template <> __device__ __forceinline__ float16v read_acc<5>()
+{
+    float16v v;
+    float t0, t1, t2, t3, t4, t5, t6, t7, t8, t9, t10, t11, t12, t13, t14, t15;
+    asm volatile("v_accvgpr_read_b32 %0, a80\n\tv_accvgpr_read_b32 %1, a81\n\tv_accvgpr_read_b32 %2, a82\n\tv_accvgpr_read_b32 %3, a83\n\tv_accvgpr_read_b32 %4, a84\n\tv_accvgpr_read_b32 %5, a85\n\tv_accvgpr_read_b32 %6, a86\n\tv_accvgpr_read_b32 %7, a87\n\tv_accvgpr_read_b32 %8, a88\n\tv_accvgpr_read_b32 %9, a89\n\tv_accvgpr_read_b32 %10, a90\n\tv_accvgpr_read_b32 %11, a91\n\tv_accvgpr_read_b32 %12, a92\n\tv_accvgpr_read_b32 %13, a93\n\tv_accvgpr_read_b32 %14, a94\n\tv_accvgpr_read_b32 %15, a95" : "=v"(t0), "=v"(t1), "=v"(t2), "=v"(t3), "=v"(t4), "=v"(t5), "=v"(t6), "=v"(t7), "=v"(t8), "=v"(t9), "=v"(t10), "=v"(t11), "=v"(t12), "=v"(t13), "=v"(t14), "=v"(t15));
+    v[0] = t0;
+    v[1] = t1;
+    v[2] = t2;
+    v[3] = t3;
+    v[4] = t4;
+    v[5] = t5;
+    v[6] = t6;
+    v[7] = t7;
+    v[8] = t8;
+    v[9] = t9;
+    v[10] = t10;
+    v[11] = t11;
+    v[12] = t12;
+    v[13] = t13;
+    v[14] = t14;
+    v[15] = t15;
+    return v;
+}
+template <> __device__ __forceinline__ void mfma_acc<6>(uint4v a, uint4v b)
+{
+    asm volatile("v_mfma_f32_32x32x16_f16 a[96:111], %0, %1, a[96:111]" : : "v"(a), "v"(b) : "a96", "a97", "a98", "a99", "a100", "a101", "a102", "a103", "a104", "a105", "a106", "a107", "a108", "a109", "a110", "a111");
+}
+template <> __device__ __forceinline__ float16v read_acc<6>()
+{
+    float16v v;
+    float t0, t1, t2, t3, t4, t5, t6, t7, t8, t9, t10, t11, t12, t13, t14, t15;
+    asm volatile("v_accvgpr_read_b32 %0, a96\n\tv_accvgpr_read_b32 %1, a97\n\tv_accvgpr_read_b32 %2, a98\n\tv_accvgpr_read_b32 %3, a99\n\tv_accvgpr_read_b32 %4, a100\n\tv_accvgpr_read_b32 %5, a101\n\tv_accvgpr_read_b32 %6, a102\n\tv_accvgpr_read_b32 %7, a103\n\tv_accvgpr_read_b32 %8, a104\n\tv_accvgpr_read_b32 %9, a105\n\tv_accvgpr_read_b32 %10, a106\n\tv_accvgpr_read_b32 %11, a107\n\tv_accvgpr_read_b32 %12, a108\n\tv_accvgpr_read_b32 %13, a109\n\tv_accvgpr_read_b32 %14, a110\n\tv_accvgpr_read_b32 %15, a111" : "=v"(t0), "=v"(t1), "=v"(t2), "=v"(t3), "=v"(t4), "=v"(t5), "=v"(t6), "=v"(t7), "=v"(t8), "=v"(t9), "=v"(t10), "=v"(t11), "=v"(t12), "=v"(t13), "=v"(t14), "=v"(t15));
+    v[0] = t0;
+    v[1] = t1;
+    v[2] = t2;
+    v[3] = t3;
+    v[4] = t4;
+    v[5] = t5;
+    v[6] = t6;
+    v[7] = t7;
+    v[8] = t8;
+    v[9] = t9;
+    v[10] = t10;
+    v[11] = t11;
+    v[12] = t12;
+    v[13] = t13;
+    v[14] = t14;
+    v[15] = t15;
+    return v;
+}
+template <> __device__ __forceinline__ void mfma_acc<7>(uint4v a, uint4v b)
+{
+    asm volatile("v_mfma_f32_32x32x16_f16 a[112:127], %0, %1, a[112:127]" : : "v"(a), "v"(b) : "a112", "a113", "a114", "a115", "a116", "a117", "a118", "a119", "a120", "a121", "a122", "a123", "a124", "a125", "a126", "a127");
+}
+template <> __device__ __forceinline__ float16v read_acc<7>()
+{
+    float16v v;
+    float t0, t1, t2, t3, t4, t5, t6, t7, t8, t9, t10, t11, t12, t13, t14, t15;
+    asm volatile("v_accvgpr_read_b32 %0, a112\n\tv_accvgpr_read_b32 %1, a113\n\tv_accvgpr_read_b32 %2, a114\n\tv_accvgpr_read_b32 %3, a115\n\tv_accvgpr_read_b32 %4, a116\n\tv_accvgpr_read_b32 %5, a117\n\tv_accvgpr_read_b32 %6, a118\n\tv_accvgpr_read_b32 %7, a119\n\tv_accvgpr_read_b32 %8, a120\n\tv_accvgpr_read_b32 %9, a121\n\tv_accvgpr_read_b32 %10, a122\n\tv_accvgpr_read_b32 %11, a123\n\tv_accvgpr_read_b32 %12, a124\n\tv_accvgpr_read_b32 %13, a125\n\tv_accvgpr_read_b32 %14, a126\n\tv_accvgpr_read_b32 %15, a127" : "=v"(t0), "=v"(t1), "=v"(t2), "=v"(t3), "=v"(t4), "=v"(t5), "=v"(t6), "=v"(t7), "=v"(t8), "=v"(t9), "=v"(t10), "=v"(t11), "=v"(t12), "=v"(t13), "=v"(t14), "=v"(t15));
+    v[0] = t0;
+    v[1] = t1;
+    v[2] = t2;
+    v[3] = t3;
+    v[4] = t4;
+    v[5] = t5;
+    v[6] = t6;
+    v[7] = t7;
+    v[8] = t8;
+    v[9] = t9;
+    v[10] = t10;
+    v[11] = t11;
+    v[12] = t12;
+    v[13] = t13;
+    v[14] = t14;
+    v[15] = t15;
+    return v;
+}
+__device__ __forceinline__ void zero_accs()
+{
+    asm volatile("v_accvgpr_write_b32 a0, 0\n\tv_accvgpr_write_b32 a1, 0\n\tv_accvgpr_write_b32 a2, 0\n\tv_accvgpr_write_b32 a3, 0\n\tv_accvgpr_write_b32 a4, 0\n\tv_accvgpr_write_b32 a5, 0\n\tv_accvgpr_write_b32 a6, 0\n\tv_accvgpr_write_b32 a7, 0\n\tv_accvgpr_write_b32 a8, 0\n\tv_accvgpr_write_b32 a9, 0\n\tv_accvgpr_write_b32 a10, 0\n\tv_accvgpr_write_b32 a11, 0\n\tv_accvgpr_write_b32 a12, 0\n\tv_accvgpr_write_b32 a13, 0\n\tv_accvgpr_write_b32 a14, 0\n\tv_accvgpr_write_b32 a15, 0" : : : "a0", "a1", "a2", "a3", "a4", "a5", "a6", "a7", "a8", "a9", "a10", "a11", "a12", "a13", "a14", "a15");
+    asm volatile("v_accvgpr_write_b32 a16, 0\n\tv_accvgpr_write_b32 a17, 0\n\tv_accvgpr_write_b32 a18, 0\n\tv_accvgpr_write_b32 a19, 0\n\tv_accvgpr_write_b32 a20, 0\n\tv_accvgpr_write_b32 a21, 0\n\tv_accvgpr_write_b32 a22, 0\n\tv_accvgpr_write_b32 a23, 0\n\tv_accvgpr_write_b32 a24, 0\n\tv_accvgpr_write_b32 a25, 0\n\tv_accvgpr_write_b32 a26, 0\n\tv_accvgpr_write_b32 a27, 0\n\tv_accvgpr_write_b32 a28, 0\n\tv_accvgpr_write_b32 a29, 0\n\tv_accvgpr_write_b32 a30, 0\n\tv_accvgpr_write_b32 a31, 0" : : : "a16", "a17", "a18", "a19", "a20", "a21", "a22", "a23", "a24", "a25", "a26", "a27", "a28", "a29", "a30", "a31");
+    asm volatile("v_accvgpr_write_b32 a32, 0\n\tv_accvgpr_write_b32 a33, 0\n\tv_accvgpr_write_b32 a34, 0\n\tv_accvgpr_write_b32 a35, 0\n\tv_accvgpr_write_b32 a36, 0\n\tv_accvgpr_write_b32 a37, 0\n\tv_accvgpr_write_b32 a38, 0\n\tv_accvgpr_write_b32 a39, 0\n\tv_accvgpr_write_b32 a40, 0\n\tv_accvgpr_write_b32 a41, 0\n\tv_accvgpr_write_b32 a42, 0\n\tv_accvgpr_write_b32 a43, 0\n\tv_accvgpr_write_b32 a44, 0\n\tv_accvgpr_write_b32 a45, 0\n\tv_accvgpr_write_b32 a46, 0\n\tv_accvgpr_write_b32 a47, 0" : : : "a32", "a33", "a34", "a35", "a36", "a37", "a38", "a39", "a40", "a41", "a42", "a43", "a44", "a45", "a46", "a47");
+    asm volatile("v_accvgpr_write_b32 a48, 0\n\tv_accvgpr_write_b32 a49, 0\n\tv_accvgpr_write_b32 a50, 0\n\tv_accvgpr_write_b32 a51, 0\n\tv_accvgpr_write_b32 a52, 0\n\tv_accvgpr_write_b32 a53, 0\n\tv_accvgpr_write_b32 a54, 0\n\tv_accvgpr_write_b32 a55, 0\n\tv_accvgpr_write_b32 a56, 0\n\tv_accvgpr_write_b32 a57, 0\n\tv_accvgpr_write_b32 a58, 0\n\tv_accvgpr_write_b32 a59, 0\n\tv_accvgpr_write_b32 a60, 0\n\tv_accvgpr_write_b32 a61, 0\n\tv_accvgpr_write_b32 a62, 0\n\tv_accvgpr_write_b32 a63, 0" : : : "a48", "a49", "a50", "a51", "a52", "a53", "a54", "a55", "a56", "a57", "a58", "a59", "a60", "a61", "a62", "a63");
+    asm volatile("v_accvgpr_write_b32 a64, 0\n\tv_accvgpr_write_b32 a65, 0\n\tv_accvgpr_write_b32 a66, 0\n\tv_accvgpr_write_b32 a67, 0\n\tv_accvgpr_write_b32 a68, 0\n\tv_accvgpr_write_b32 a69, 0\n\tv_accvgpr_write_b32 a70, 0\n\tv_accvgpr_write_b32 a71, 0\n\tv_accvgpr_write_b32 a72, 0\n\tv_accvgpr_write_b32 a73, 0\n\tv_accvgpr_write_b32 a74, 0\n\tv_accvgpr_write_b32 a75, 0\n\tv_accvgpr_write_b32 a76, 0\n\tv_accvgpr_write_b32 a77, 0\n\tv_accvgpr_write_b32 a78, 0\n\tv_accvgpr_write_b32 a79, 0" : : : "a64", "a65", "a66", "a67", "a68", "a69", "a70", "a71", "a72", "a73", "a74", "a75", "a76", "a77", "a78", "a79");
+    asm volatile("v_accvgpr_write_b32 a80, 0\n\tv_accvgpr_write_b32 a81, 0\n\tv_accvgpr_write_b32 a82, 0\n\tv_accvgpr_write_b32 a83, 0\n\tv_accvgpr_write_b32 a84, 0\n\tv_accvgpr_write_b32 a85, 0\n\tv_accvgpr_write_b32 a86, 0\n\tv_accvgpr_write_b32 a87, 0\n\tv_accvgpr_write_b32 a88, 0\n\tv_accvgpr_write_b32 a89, 0\n\tv_accvgpr_write_b32 a90, 0\n\tv_accvgpr_write_b32 a91, 0\n\tv_accvgpr_write_b32 a92, 0\n\tv_accvgpr_write_b32 a93, 0\n\tv_accvgpr_write_b32 a94, 0\n\tv_accvgpr_write_b32 a95, 0" : : : "a80", "a81", "a82", "a83", "a84", "a85", "a86", "a87", "a88", "a89", "a90", "a91", "a92", "a93", "a94", "a95");
+    asm volatile("v_accvgpr_write_b32 a96, 0\n\tv_accvgpr_write_b32 a97, 0\n\tv_accvgpr_write_b32 a98, 0\n\tv_accvgpr_write_b32 a99, 0\n\tv_accvgpr_write_b32 a100, 0\n\tv_accvgpr_write_b32 a101, 0\n\tv_accvgpr_write_b32 a102, 0\n\tv_accvgpr_write_b32 a103, 0\n\tv_accvgpr_write_b32 a104, 0\n\tv_accvgpr_write_b32 a105, 0\n\tv_accvgpr_write_b32 a106, 0\n\tv_accvgpr_write_b32 a107, 0\n\tv_accvgpr_write_b32 a108, 0\n\tv_accvgpr_write_b32 a109, 0\n\tv_accvgpr_write_b32 a110, 0\n\tv_accvgpr_write_b32 a111, 0" : : : "a96", "a97", "a98", "a99", "a100", "a101", "a102", "a103", "a104", "a105", "a106", "a107", "a108", "a109", "a110", "a111");
+    asm volatile("v_accvgpr_write_b32 a112, 0\n\tv_accvgpr_write_b32 a113, 0\n\tv_accvgpr_write_b32 a114, 0\n\tv_accvgpr_write_b32 a115, 0\n\tv_accvgpr_write_b32 a116, 0\n\tv_accvgpr_write_b32 a117, 0\n\tv_accvgpr_write_b32 a118, 0\n\tv_accvgpr_write_b32 a119, 0\n\tv_accvgpr_write_b32 a120, 0\n\tv_accvgpr_write_b32 a121, 0\n\tv_accvgpr_write_b32 a122, 0\n\tv_accvgpr_write_b32 a123, 0\n\tv_accvgpr_write_b32 a124, 0\n\tv_accvgpr_write_b32 a125, 0\n\tv_accvgpr_write_b32 a126, 0\n\tv_accvgpr_write_b32 a127, 0" : : : "a112", "a113", "a114", "a115", "a116", "a117", "a118", "a119", "a120", "a121", "a122", "a123", "a124", "a125", "a126", "a127");
+}
+
+// One lane's packed words of a chunk half: per pair, the lane's row and the 64 columns
+// [64*(2*half + L>>5), +64) of the chunk.
 template <int BITS>
 struct GemmTileRegs {
-    uint4v lo[kGemmRowTiles];
-    uint2v hi[kGemmRowTiles];
+    uint4v lo[kGemmPairs];
+    uint2v hi[kGemmPairs];
 };
 
 template <int BITS>
-__device__ __forceinline__ void load_gemm_tiles(GemmTileRegs<BITS> &r, const uint8_t *__restrict__ packed, int t0, int nt,
-                                                int kc, int c, int lane)
+__device__ __forceinline__ void load_gemm_tiles(GemmTileRegs<BITS> &r, __amdgpu_buffer_rsrc_t packed, int t0, int nt,
+                                                int kc, int c, int h, int lane)
 {
-    constexpr size_t TB = BITS == 2 ? 1024 : 1536;
+    constexpr uint32_t TB = BITS == 2 ? 1024 : 1536;
+    const int sub = (lane >> 4) & 1, kh = lane >> 5, i = lane & 15;
 #pragma unroll
-    for (int rt = 0; rt < kGemmRowTiles; ++rt) {
-        if (t0 + rt < nt) {
-            const uint8_t *base = packed + ((size_t)(t0 + rt) * kc + c) * TB;
-            r.lo[rt] = *reinterpret_cast<const uint4v *>(base + 16 * lane);
-            if (BITS == 3) r.hi[rt] = *reinterpret_cast<const uint2v *>(base + 1024 + 8 * lane);
-        } else {
-            r.lo[rt] = uint4v{0u, 0u, 0u, 0u};
-            r.hi[rt] = uint2v{0u, 0u};
-        }
+    for (int p = 0; p < kGemmPairs; ++p) {
+        const int tile = t0 + 2 * p + sub;
+        const uint32_t base = ((uint32_t)tile * (uint32_t)kc + (uint32_t)c) * TB;
+        const int slot = 16 * (2 * h + kh) + i;          // lane slot inside the 16 x 256 tile
+        const bool v = tile < nt;
+        r.lo[p] = __builtin_amdgcn_raw_buffer_load_b128(packed, v ? base + 16 * slot : 0xFFFFFFF0u, 0, 0);
+        if (BITS == 3) r.hi[p] = __builtin_amdgcn_raw_buffer_load_b64(packed, v ? base + 1024 + 8 * slot : 0xFFFFFFF0u, 0, 0);
     }
 }
 
-// copy one 64 KiB stage: every wave copies 16 KiB as 16 wave-wide 1 KiB direct-to-LDS loads
+// copy one 64 KiB stage: every wave copies 8 KiB as 8 wave-wide 1 KiB direct-to-LDS loads
 __device__ __forceinline__ void stage_copy(const uint8_t *__restrict__ src, uint8_t *lds_dst, int wave, int lane)
 {
 #pragma unroll
-    for (int u = 0; u < 16; ++u) {
-        const int blk = wave * 16 + u;  // 1 KiB block index inside the stage
+    for (int u = 0; u < 8; ++u) {
+        const int blk = wave * 8 + u;  // 1 KiB block index inside the stage
         __builtin_amdgcn_global_load_lds((glb_u32 *)(src + (size_t)blk * 1024 + lane * 16),
                                          (lds_u32 *)(lds_dst + blk * 1024), 16, 0, 0);
     }
 }
 
-template <int BITS, int D>
-__device__ __forceinline__ void gemm_word(const GemmTileRegs<BITS> &r, const HighBits (&hb)[kGemmRowTiles],
-                                          const RowTables (&tb)[kGemmRowTiles], const uint8_t *stage, int boff,
-                                          float4v (&acc)[kGemmRowTiles][kGemmTokTiles])
+// B operands (16 bytes per lane) rotate through a window of four registers: the read for
+// matrix step s+3 is issued while step s computes, which covers the LDS latency with one wave
+// per SIMD.  A stage holds blocks [token block 4][half 2][k-step 8] of 1 KiB.
+struct BWindow { uint4v w[4]; };
+
+__device__ __forceinline__ uint4v read_b(const uint8_t *stage, int h, int g, int tb, int boff)
 {
-    uint4v op[kGemmRowTiles][2];
+    return *reinterpret_cast<const uint4v *>(stage + ((tb * 2 + h) * 8 + g) * 1024 + boff);
+}
+
+// One packed word per pair (16 weights per lane) = two k-steps x 4 token blocks = 8 matrix steps
+// of 2 MFMAs.  On entry the window holds steps 0..2 of this word; on exit steps 0..2 of the
+// next word (the next chunk's first word, from `next_stage`, after the last word of a chunk).
+template <int BITS, int D>
+__device__ __forceinline__ void gemm_word(const GemmTileRegs<BITS> &r, const HighBits (&hb)[kGemmPairs],
+                                          const RowTables (&tb)[kGemmPairs], const uint8_t *stage,
+                                          const uint8_t *next_stage, int h, int boff, BWindow &bw)
+{
+    uint4v op[kGemmPairs][2];
 #pragma unroll
-    for (int rt = 0; rt < kGemmRowTiles; ++rt) decode_word<BITS, D>(r.lo[rt][D], hb[rt], tb[rt], op[rt][0], op[rt][1]);
-#pragma unroll
-    for (int a = 0; a < 2; ++a) {
-        const int g = 2 * D + a;
-#pragma unroll
-        for (int mt = 0; mt < kGemmTokTiles; ++mt) {
-            const uint4v b = *reinterpret_cast<const uint4v *>(stage + (mt * 8 + g) * 1024 + boff);
-#pragma unroll
-            for (int rt = 0; rt < kGemmRowTiles; ++rt)
-                acc[rt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(op[rt][a]), as_half8(b), acc[rt][mt], 0, 0, 0);
-        }
+    for (int p = 0; p < kGemmPairs; ++p) decode_word<BITS, D>(r.lo[p][D], hb[p], tb[p], op[p][0], op[p][1]);
+    __builtin_amdgcn_sched_barrier(0);
+#define LCD_GEMM_STEP(ST)                                                                                   \
+    {                                                                                                       \
+        constexpr int st = ST, a = st >> 2, blk = st & 3, nx = st + 3;                                      \
+        /* prefetch step st+3 into the slot that step st-1 used */                                          \
+        if (nx < 8) bw.w[nx & 3] = read_b(stage, h, 2 * D + (nx >> 2), nx & 3, boff);                       \
+        else if (D < 3) bw.w[nx & 3] = read_b(stage, h, 2 * D + 2, nx - 8, boff);                           \
+        else if (next_stage) bw.w[nx & 3] = read_b(next_stage, h, 0, nx - 8, boff);                         \
+        mfma_acc<blk>(op[0][a], bw.w[st & 3]);                                                              \
+        mfma_acc<4 + blk>(op[1][a], bw.w[st & 3]);                                                          \
+        __builtin_amdgcn_sched_barrier(0);                                                                  \
     }
+    LCD_GEMM_STEP(0) LCD_GEMM_STEP(1) LCD_GEMM_STEP(2) LCD_GEMM_STEP(3)
+    LCD_GEMM_STEP(4) LCD_GEMM_STEP(5) LCD_GEMM_STEP(6) LCD_GEMM_STEP(7)
+#undef LCD_GEMM_STEP
 }
 
 template <int BITS>
 __global__ void __launch_bounds__(kGemmWaves * 64, 1)
-gemm_kernel(const uint8_t *__restrict__ packed, const uint8_t *__restrict__ lutB, const uint8_t *__restrict__ xs,
-            uint16_t *__restrict__ y, int M, int Mpad, int N, int K)
+gemm_kernel(const uint8_t *__restrict__ packed_, const uint8_t *__restrict__ lutB, const uint8_t *__restrict__ xs,
+            uint16_t *__restrict__ y, int M, int Mpad, int N, int K, int grid_rows, int tiles_per_xcd)
 {
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];  // 2 stages x 64 KiB
+    constexpr uint32_t TB = BITS == 2 ? 1024 : 1536;
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int q = lane >> 4, j = lane & 15, bq = lane >> 4;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: keeps addresses scalar
     const int kc = K / kTileCols, nt = N / kTileRows;
-    const int t0 = (blockIdx.x * kGemmWaves + wave) * kGemmRowTiles;   // first row tile of this wave
-    const int mt0 = blockIdx.y * kGemmTokTiles;                        // first token tile of this workgroup
-    const int boff = (j * 4 + q) * 16;                                  // lane's 16 bytes inside a 1 KiB operand block
+    // XCD-aware tile order.  Workgroup ids go round-robin over the 8 XCDs, each with its own L2.
+    // Output tiles are numbered token-block-major and cut into 8 contiguous runs, one per XCD, so
+    // the workgroups that are resident on an XCD at the same time share one or two 128-token
+    // blocks of activations (1 MiB each at K = 4096), which then stay in that XCD's 4 MiB L2.
+    const int out_tile = (int)(blockIdx.x % kXcds) * tiles_per_xcd + (int)(blockIdx.x / kXcds);
+    const int total_tiles = grid_rows * (Mpad / kGemmTokens);
+    if ((int)(blockIdx.x / kXcds) >= tiles_per_xcd || out_tile >= total_tiles) return;
+    const int bx = out_tile % grid_rows, by = out_tile / grid_rows;
+    const int rgrp = wave & (kGemmRowGroups - 1), khalf = wave >> 2;     // row group and chunk half of this wave
+    const int t0 = (bx * kGemmRowGroups + rgrp) * (2 * kGemmPairs);      // first row tile of this wave
+    const int tb0 = by * kGemmTokBlks;                                   // first 32-token block of this workgroup
+    const int boff = lane * 16;                                           // lane's 16 bytes inside a 1 KiB operand block
+    const __amdgpu_buffer_rsrc_t packed = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(packed_), 0, (uint32_t)nt * (uint32_t)kc * TB, 0x00020000);
 
     // activations of chunk c for this workgroup's 128 tokens: one contiguous 64 KiB block
-    const size_t chunk_stride = (size_t)(Mpad >> 4) * 8 * 1024;
-    const uint8_t *xs_base = xs + (size_t)mt0 * 8 * 1024;
+    const size_t chunk_stride = (size_t)(Mpad >> 5) * 16 * 1024;
+    const uint8_t *xs_base = xs + (size_t)tb0 * 16 * 1024;
 
-    RowTables tb[kGemmRowTiles];
+    // this lane's row in each pair, and its byte-split codebook
+    RowTables tb[kGemmPairs];
 #pragma unroll
-    for (int rt = 0; rt < kGemmRowTiles; ++rt) {
-        const int row = min((t0 + rt), nt - 1) * kTileRows + (lane & 15);
+    for (int p = 0; p < kGemmPairs; ++p) {
+        const int tile = min(t0 + 2 * p + ((lane >> 4) & 1), nt - 1);
+        const int row = tile * kTileRows + (lane & 15);
         if (BITS == 2) {
             const uint2v v = *reinterpret_cast<const uint2v *>(lutB + (size_t)row * 8);
-            tb[rt].lo[0] = v[0]; tb[rt].hi[0] = v[1]; tb[rt].lo[1] = 0; tb[rt].hi[1] = 0;
+            tb[p].lo[0] = v[0]; tb[p].hi[0] = v[1]; tb[p].lo[1] = 0; tb[p].hi[1] = 0;
         } else {
             const uint4v v = *reinterpret_cast<const uint4v *>(lutB + (size_t)row * 16);
-            tb[rt].lo[0] = v[0]; tb[rt].lo[1] = v[1]; tb[rt].hi[0] = v[2]; tb[rt].hi[1] = v[3];
+            tb[p].lo[0] = v[0]; tb[p].lo[1] = v[1]; tb[p].hi[0] = v[2]; tb[p].hi[1] = v[3];
         }
     }
-
-    float4v acc[kGemmRowTiles][kGemmTokTiles];
-#pragma unroll
-    for (int rt = 0; rt < kGemmRowTiles; ++rt)
-#pragma unroll
-        for (int mt = 0; mt < kGemmTokTiles; ++mt) acc[rt][mt] = float4v{0.f, 0.f, 0.f, 0.f};
+    zero_accs();
 
     GemmTileRegs<BITS> r0, r1;
-    load_gemm_tiles<BITS>(r0, packed, t0, nt, kc, 0, lane);
+    load_gemm_tiles<BITS>(r0, packed, t0, nt, kc, 0, khalf, lane);
     stage_copy(xs_base, lds, wave, lane);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
-    auto compute = [&](const GemmTileRegs<BITS> &r, const uint8_t *stage) {
-        HighBits hb[kGemmRowTiles];
+    BWindow bw;
+    // Chunk c is computed from LDS stage c&1.  Its last word prefetches the first B operands of
+    // chunk c+1 from the other stage, so that stage must be resident before the last word: the
+    // wait + barrier for chunk c+1's copy sits just before it.
+    auto compute = [&](const GemmTileRegs<BITS> &r, const uint8_t *stage, const uint8_t *next_stage) {
+        HighBits hb[kGemmPairs];
 #pragma unroll
-        for (int rt = 0; rt < kGemmRowTiles; ++rt) {
-            hb[rt] = HighBits{0u, 0u};
-            if (BITS == 3) hb[rt] = regroup_high(r.hi[rt]);
+        for (int p = 0; p < kGemmPairs; ++p) {
+            hb[p] = HighBits{0u, 0u};
+            if (BITS == 3) hb[p] = regroup_high(r.hi[p]);
         }
-        gemm_word<BITS, 0>(r, hb, tb, stage, boff, acc);
-        gemm_word<BITS, 1>(r, hb, tb, stage, boff, acc);
-        gemm_word<BITS, 2>(r, hb, tb, stage, boff, acc);
-        gemm_word<BITS, 3>(r, hb, tb, stage, boff, acc);
+        gemm_word<BITS, 0>(r, hb, tb, stage, next_stage, khalf, boff, bw);
+        gemm_word<BITS, 1>(r, hb, tb, stage, next_stage, khalf, boff, bw);
+        gemm_word<BITS, 2>(r, hb, tb, stage, next_stage, khalf, boff, bw);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();   // next chunk's stage (and packed words) have landed for every wave
+        gemm_word<BITS, 3>(r, hb, tb, stage, next_stage, khalf, boff, bw);
     };
 
+    bw.w[0] = read_b(lds, khalf, 0, 0, boff);
+    bw.w[1] = read_b(lds, khalf, 0, 1, boff);
+    bw.w[2] = read_b(lds, khalf, 0, 2, boff);
     for (int c = 0; c < kc; c += 2) {
         // even chunk: compute from stage 0 / r0 while chunk c+1 lands in stage 1 / r1
-        if (c + 1 < kc) {
-            load_gemm_tiles<BITS>(r1, packed, t0, nt, kc, c + 1, lane);
+        const bool more1 = c + 1 < kc;
+        if (more1) {
+            load_gemm_tiles<BITS>(r1, packed, t0, nt, kc, c + 1, khalf, lane);
             stage_copy(xs_base + (size_t)(c + 1) * chunk_stride, lds + kStageBytes, wave, lane);
         }
-        compute(r0, lds);
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-        if (c + 1 >= kc) break;
-        if (c + 2 < kc) {
-            load_gemm_tiles<BITS>(r0, packed, t0, nt, kc, c + 2, lane);
+        compute(r0, lds, more1 ? lds + kStageBytes : nullptr);
+        __syncthreads();   // every wave is done reading stage 0 before it is overwritten
+        if (!more1) break;
+        const bool more2 = c + 2 < kc;
+        if (more2) {
+            load_gemm_tiles<BITS>(r0, packed, t0, nt, kc, c + 2, khalf, lane);
             stage_copy(xs_base + (size_t)(c + 2) * chunk_stride, lds, wave, lane);
         }
-        compute(r1, lds + kStageBytes);
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        compute(r1, lds + kStageBytes, more2 ? lds : nullptr);
         __syncthreads();
     }
 
-    // store: lane (bq, j) holds rows 4bq..4bq+3 of token 16*mt + j
+    // The wave that owns the second half of the chunks hands its accumulators to its partner
+    // through LDS (the stages are free now): [row group][accumulator 8][register quad 4][lane] float4.
+    float4v *xchg = reinterpret_cast<float4v *>(lds) + (size_t)rgrp * (8 * 4 * 64);
+    auto put_acc = [&](const float16v &v, int idx) {
 #pragma unroll
-    for (int rt = 0; rt < kGemmRowTiles; ++rt) {
-        if (t0 + rt >= nt) continue;
+        for (int rg = 0; rg < 4; ++rg) xchg[(idx * 4 + rg) * 64 + lane] = float4v{v[4 * rg], v[4 * rg + 1], v[4 * rg + 2], v[4 * rg + 3]};
+    };
+    if (khalf == 1) {
+        put_acc(read_acc<0>(), 0); put_acc(read_acc<1>(), 1); put_acc(read_acc<2>(), 2); put_acc(read_acc<3>(), 3);
+        put_acc(read_acc<4>(), 4); put_acc(read_acc<5>(), 5); put_acc(read_acc<6>(), 6); put_acc(read_acc<7>(), 7);
+    }
+    __syncthreads();
+    if (khalf == 1) return;
+
+    // store: accumulator register r of lane l is row 8*(r/4) + 4*(l/32) + r%4 of the pair, token l%32
+    const int tok = lane & 31, lh = lane >> 5;
+    auto store_acc = [&](const float16v &own, int p, int b) {
+        const int m = (tb0 + b) * 32 + tok;
 #pragma unroll
-        for (int mt = 0; mt < kGemmTokTiles; ++mt) {
-            const int m = (mt0 + mt) * 16 + j;
-            if (m < M) {
+        for (int rg = 0; rg < 4; ++rg) {
+            const float4v other = xchg[((p * 4 + b) * 4 + rg) * 64 + lane];
+            const int row_in_pair = 8 * rg + 4 * lh;
+            const int tile = t0 + 2 * p + (row_in_pair >> 4);
+            if (m < M && tile < nt) {
                 typedef _Float16 half4 __attribute__((ext_vector_type(4)));
                 half4 o;
 #pragma unroll
-                for (int u = 0; u < 4; ++u) o[u] = (_Float16)acc[rt][mt][u];
-                *reinterpret_cast<half4 *>(y + (size_t)m * N + (size_t)(t0 + rt) * kTileRows + 4 * bq) = o;
+                for (int u = 0; u < 4; ++u) o[u] = (_Float16)(own[4 * rg + u] + other[u]);
+                *reinterpret_cast<half4 *>(y + (size_t)m * N + (size_t)(t0 + 2 * p) * kTileRows + row_in_pair) = o;
             }
         }
-    }
+    };
+    store_acc(read_acc<0>(), 0, 0); store_acc(read_acc<1>(), 0, 1); store_acc(read_acc<2>(), 0, 2); store_acc(read_acc<3>(), 0, 3);
+    store_acc(read_acc<4>(), 1, 0); store_acc(read_acc<5>(), 1, 1); store_acc(read_acc<6>(), 1, 2); store_acc(read_acc<7>(), 1, 3);
 }
 
 int launch_gemm(const void *packed, const void *lut, const uint16_t *x, const float *s, uint16_t *y,
@@ -184,8 +480,11 @@ int launch_gemm(const void *packed, const void *lut, const uint16_t *x, const fl
     if (int e = launch_smooth(x, s, workspace, M, Mpad, K, 1, stream)) return e;
     const uint8_t *lutB = static_cast<const uint8_t *>(lut) + (size_t)N * (bits == 2 ? 4 : 8) * 4;
     const int nt = N / kTileRows;
-    const int rows_per_wg = kGemmWaves * kGemmRowTiles;
-    const dim3 grid((nt + rows_per_wg - 1) / rows_per_wg, Mpad / kGemmTokens), block(kGemmWaves * 64);
+    const int tiles_per_wg = kGemmRowGroups * 2 * kGemmPairs;
+    const int grid_rows = (nt + tiles_per_wg - 1) / tiles_per_wg;
+    const int total_tiles = grid_rows * (Mpad / kGemmTokens);
+    const int tiles_per_xcd = (total_tiles + kXcds - 1) / kXcds;
+    const dim3 grid(tiles_per_xcd * kXcds), block(kGemmWaves * 64);
     const size_t lds_bytes = 2 * kStageBytes;
     static bool attr_set[2] = {false, false};
     if (bits == 2) {
@@ -194,14 +493,14 @@ int launch_gemm(const void *packed, const void *lut, const uint16_t *x, const fl
             attr_set[0] = true;
         }
         hipLaunchKernelGGL(gemm_kernel<2>, grid, block, lds_bytes, stream, (const uint8_t *)packed, lutB,
-                           (const uint8_t *)workspace, y, M, Mpad, N, K);
+                           (const uint8_t *)workspace, y, M, Mpad, N, K, grid_rows, tiles_per_xcd);
     } else {
         if (!attr_set[1]) {
             if (hipError_t e = hipFuncSetAttribute((const void *)gemm_kernel<3>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes)) return (int)e;
             attr_set[1] = true;
         }
         hipLaunchKernelGGL(gemm_kernel<3>, grid, block, lds_bytes, stream, (const uint8_t *)packed, lutB,
-                           (const uint8_t *)workspace, y, M, Mpad, N, K);
+                           (const uint8_t *)workspace, y, M, Mpad, N, K, grid_rows, tiles_per_xcd);
     }
     return (int)hipGetLastError();
 }

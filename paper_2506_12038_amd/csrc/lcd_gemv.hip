@@ -153,7 +153,8 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const BucketBa
     float *cf_lds = reinterpret_cast<float *>(smem + (size_t)batch.kc_max * kTileCols * 2);
     float *part = cf_lds + kVisitTiles * 16 * NC;
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: keeps addresses scalar
     const int q = lane >> 4, j = lane & 15, bq = lane >> 4;
     LCD_STAMP(0);
 
@@ -412,7 +413,8 @@ gemv_dense_kernel(const uint8_t *__restrict__ packed, const uint8_t *__restrict_
 {
     __shared__ __attribute__((aligned(16))) float part[2][kMaxWaves][16][16];  // [buf][wave][token][row]
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+    const int lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: keeps addresses scalar
     const int q = lane >> 4, j = lane & 15, bq = lane >> 4;
     const int kc = K / kTileCols, nt = N / kTileRows;
     const int split = blockIdx.y;

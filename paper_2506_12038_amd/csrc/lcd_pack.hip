@@ -143,9 +143,9 @@ __global__ void __launch_bounds__(256) build_lut_kernel(const uint16_t *__restri
 // One thread per group of 8 consecutive k.  Output order:
 //   LAYOUT 0: [M][K], inside each group of 8 the slot order 0,4,1,5,2,6,3,7 that the register
 //             dequantiser produces (batched decode path);
-//   LAYOUT 1: MFMA-operand order for the prefill path:
-//             [chunk k/256][token tile m/16][step g=(k%64)/8][m%16][q=(k%256)/64][8 slots], tokens
-//             padded with zeros up to Mpad (a multiple of 128).
+//   LAYOUT 1: operand order of v_mfma_f32_32x32x16_f16 for the prefill path:
+//             [chunk k/256][token block m/32][half (k%256)/128][step g=(k%64)/8][(k%128)/64][m%32][8 slots],
+//             tokens padded with zeros up to Mpad (a multiple of 128).
 template <int LAYOUT>
 __global__ void __launch_bounds__(256) smooth_kernel(const uint16_t *__restrict__ x, const float *__restrict__ s,
                                                      _Float16 *__restrict__ xs, int M, int Mpad, int K)
@@ -175,8 +175,8 @@ __global__ void __launch_bounds__(256) smooth_kernel(const uint16_t *__restrict_
     if (LAYOUT == 0) {
         dst = (size_t)m * K + k;
     } else {
-        const int c = k >> 8, q = (k >> 6) & 3, g = (k >> 3) & 7;
-        dst = ((((size_t)c * (Mpad >> 4) + (m >> 4)) * 8 + g) * 16 + (m & 15)) * 32 + q * 8;
+        const int c = k >> 8, h = (k >> 7) & 1, kh = (k >> 6) & 1, g = (k >> 3) & 7;
+        dst = ((((((size_t)c * (Mpad >> 5) + (m >> 5)) * 2 + h) * 8 + g) * 2 + kh) * 32 + (m & 31)) * 8;
     }
     *reinterpret_cast<half8 *>(xs + dst) = o;
 }
