@@ -167,7 +167,7 @@ def cpu_baseline(cfg_index, M, budget_s=12.0):
     sample_bytes = sum(rows * K * cfg.bits // 8 for rows, K, _ in layers)
     sample_flops = sum(2 * M * rows * K for rows, K, _ in layers)
     best, spent, passes = None, 0.0, 0
-    while spent < budget_s and passes < 40:
+    while spent < budget_s and passes < 1000:
         t0 = time.perf_counter()
         for rows, K, layer in layers:
             oracle.lut_matmul(layer["codebook"], layer["idx"], layer["x"], layer["s"], cfg.bits)
@@ -182,6 +182,18 @@ def cpu_baseline(cfg_index, M, budget_s=12.0):
         "sample": f"config {cfg_index} at M={M}: rows x K = {', '.join(desc)} (each distinct matrix shape once), "
                   f"fp64 oracle, best of {passes} passes, {spent:.1f} s of oracle time in total",
     }
+
+
+def measured_traffic(kernel, cfg_index):
+    """HBM bytes per launch of the dominant kernel, from the committed rocprofv3 --pmc summary
+    (FETCH_SIZE / WRITE_SIZE, scaled by a copy of known size); None if there is no such file."""
+    f = ROOT / "profiles" / f"{kernel}_config{cfg_index}_hbm_traffic.txt"
+    if not f.exists():
+        return None
+    for line in f.read_text().splitlines():
+        if line.startswith("traffic_bytes_per_launch:"):
+            return int(line.split(":")[1])
+    return None
 
 
 def main():
@@ -209,7 +221,8 @@ def main():
         value = ls.index_bytes / (wall_ms * 1e-3) / 1e9
         roofline = {
             "bound": "hbm", "achieved": ls.index_bytes / (event_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": ls.index_bytes / (event_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None,
+            "frac": ls.index_bytes / (event_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "traffic": measured_traffic("gemv_bucket_kernel" if M == 1 else "gemv_dense_kernel", args.config) if n_launch == 1 else None,
             "kernel": "gemv_bucket_kernel" if M == 1 else "gemv_dense_kernel",
             "launches_per_step": n_launch, "algorithmic_bytes_per_step": ls.index_bytes,
             "avg_launch_us": event_ms * 1e3 / n_launch,
