@@ -71,7 +71,6 @@ struct BucketBatch {
     BucketProblem p[kMaxGroup];
     int wg_begin[kMaxGroup + 1];  // first workgroup of every layer
     int count;
-    int kc_max;
 #ifdef LCD_TRACE
     unsigned long long *trace;   // debug builds only: 16 timestamps per workgroup
 #endif
@@ -148,9 +147,9 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const BucketBa
     constexpr uint32_t TB = BITS == 2 ? 1024 : 1536;
     constexpr int NT = kBW * 64;
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
-    // LDS: [ xs: kc_max*256 halfs ][ cf: kVisitTiles*16*NC floats ][ part: kBW*kVisitTiles*16 floats ]
+    // LDS: [ xs: one segment, kBSeg*256 halfs ][ cf: kVisitTiles*16*NC floats ][ part: kBW*kVisitTiles*16 floats ]
     _Float16 *xs_lds = reinterpret_cast<_Float16 *>(smem);
-    float *cf_lds = reinterpret_cast<float *>(smem + (size_t)batch.kc_max * kTileCols * 2);
+    float *cf_lds = reinterpret_cast<float *>(smem + (size_t)kBSeg * kTileCols * 2);
     float *part = cf_lds + kVisitTiles * 16 * NC;
 
     const int lane = threadIdx.x & 63;
@@ -176,21 +175,33 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const BucketBa
     cur = pf;
     if (cur.done) return;
 
-    // The activation / multiplier loads head the longest dependency chain: every wave issues
-    // them before its tile loads and converts them as soon as they (not the tiles) arrive.
-    constexpr int XR = 1;   // activation groups preloaded per thread (K <= 8192); larger K takes a serial loop
+    // Activations.  A segment is kBSeg*256 = 8 * (threads of the workgroup) columns, and thread t of
+    // wave w smooths columns [8t, 8t+8) of it -- which lie in wave w's own two chunks.  So a wave
+    // stages its activations through its own 1 KiB of LDS (to fan 8 values out to the 16 lanes
+    // that need them) without any workgroup synchronisation.  The loads for a segment are issued
+    // one segment ahead; the very first ones head the kernel, before the tile loads, because they
+    // start the longest dependency chain.  Reads past the end of x / s return zero through the
+    // buffer resource.
     const int groups = kc * (kTileCols / 8);
-    uint4v xv[XR];
-    float4v s0[XR], s1[XR];
+    uint4v xv;
+    float4v s0, s1;
+    auto load_x = [&](int sg, bool valid) {
+        const uint32_t g = (uint32_t)sg * NT + threadIdx.x;
+        xv = __builtin_amdgcn_raw_buffer_load_b128(rs_x, valid ? g * 16 : kOob, 0, 0);
+        s0 = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(rs_s, valid ? g * 32 : kOob, 0, 0));
+        s1 = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(rs_s, valid ? g * 32 + 16 : kOob, 0, 0));
+    };
+    load_x(0, true);
+    // multipliers of the first visit: (tiles * 4 * NC) float4, at most CFR per thread
+    constexpr int CFR = kVisitTiles * 4 * NC / NT;
+    static_assert(CFR * NT == kVisitTiles * 4 * NC, "multiplier preload must cover a full visit");
+    const int nf4_first = (cur.v1 - cur.v0) * 4 * NC;
+    uint4v cfv[CFR];
 #pragma unroll
-    for (int u = 0; u < XR; ++u) {
-        const int g = threadIdx.x + u * NT;
-        xv[u] = __builtin_amdgcn_raw_buffer_load_b128(rs_x, g < groups ? g * 16 : kOob, 0, 0);
-        s0[u] = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(rs_s, g < groups ? g * 32 : kOob, 0, 0));
-        s1[u] = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(rs_s, g < groups ? g * 32 + 16 : kOob, 0, 0));
+    for (int u = 0; u < CFR; ++u) {
+        const int e = u * NT + (int)threadIdx.x;
+        cfv[u] = __builtin_amdgcn_raw_buffer_load_b128(rs_lut, e < nf4_first ? ((uint32_t)cur.v0 * 4 * NC + e) * 16 : kOob, 0, 0);
     }
-    const int nf4_first = (cur.v1 - cur.v0) * 4 * NC;   // float4 count of the first visit's multipliers (<= NT)
-    const uint4v cfv = __builtin_amdgcn_raw_buffer_load_b128(rs_lut, (int)threadIdx.x < nf4_first ? ((uint32_t)cur.v0 * 4 * NC + threadIdx.x) * 16 : kOob, 0, 0);
     StepRegs<BITS> r0, r1, r2, r3;
     issue_step_loads<BITS>(r0, pf, rs_packed, kc, wave, lane); cursor_advance(pf, nseg);
 
@@ -263,22 +274,29 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const BucketBa
 
     // four steps = one turn of the register-set rotation; cur.i is the first step's tile
     auto four_steps = [&]() {
-        float4v t0, t1;
+        // a run is padded to a multiple of four steps; the padding steps (wave-uniform test)
+        // skip their arithmetic
+        const int left = (cur.v1 - cur.v0) - cur.i;
+        const float4v zero = {0.f, 0.f, 0.f, 0.f};
+        float4v t0, t1 = zero, t3 = zero;
         issue_step_loads<BITS>(r3, pf, rs_packed, kc, wave, lane); cursor_advance(pf, nseg);
         t0 = tile_sums(r0);
         issue_step_loads<BITS>(r0, pf, rs_packed, kc, wave, lane); cursor_advance(pf, nseg);
-        t1 = tile_sums(r1);
+        if (left > 1) t1 = tile_sums(r1);
 #pragma unroll
         for (int u = 0; u < 4; ++u) t0[u] += dpp_f32<(TG == 2 ? 0x118 : 0x114)>(t1[u]);   // row_shr:8 / row_shr:4
         if (TG == 2) reduce_group(t0, cur.i);
         issue_step_loads<BITS>(r1, pf, rs_packed, kc, wave, lane); cursor_advance(pf, nseg);
-        t1 = tile_sums(r2);
+        t1 = zero;
+        if (left > 2) t1 = tile_sums(r2);
         issue_step_loads<BITS>(r2, pf, rs_packed, kc, wave, lane); cursor_advance(pf, nseg);
-        float4v t3 = tile_sums(r3);
+        if (left > 3) t3 = tile_sums(r3);
         if (TG == 2) {
+            if (left > 2) {
 #pragma unroll
-            for (int u = 0; u < 4; ++u) t1[u] += dpp_f32<0x118>(t3[u]);
-            reduce_group(t1, cur.i + 2);
+                for (int u = 0; u < 4; ++u) t1[u] += dpp_f32<0x118>(t3[u]);
+                reduce_group(t1, cur.i + 2);
+            }
         } else {
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
@@ -294,29 +312,12 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const BucketBa
     while (!cur.done) {
         // ---- visit prologue (the barrier that ended the previous visit protects the LDS reuse)
         if (first_visit) {
-            if ((int)threadIdx.x < nf4_first) reinterpret_cast<uint4v *>(cf_lds)[threadIdx.x] = cfv;
 #pragma unroll
-            for (int u = 0; u < XR; ++u) {
-                if (u * NT >= groups) break;          // uniform: this round is empty for every thread
-                const int g = threadIdx.x + u * NT;
-                half8 o;
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    o[e] = smooth_one((uint16_t)(xv[u][e >> 1] >> (16 * (e & 1))), e < 4 ? s0[u][e] : s1[u][e - 4]);
-                if (g < groups) *reinterpret_cast<half8 *>(&xs_lds[8 * g]) = o;
+            for (int u = 0; u < CFR; ++u) {
+                const int e = u * NT + (int)threadIdx.x;
+                if (e < nf4_first) reinterpret_cast<uint4v *>(cf_lds)[e] = cfv[u];
             }
-            for (int g = threadIdx.x + XR * NT; g < groups; g += NT) {   // larger K only
-                const uint4v xw = __builtin_amdgcn_raw_buffer_load_b128(rs_x, g * 16, 0, 0);
-                const float4v w0 = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(rs_s, g * 32, 0, 0));
-                const float4v w1 = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(rs_s, g * 32 + 16, 0, 0));
-                half8 o;
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    o[e] = smooth_one((uint16_t)(xw[e >> 1] >> (16 * (e & 1))), e < 4 ? w0[e] : w1[e - 4]);
-                *reinterpret_cast<half8 *>(&xs_lds[8 * g]) = o;
-            }
-            // the remaining two sets of the pipeline go out only now, so that the conversion above
-            // is not stuck behind their issue
+            // the remaining two sets of the pipeline
             issue_step_loads<BITS>(r1, pf, rs_packed, kc, wave, lane); cursor_advance(pf, nseg);
             issue_step_loads<BITS>(r2, pf, rs_packed, kc, wave, lane); cursor_advance(pf, nseg);
             first_visit = false;
@@ -331,16 +332,22 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const BucketBa
 #pragma unroll
         for (int b = 0; b < 16; ++b) B1[b] = ((b & 3) == j) ? (_Float16)1.0f : (_Float16)0.0f;
         for (cur.sg = 0; cur.sg < nseg; ++cur.sg) {
+            {   // smooth this thread's 8 activations of the segment (loaded one segment ago)
+                const int g = cur.sg * NT + (int)threadIdx.x;
+                half8 o;
 #pragma unroll
-            for (int ch = 0; ch < kBCH; ++ch) {
-                const int chunk = cur.sg * kBSeg + wave * kBCH + ch;
-#pragma unroll
-                for (int g = 0; g < 8; ++g) {
-                    uint4v v = {0u, 0u, 0u, 0u};
-                    if (chunk < kc) v = *reinterpret_cast<const uint4v *>(&xs_lds[chunk * 256 + 64 * q + 8 * g]);
-                    A[ch][g] = v;
-                }
+                for (int e = 0; e < 8; ++e)
+                    o[e] = g < groups ? smooth_one((uint16_t)(xv[e >> 1] >> (16 * (e & 1))), e < 4 ? s0[e] : s1[e - 4]) : (_Float16)0.0f;
+                *reinterpret_cast<half8 *>(&xs_lds[8 * threadIdx.x]) = o;
+                // next segment's activations: of this visit, or segment 0 again for the next visit
+                const bool more = cur.sg + 1 < nseg;
+                load_x(more ? cur.sg + 1 : 0, more || cur.v1 < cur.range_end);
             }
+#pragma unroll
+            for (int ch = 0; ch < kBCH; ++ch)
+#pragma unroll
+                for (int g = 0; g < 8; ++g)   // written by this wave only: no barrier
+                    A[ch][g] = *reinterpret_cast<const uint4v *>(&xs_lds[(wave * kBCH + ch) * kTileCols + 64 * q + 8 * g]);
             for (cur.i = 0; cur.i < cur.steps;) four_steps();
         }
         LCD_STAMP(4);
@@ -503,7 +510,7 @@ int launch_bucket_group(const GroupItem *items, int count, int bits, void *strea
     hipStream_t stream = (hipStream_t)stream_;
     BucketBatch batch{};
     long long cost[kMaxGroup], total = 0;
-    int kmax = 0, tiles = 0;
+    int tiles = 0;
     for (int i = 0; i < count; ++i) {
         BucketProblem &p = batch.p[i];
         p.packed = (const uint8_t *)items[i].packed;
@@ -513,28 +520,36 @@ int launch_bucket_group(const GroupItem *items, int count, int bits, void *strea
         cost[i] = (long long)p.nt * ((p.kc + kBSeg - 1) / kBSeg);   // steps: every row tile takes one step per segment
         total += cost[i];
         tiles += p.nt;
-        if (p.kc > kmax) kmax = p.kc;
     }
-    // workgroups per layer: proportional to its step count, at least 1, at most its row tiles
+    // Workgroups per layer.  A layer's time is that of its slowest workgroup, in units of steps:
+    // a fixed start-up, then for each K segment one step per row tile plus the cost of switching
+    // to the segment's activations.  A 2-bit step moves half the bytes and has no sign-flip
+    // arithmetic, so the fixed costs are worth more of them.  Start from 7/8 of the proportional
+    // share, then hand out the rest one by one to the layer that is slowest at that moment.
     int grid = num_cus();
     if (grid > tiles) grid = tiles;
     if (grid < count) grid = count;
+    const double startup_steps = bits == 2 ? 4.0 : 2.0, segment_steps = bits == 2 ? 0.8 : 0.4;
+    auto layer_time = [&](int i, int n) {
+        const int segs = (batch.p[i].kc + kBSeg - 1) / kBSeg;
+        const int t = (batch.p[i].nt + n - 1) / n, visits = (t + kVisitTiles - 1) / kVisitTiles;
+        return startup_steps + segs * (t + visits * segment_steps);
+    };
     int nwg[kMaxGroup], used = 0;
     for (int i = 0; i < count; ++i) {
-        long long n = cost[i] * grid / total;
+        long long n = cost[i] * grid * 7 / (total * 8);
         if (n < 1) n = 1;
         if (n > batch.p[i].nt) n = batch.p[i].nt;
         nwg[i] = (int)n;
         used += nwg[i];
     }
-    while (used < grid) {  // hand the remaining workgroups to the layers with the most work per workgroup
+    while (used < grid) {
         int best = -1;
-        double best_load = 0.0;
+        double best_time = 0.0;
         for (int i = 0; i < count; ++i) {
             if (nwg[i] >= batch.p[i].nt) continue;
-            // time of a layer ~ its slowest workgroup: ceil(nt / nwg) row tiles of kc chunks
-            const double load = (double)((batch.p[i].nt + nwg[i] - 1) / nwg[i]) * ((batch.p[i].kc + kBSeg - 1) / kBSeg);
-            if (load > best_load) { best_load = load; best = i; }
+            const double t = layer_time(i, nwg[i]);
+            if (t > best_time) { best_time = t; best = i; }
         }
         if (best < 0) break;
         ++nwg[best];
@@ -550,12 +565,11 @@ int launch_bucket_group(const GroupItem *items, int count, int bits, void *strea
     }
     for (int i = count; i <= kMaxGroup; ++i) batch.wg_begin[i] = acc;
     batch.count = count;
-    batch.kc_max = kmax;
 #ifdef LCD_TRACE
     batch.trace = g_trace;
 #endif
     const int NC = bits == 2 ? 4 : 8;
-    const size_t lds = (size_t)kmax * kTileCols * 2 + (size_t)kVisitTiles * 16 * NC * 4 + (size_t)kBW * kVisitTiles * 16 * 4;
+    const size_t lds = (size_t)kBSeg * kTileCols * 2 + (size_t)kVisitTiles * 16 * NC * 4 + (size_t)kBW * kVisitTiles * 16 * 4;
     static size_t lds_set[2] = {0, 0};
     const void *fn = bits == 2 ? (const void *)gemv_bucket_kernel<2> : (const void *)gemv_bucket_kernel<3>;
     if (lds > lds_set[bits - 2]) {

@@ -247,7 +247,6 @@ lcd_status lcd_lut_gemv(const void *packed, const void *lut, const uint16_t *x, 
 {
     if (M > 16) return fail(LCD_ERR_BAD_M, "lcd_lut_gemv: M=%d > 16 (use lcd_lut_gemm)", M);
     if (lcd_status st = check_product(packed, lut, x, s, y, M, N, K, bits, workspace, workspace_bytes)) return st;
-    if (M == 1 && K > kMaxBucketK) return fail(LCD_ERR_BAD_SHAPE, "K=%d > %d is not supported at M=1", K, kMaxBucketK);
     const GemvPlan plan = plan_gemv(M, N, K, bits);
     if (int e = launch_gemv(packed, lut, x, s, y, M, N, K, bits, workspace, plan, stream))
         return fail(LCD_ERR_HIP, "gemv launch: %s", hip_error_name(e));
@@ -275,7 +274,6 @@ lcd_status lcd_lut_gemv_grouped(const lcd_gemv_problem *problems, int count, int
     for (int i = 0; i < count; ++i) {
         const lcd_gemv_problem &p = problems[i];
         if (lcd_status st = check_product(p.packed, p.lut, p.x, p.s, p.y, M, p.N, p.K, bits, workspace, workspace_bytes)) return st;
-        if (M == 1 && p.K > kMaxBucketK) return fail(LCD_ERR_BAD_SHAPE, "K=%d > %d is not supported at M=1", p.K, kMaxBucketK);
     }
     if (M == 1) {
         GroupItem items[kMaxGroup];

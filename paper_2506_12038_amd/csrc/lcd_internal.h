@@ -36,7 +36,6 @@ struct GemmPlan {
 GemmPlan plan_gemm(int M, int N, int K, int bits);
 
 constexpr int kMaxGroup = 16;     // problems per grouped launch
-constexpr int kMaxBucketK = 65536;  // single-token kernel keeps one token's activations in LDS
 
 struct GroupItem {
     const void *packed; const void *lut; const uint16_t *x; const float *s; uint16_t *y; int N, K;

@@ -139,6 +139,3 @@ def test_grouped_entry_point_validates_on_host():
     arr[1].K = 512
     arr[1].y = 0x1002
     assert st(lib.lcd_lut_gemv_grouped(arr, 2, 1, 2, ctypes.c_void_p(a), big, None)) == b"LCD_ERR_ALIGN"
-    # single-token path keeps one token's activations in LDS: K is bounded
-    assert st(lib.lcd_lut_gemv(ctypes.c_void_p(a), ctypes.c_void_p(a), ctypes.c_void_p(a), ctypes.c_void_p(a),
-                               ctypes.c_void_p(a), 1, 16, 65536 + 256, 2, ctypes.c_void_p(a), big, None)) == b"LCD_ERR_BAD_SHAPE"
