@@ -477,7 +477,7 @@ int launch_gemm(const void *packed, const void *lut, const uint16_t *x, const fl
 {
     hipStream_t stream = (hipStream_t)stream_;
     const int Mpad = plan.m_pad;
-    if (int e = launch_smooth(x, s, workspace, M, Mpad, K, 1, stream)) return e;
+    if (int e = launch_smooth(x, s, workspace, M, Mpad, K, stream)) return e;
     const uint8_t *lutB = static_cast<const uint8_t *>(lut) + (size_t)N * (bits == 2 ? 4 : 8) * 4;
     const int nt = N / kTileRows;
     const int tiles_per_wg = kGemmRowGroups * 2 * kGemmPairs;

@@ -26,7 +26,6 @@
 namespace lcd {
 
 
-constexpr int kMaxWaves = 8;
 
 // Buffer resources give branch-free predication: a lane whose offset is past the end of the
 // buffer reads zeros and touches no memory.
@@ -368,124 +367,202 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const BucketBa
     }
 }
 
-// ---- batched decode kernel (2 <= M <= 16) ---------------------------------------------------
-// Same work split as the bucket kernel, but the 16 columns of the matrix core's output tile are
-// the tokens: the packed indices are dequantised in registers (v_perm_b32 through per-row
-// byte-split codebook tables) into the A operand of v_mfma_f32_16x16x32_f16, and the smoothed
-// activations of the wave's K range stay in registers as B operands.
-template <int BITS, int CH>
-struct DenseTileRegs {
-    uint4v lo[CH];
-    uint2v hi[CH];
-    RowTables tb;
+
+// ---- batched decode kernel (2 <= M <= 16): persistent workgroups over a group of layers -------
+//
+// Same walk as the bucket kernel (layer -> run of row tiles -> visits -> K segments -> steps, loads
+// kSets-1 steps ahead), but the 16 columns of the matrix core's output tile are the tokens: the
+// packed indices are dequantised in registers (v_perm_b32 through per-row byte-split codebook
+// tables) into the A operand of v_mfma_f32_16x16x32_f16, and the smoothed activations of the
+// wave's two chunks, all tokens, stay in registers as B operands for a whole segment.
+//   segment start  every wave smooths its own 512 columns of every token (Sec. 3.4: x / s) and
+//                  fans them out to the B-operand layout through its own LDS stage: no workgroup
+//                  synchronisation;
+//   step           one row tile: 16 MFMAs per wave; the 8 waves' 16x16 partial tiles meet in LDS
+//                  (double-buffered, one s_barrier per step, no wait on outstanding loads) and
+//                  256 threads add them in a fixed order.  With one segment the sum is rounded
+//                  and stored; with several it accumulates in LDS until the last segment.
+constexpr int kStageStride = kTileCols + 8;   // halfs per token row of a wave's stage (+16 B: no bank conflicts)
+
+template <int BITS>
+struct TokStepRegs {
+    uint4v lo[kBCH];
+    uint2v hi[kBCH];
+    uint4v tb;         // the lane's row of byte-split codebook tables
 };
 
-template <int BITS, int CH>
-__device__ __forceinline__ void load_dense_tile(DenseTileRegs<BITS, CH> &r, const uint8_t *__restrict__ packed,
-                                                const uint8_t *__restrict__ lutB, int t, int kc, int c_begin, int nch, int lane)
+template <int BITS>
+__device__ __forceinline__ void issue_tok_loads(TokStepRegs<BITS> &r, const Cursor &c, __amdgpu_buffer_rsrc_t rs,
+                                                __amdgpu_buffer_rsrc_t rs_tb, int kc, int wave, int lane)
 {
-    constexpr size_t TB = BITS == 2 ? 1024 : 1536;
-    const uint8_t *base = packed + ((size_t)t * kc + c_begin) * TB;
+    constexpr uint32_t TB = BITS == 2 ? 1024 : 1536;
+    const int tile = c.v0 + c.i;
+    const bool tv = !c.done && tile < c.v1;
 #pragma unroll
-    for (int ch = 0; ch < CH; ++ch) {
-        if (ch < nch) {
-            r.lo[ch] = __builtin_nontemporal_load(reinterpret_cast<const uint4v *>(base + ch * TB + 16 * lane));
-            if (BITS == 3) r.hi[ch] = __builtin_nontemporal_load(reinterpret_cast<const uint2v *>(base + ch * TB + 1024 + 8 * lane));
-        }
+    for (int ch = 0; ch < kBCH; ++ch) {
+        const int chunk = c.sg * kBSeg + wave * kBCH + ch;
+        const bool v = tv && chunk < kc;
+        const uint32_t o = ((uint32_t)tile * (uint32_t)kc + (uint32_t)chunk) * TB;
+        r.lo[ch] = __builtin_amdgcn_raw_buffer_load_b128(rs, v ? o + 16 * lane : kOob, 0, 0);
+        if (BITS == 3) r.hi[ch] = __builtin_amdgcn_raw_buffer_load_b64(rs, v ? o + 1024 + 8 * lane : kOob, 0, 0);
     }
-    const size_t row = (size_t)t * kTileRows + (lane & 15);
+    const uint32_t row = (uint32_t)tile * kTileRows + (lane & 15);
     if (BITS == 2) {
-        const uint2v v = *reinterpret_cast<const uint2v *>(lutB + row * 8);
-        r.tb.lo[0] = v[0]; r.tb.hi[0] = v[1]; r.tb.lo[1] = 0; r.tb.hi[1] = 0;
+        const uint2v t = __builtin_amdgcn_raw_buffer_load_b64(rs_tb, tv ? row * 8 : kOob, 0, 0);
+        r.tb = uint4v{t[0], t[1], 0u, 0u};
     } else {
-        const uint4v v = *reinterpret_cast<const uint4v *>(lutB + row * 16);
-        r.tb.lo[0] = v[0]; r.tb.lo[1] = v[1]; r.tb.hi[0] = v[2]; r.tb.hi[1] = v[3];
+        r.tb = __builtin_amdgcn_raw_buffer_load_b128(rs_tb, tv ? row * 16 : kOob, 0, 0);
     }
 }
 
-template <int BITS, int CH, int D>
-__device__ __forceinline__ void dense_word(const DenseTileRegs<BITS, CH> &r, int ch, const HighBits &hb,
-                                           const uint4v (&Bx)[CH][8], float4v (&acc)[2])
+template <int BITS>
+__global__ void __launch_bounds__(kBW * 64, 1) gemv_tokens_kernel(const BucketBatch batch, const int M)
 {
-    uint4v op0, op1;
-    decode_word<BITS, D>(r.lo[ch][D], hb, r.tb, op0, op1);
-    acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(op0), as_half8(Bx[ch][2 * D]), acc[0], 0, 0, 0);
-    acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(op1), as_half8(Bx[ch][2 * D + 1]), acc[1], 0, 0, 0);
-}
+    constexpr int NC = BITS == 2 ? 4 : 8;
+    constexpr uint32_t TB = BITS == 2 ? 1024 : 1536;
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+    // LDS: [ stage: kBW x 16 tokens x kStageStride halfs ][ red: 2 x kBW x 256 floats ][ sums: kVisitTiles x 256 floats ]
+    _Float16 *stage = reinterpret_cast<_Float16 *>(smem) ;
+    float *red = reinterpret_cast<float *>(smem + (size_t)kBW * 16 * kStageStride * 2);
+    float *sums = red + 2 * kBW * 256;
 
-template <int BITS, int CH>
-__global__ void __launch_bounds__(kMaxWaves * 64, 1)
-gemv_dense_kernel(const uint8_t *__restrict__ packed, const uint8_t *__restrict__ lutB, const _Float16 *__restrict__ xs,
-                  uint16_t *__restrict__ y, float *__restrict__ partial, int M, int N, int K, int chunks_per_split, int splits)
-{
-    __shared__ __attribute__((aligned(16))) float part[2][kMaxWaves][16][16];  // [buf][wave][token][row]
-
-    const int lane = threadIdx.x & 63, nwaves = blockDim.x >> 6;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: keeps addresses scalar
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int q = lane >> 4, j = lane & 15, bq = lane >> 4;
-    const int kc = K / kTileCols, nt = N / kTileRows;
-    const int split = blockIdx.y;
-    const int split_c0 = split * chunks_per_split;
-    const int split_c1 = min(kc, split_c0 + chunks_per_split);
-    const int c_begin = split_c0 + wave * CH;
-    const int nch = max(0, min(CH, split_c1 - c_begin));
 
-    DenseTileRegs<BITS, CH> r0, r1;
-    int t = blockIdx.x;
-    if (t < nt) load_dense_tile<BITS, CH>(r0, packed, lutB, t, kc, c_begin, nch, lane);
+    int pi = 0;
+    for (int i = 1; i < batch.count; ++i) pi += ((int)blockIdx.x >= batch.wg_begin[i]) ? 1 : 0;
+    const BucketProblem pb = batch.p[pi];
+    const int li = (int)blockIdx.x - batch.wg_begin[pi];
+    const int ta = li * pb.tiles_base + min(li, pb.tiles_extra);
+    const int tb_end = ta + pb.tiles_base + (li < pb.tiles_extra ? 1 : 0);
+    const int kc = pb.kc, nseg = (kc + kBSeg - 1) / kBSeg, K = kc * kTileCols, N = pb.nt * kTileRows;
+    const __amdgpu_buffer_rsrc_t rs_packed = make_rsrc(pb.packed, (uint32_t)pb.nt * (uint32_t)kc * TB);
+    const __amdgpu_buffer_rsrc_t rs_x = make_rsrc(pb.x, (uint32_t)M * (uint32_t)K * 2);
+    const __amdgpu_buffer_rsrc_t rs_s = make_rsrc(pb.s, (uint32_t)K * 4);
+    const __amdgpu_buffer_rsrc_t rs_tb = make_rsrc(reinterpret_cast<const uint8_t *>(pb.lutA) + (size_t)N * NC * 4, (uint32_t)N * (BITS == 2 ? 8 : 16));
 
-    // B operands: lane (q, token j) keeps xs[j][chunk*256 + 64q + 8g + 0..7] for every chunk it owns
-    uint4v Bx[CH][8];
-#pragma unroll
-    for (int ch = 0; ch < CH; ++ch)
-#pragma unroll
-        for (int g = 0; g < 8; ++g) {
-            uint4v v = {0u, 0u, 0u, 0u};
-            if (ch < nch && j < M)
-                v = *reinterpret_cast<const uint4v *>(xs + (size_t)j * K + (size_t)(c_begin + ch) * kTileCols + 64 * q + 8 * g);
-            Bx[ch][g] = v;
-        }
+    Cursor pf{}, cur{};
+    cursor_begin(pf, ta, tb_end);
+    cur = pf;
+    if (cur.done) return;
 
-    auto process = [&](const DenseTileRegs<BITS, CH> &r, int tile, int buf) {
-        float4v acc[2] = {float4v{0.f, 0.f, 0.f, 0.f}, float4v{0.f, 0.f, 0.f, 0.f}};
+    TokStepRegs<BITS> r0, r1, r2, r3;
+    uint4v Bx[kBCH][8];                      // B operands: lane (q, token j) holds 8 activations per MFMA
+    _Float16 *my_stage = stage + wave * (16 * kStageStride);
+
+    // Smooth the wave's two chunks of segment sg for all tokens and load them as B operands.
+    // Lane l covers the 8 columns [8*(l&31), +8) of a chunk for the tokens 8*(l>>5) .. +7.
+    auto load_activations = [&](int sg) {
+        const int kg = lane & 31, th = lane >> 5;
+        uint4v xr[kBCH][8];
+        float4v sa[kBCH], sb[kBCH];
 #pragma unroll
-        for (int ch = 0; ch < CH; ++ch) {
-            if (ch < nch) {
-                HighBits hb{0u, 0u};
-                if (BITS == 3) hb = regroup_high(r.hi[ch]);
-                dense_word<BITS, CH, 0>(r, ch, hb, Bx, acc);
-                dense_word<BITS, CH, 1>(r, ch, hb, Bx, acc);
-                dense_word<BITS, CH, 2>(r, ch, hb, Bx, acc);
-                dense_word<BITS, CH, 3>(r, ch, hb, Bx, acc);
+        for (int ch = 0; ch < kBCH; ++ch) {
+            const int chunk = sg * kBSeg + wave * kBCH + ch;
+            const uint32_t k0 = (uint32_t)chunk * kTileCols + 8 * kg;
+            const bool cv = chunk < kc;
+            sa[ch] = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(rs_s, cv ? k0 * 4 : kOob, 0, 0));
+            sb[ch] = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(rs_s, cv ? k0 * 4 + 16 : kOob, 0, 0));
+#pragma unroll
+            for (int mm = 0; mm < 8; ++mm) {
+                const int m = th * 8 + mm;
+                xr[ch][mm] = __builtin_amdgcn_raw_buffer_load_b128(rs_x, (cv && m < M) ? ((uint32_t)m * (uint32_t)K + k0) * 2 : kOob, 0, 0);
             }
         }
-        // accumulator: lane (bq, j) holds rows 4bq..4bq+3 of token j
-        const float4v p = acc[0] + acc[1];
-        *reinterpret_cast<float4v *>(&part[buf][wave][j][4 * bq]) = p;
-        __syncthreads();
-        {
-            const int e = threadIdx.x;
-            for (int o = e; o < 16 * M; o += blockDim.x) {
-                const int m = o >> 4, row = o & 15;
-                float sum = 0.f;
-                for (int w = 0; w < nwaves; ++w) sum += part[buf][w][m][row];
-                const size_t dst = (size_t)m * N + (size_t)tile * kTileRows + row;
-                if (splits == 1) y[dst] = __builtin_bit_cast(uint16_t, (_Float16)sum);
-                else partial[(size_t)split * M * N + dst] = sum;
+#pragma unroll
+        for (int ch = 0; ch < kBCH; ++ch) {
+            const bool cv = sg * kBSeg + wave * kBCH + ch < kc;
+            float rs[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) rs[e] = cv ? __builtin_amdgcn_rcpf(e < 4 ? sa[ch][e] : sb[ch][e - 4]) : 0.0f;
+#pragma unroll
+            for (int mm = 0; mm < 8; ++mm) {
+                half8 o;   // operand slot order 0,4,1,5,2,6,3,7 (the dequantiser pairs weight v with weight 4+v)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float xf = (float)__builtin_bit_cast(_Float16, (uint16_t)(xr[ch][mm][e >> 1] >> (16 * (e & 1))));
+                    o[(e & 3) * 2 + (e >> 2)] = (_Float16)(xf * rs[e]);
+                }
+                *reinterpret_cast<half8 *>(&my_stage[(th * 8 + mm) * kStageStride + 8 * kg]) = o;
             }
+#pragma unroll
+            for (int g = 0; g < 8; ++g)   // written by this wave only: LDS operations of a wave stay in order
+                Bx[ch][g] = *reinterpret_cast<const uint4v *>(&my_stage[j * kStageStride + 64 * q + 8 * g]);
         }
     };
 
-    const int stride = gridDim.x;
-    while (t < nt) {
-        const int t1 = t + stride;
-        if (t1 < nt) load_dense_tile<BITS, CH>(r1, packed, lutB, t1, kc, c_begin, nch, lane);
-        process(r0, t, 0);
-        if (t1 >= nt) break;
-        const int t2 = t1 + stride;
-        if (t2 < nt) load_dense_tile<BITS, CH>(r0, packed, lutB, t2, kc, c_begin, nch, lane);
-        process(r1, t1, 1);
-        t = t2;
+    auto tile_product = [&](const TokStepRegs<BITS> &r) -> float4v {
+        float4v acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+        RowTables t;
+        if (BITS == 2) { t.lo[0] = r.tb[0]; t.hi[0] = r.tb[1]; t.lo[1] = 0; t.hi[1] = 0; }
+        else { t.lo[0] = r.tb[0]; t.lo[1] = r.tb[1]; t.hi[0] = r.tb[2]; t.hi[1] = r.tb[3]; }
+#pragma unroll
+        for (int ch = 0; ch < kBCH; ++ch) {
+            HighBits hb{0u, 0u};
+            if (BITS == 3) hb = regroup_high(r.hi[ch]);
+            uint4v op0, op1;
+            decode_word<BITS, 0>(r.lo[ch][0], hb, t, op0, op1);
+            acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(op0), as_half8(Bx[ch][0]), acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(op1), as_half8(Bx[ch][1]), acc1, 0, 0, 0);
+            decode_word<BITS, 1>(r.lo[ch][1], hb, t, op0, op1);
+            acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(op0), as_half8(Bx[ch][2]), acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(op1), as_half8(Bx[ch][3]), acc1, 0, 0, 0);
+            decode_word<BITS, 2>(r.lo[ch][2], hb, t, op0, op1);
+            acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(op0), as_half8(Bx[ch][4]), acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(op1), as_half8(Bx[ch][5]), acc1, 0, 0, 0);
+            decode_word<BITS, 3>(r.lo[ch][3], hb, t, op0, op1);
+            acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(op0), as_half8(Bx[ch][6]), acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(op1), as_half8(Bx[ch][7]), acc1, 0, 0, 0);
+        }
+        return acc0 + acc1;   // lane (bq, j): rows 4bq..4bq+3 of token j
+    };
+
+    // one step: this wave's partial tile -> LDS; barrier; fixed-order sum over the waves
+    int phase = 0;
+    auto finish_step = [&](float4v p, int tl) {
+        float *buf = red + phase * (kBW * 256);
+        *reinterpret_cast<float4v *>(&buf[wave * 256 + j * 16 + 4 * bq]) = p;
+        // LDS writes done, then the barrier; outstanding global loads keep flying
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        if (threadIdx.x < 256) {
+            const int m = threadIdx.x >> 4, row = threadIdx.x & 15;
+            float sum = 0.f;
+#pragma unroll
+            for (int w = 0; w < kBW; ++w) sum += buf[w * 256 + threadIdx.x];
+            if (nseg > 1) {
+                float *slot = &sums[tl * 256 + threadIdx.x];
+                if (cur.sg > 0) sum += *slot;
+                if (cur.sg + 1 < nseg) *slot = sum;
+            }
+            if (cur.sg + 1 == nseg && m < M)
+                pb.y[(size_t)m * N + (size_t)(cur.v0 + tl) * kTileRows + row] = __builtin_bit_cast(uint16_t, (_Float16)sum);
+        }
+        phase ^= 1;
+    };
+
+    auto four_steps = [&]() {
+        const int left = (cur.v1 - cur.v0) - cur.i;   // tiles left in this run; padding steps skip their work
+        issue_tok_loads<BITS>(r3, pf, rs_packed, rs_tb, kc, wave, lane); cursor_advance(pf, nseg);
+        finish_step(tile_product(r0), cur.i);
+        issue_tok_loads<BITS>(r0, pf, rs_packed, rs_tb, kc, wave, lane); cursor_advance(pf, nseg);
+        if (left > 1) finish_step(tile_product(r1), cur.i + 1);
+        issue_tok_loads<BITS>(r1, pf, rs_packed, rs_tb, kc, wave, lane); cursor_advance(pf, nseg);
+        if (left > 2) finish_step(tile_product(r2), cur.i + 2);
+        issue_tok_loads<BITS>(r2, pf, rs_packed, rs_tb, kc, wave, lane); cursor_advance(pf, nseg);
+        if (left > 3) finish_step(tile_product(r3), cur.i + 3);
+        cur.i += 4;
+    };
+
+    issue_tok_loads<BITS>(r0, pf, rs_packed, rs_tb, kc, wave, lane); cursor_advance(pf, nseg);
+    issue_tok_loads<BITS>(r1, pf, rs_packed, rs_tb, kc, wave, lane); cursor_advance(pf, nseg);
+    issue_tok_loads<BITS>(r2, pf, rs_packed, rs_tb, kc, wave, lane); cursor_advance(pf, nseg);
+    while (!cur.done) {
+        for (cur.sg = 0; cur.sg < nseg; ++cur.sg) {
+            load_activations(cur.sg);
+            for (cur.i = 0; cur.i < cur.steps;) four_steps();
+        }
+        cursor_next_visit(cur);
     }
 }
 
@@ -504,8 +581,8 @@ static int num_cus()
     return g_num_cus;
 }
 
-// One launch for a group of single-token problems.
-int launch_bucket_group(const GroupItem *items, int count, int bits, void *stream_)
+// One launch for a group of decode problems: the bucket kernel for one token, the tokens kernel for 2..16.
+int launch_decode_group(const GroupItem *items, int count, int M, int bits, void *stream_)
 {
     hipStream_t stream = (hipStream_t)stream_;
     BucketBatch batch{};
@@ -529,7 +606,8 @@ int launch_bucket_group(const GroupItem *items, int count, int bits, void *strea
     int grid = num_cus();
     if (grid > tiles) grid = tiles;
     if (grid < count) grid = count;
-    const double startup_steps = bits == 2 ? 4.0 : 2.0, segment_steps = bits == 2 ? 0.8 : 0.4;
+    const double startup_steps = M > 1 ? 3.0 : bits == 2 ? 4.0 : 2.0;
+    const double segment_steps = M > 1 ? 1.2 : bits == 2 ? 0.8 : 0.4;
     auto layer_time = [&](int i, int n) {
         const int segs = (batch.p[i].kc + kBSeg - 1) / kBSeg;
         const int t = (batch.p[i].nt + n - 1) / n, visits = (t + kVisitTiles - 1) / kVisitTiles;
@@ -569,41 +647,35 @@ int launch_bucket_group(const GroupItem *items, int count, int bits, void *strea
     batch.trace = g_trace;
 #endif
     const int NC = bits == 2 ? 4 : 8;
-    const size_t lds = (size_t)kBSeg * kTileCols * 2 + (size_t)kVisitTiles * 16 * NC * 4 + (size_t)kBW * kVisitTiles * 16 * 4;
-    static size_t lds_set[2] = {0, 0};
-    const void *fn = bits == 2 ? (const void *)gemv_bucket_kernel<2> : (const void *)gemv_bucket_kernel<3>;
-    if (lds > lds_set[bits - 2]) {
-        if (hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)) return (int)e;
-        lds_set[bits - 2] = lds;
+    size_t lds;
+    const void *fn;
+    if (M == 1) {
+        lds = (size_t)kBSeg * kTileCols * 2 + (size_t)kVisitTiles * 16 * NC * 4 + (size_t)kBW * kVisitTiles * 16 * 4;
+        fn = bits == 2 ? (const void *)gemv_bucket_kernel<2> : (const void *)gemv_bucket_kernel<3>;
+    } else {
+        lds = (size_t)kBW * 16 * kStageStride * 2 + (size_t)2 * kBW * 256 * 4 + (size_t)kVisitTiles * 256 * 4;
+        fn = bits == 2 ? (const void *)gemv_tokens_kernel<2> : (const void *)gemv_tokens_kernel<3>;
     }
-    if (bits == 2) hipLaunchKernelGGL(gemv_bucket_kernel<2>, dim3(grid), dim3(kBW * 64), lds, stream, batch);
-    else hipLaunchKernelGGL(gemv_bucket_kernel<3>, dim3(grid), dim3(kBW * 64), lds, stream, batch);
+    static bool lds_set[2][2] = {{false, false}, {false, false}};
+    if (!lds_set[M > 1][bits - 2]) {
+        if (hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)) return (int)e;
+        lds_set[M > 1][bits - 2] = true;
+    }
+    if (M == 1) {
+        if (bits == 2) hipLaunchKernelGGL(gemv_bucket_kernel<2>, dim3(grid), dim3(kBW * 64), lds, stream, batch);
+        else hipLaunchKernelGGL(gemv_bucket_kernel<3>, dim3(grid), dim3(kBW * 64), lds, stream, batch);
+    } else {
+        if (bits == 2) hipLaunchKernelGGL(gemv_tokens_kernel<2>, dim3(grid), dim3(kBW * 64), lds, stream, batch, M);
+        else hipLaunchKernelGGL(gemv_tokens_kernel<3>, dim3(grid), dim3(kBW * 64), lds, stream, batch, M);
+    }
     return (int)hipGetLastError();
 }
 
 int launch_gemv(const void *packed, const void *lut, const uint16_t *x, const float *s, uint16_t *y,
-                int M, int N, int K, int bits, void *workspace, const GemvPlan &plan, void *stream_)
+                int M, int N, int K, int bits, void *stream_)
 {
-    hipStream_t stream = (hipStream_t)stream_;
-    float *partial = reinterpret_cast<float *>(static_cast<uint8_t *>(workspace) + plan.xs_bytes);
-    if (M == 1) {
-        GroupItem it{packed, lut, x, s, y, N, K};
-        return launch_bucket_group(&it, 1, bits, stream_);
-    }
-    // batched: smooth once into the workspace (dequantiser slot order), then the dense kernel
-    _Float16 *xs = reinterpret_cast<_Float16 *>(workspace);
-    if (int e = launch_smooth(x, s, xs, M, M, K, 0, stream)) return e;
-    const uint8_t *lutB = static_cast<const uint8_t *>(lut) + (size_t)N * (bits == 2 ? 4 : 8) * 4;
-    const dim3 grid(plan.grid_x, plan.splits), block(plan.waves * 64);
-    if (bits == 2)
-        hipLaunchKernelGGL((gemv_dense_kernel<2, 4>), grid, block, 0, stream, (const uint8_t *)packed, lutB, xs, y, partial,
-                           M, N, K, plan.chunks_per_split, plan.splits);
-    else
-        hipLaunchKernelGGL((gemv_dense_kernel<3, 4>), grid, block, 0, stream, (const uint8_t *)packed, lutB, xs, y, partial,
-                           M, N, K, plan.chunks_per_split, plan.splits);
-    if (int e = (int)hipGetLastError()) return e;
-    if (plan.splits > 1) return launch_reduce(partial, y, plan.splits, (long long)M * N, stream);
-    return 0;
+    GroupItem it{packed, lut, x, s, y, N, K};
+    return launch_decode_group(&it, 1, M, bits, stream_);
 }
 
 }  // namespace lcd

@@ -37,27 +37,6 @@ static lcd_status check_aligned(const void *p, const char *name)
 
 static size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-GemvPlan plan_gemv(int M, int N, int K, int bits)
-{
-    GemvPlan p{};
-    const int kc = K / kTileCols;
-    // A wave keeps the smoothed activations of `ch` chunks in registers (32 VGPRs per chunk;
-    // the 3-bit single-token path also keeps their negation).
-    p.ch = (M == 1 && bits == 3) ? 2 : 4;
-    const int kwaves = (kc + p.ch - 1) / p.ch;      // waves needed to cover K once
-    const int max_waves = 8;                        // keeps 2 waves per SIMD at <= 256 VGPRs
-    p.splits = (kwaves + max_waves - 1) / max_waves;
-    p.waves = (kwaves + p.splits - 1) / p.splits;
-    p.chunks_per_split = p.waves * p.ch;
-    const int row_tiles = N / kTileRows;
-    p.grid_x = row_tiles;
-    const int cap = 2048 / (p.waves * p.splits) > 0 ? 2048 / (p.waves * p.splits) : 1;  // ~2 waves per SIMD resident
-    if (p.grid_x > cap) p.grid_x = cap;
-    p.xs_bytes = (M > 1) ? round_up((size_t)M * K * 2, 256) : 0;
-    p.partial_bytes = (p.splits > 1) ? round_up((size_t)p.splits * M * N * 4, 256) : 0;
-    return p;
-}
-
 GemmPlan plan_gemm(int M, int N, int K, int bits)
 {
     (void)N; (void)bits;
@@ -127,14 +106,9 @@ size_t lcd_lut_bytes(int N, int bits)
 size_t lcd_workspace_bytes(int M, int N, int K, int bits)
 {
     if (check_shape(N, K, bits) != LCD_OK || M < 1) return 0;
-    size_t need = 256;
-    if (M <= 16) {
-        const GemvPlan g = plan_gemv(M, N, K, bits);
-        need = g.xs_bytes + g.partial_bytes;
-    }
+    // the decode path (lcd_lut_gemv) needs none; the prefill path keeps the smoothed activations there
     const GemmPlan m = plan_gemm(M, N, K, bits);
-    if (m.xs_bytes > need) need = m.xs_bytes;
-    return need < 256 ? 256 : need;
+    return m.xs_bytes < 256 ? 256 : m.xs_bytes;
 }
 
 lcd_status lcd_pack_indices_host(const uint8_t *idx, int N, int K, int bits, void *packed, size_t packed_bytes)
@@ -247,8 +221,7 @@ lcd_status lcd_lut_gemv(const void *packed, const void *lut, const uint16_t *x, 
 {
     if (M > 16) return fail(LCD_ERR_BAD_M, "lcd_lut_gemv: M=%d > 16 (use lcd_lut_gemm)", M);
     if (lcd_status st = check_product(packed, lut, x, s, y, M, N, K, bits, workspace, workspace_bytes)) return st;
-    const GemvPlan plan = plan_gemv(M, N, K, bits);
-    if (int e = launch_gemv(packed, lut, x, s, y, M, N, K, bits, workspace, plan, stream))
+    if (int e = launch_gemv(packed, lut, x, s, y, M, N, K, bits, stream))
         return fail(LCD_ERR_HIP, "gemv launch: %s", hip_error_name(e));
     return LCD_OK;
 }
@@ -275,20 +248,10 @@ lcd_status lcd_lut_gemv_grouped(const lcd_gemv_problem *problems, int count, int
         const lcd_gemv_problem &p = problems[i];
         if (lcd_status st = check_product(p.packed, p.lut, p.x, p.s, p.y, M, p.N, p.K, bits, workspace, workspace_bytes)) return st;
     }
-    if (M == 1) {
-        GroupItem items[kMaxGroup];
-        for (int i = 0; i < count; ++i)
-            items[i] = GroupItem{problems[i].packed, problems[i].lut, problems[i].x, problems[i].s, problems[i].y, problems[i].N, problems[i].K};
-        if (int e = launch_bucket_group(items, count, bits, stream)) return fail(LCD_ERR_HIP, "grouped gemv launch: %s", hip_error_name(e));
-        return LCD_OK;
-    }
-    // batched tokens: the layers run one after the other on the stream and share the workspace
-    for (int i = 0; i < count; ++i) {
-        const lcd_gemv_problem &p = problems[i];
-        const GemvPlan plan = plan_gemv(M, p.N, p.K, bits);
-        if (int e = launch_gemv(p.packed, p.lut, p.x, p.s, p.y, M, p.N, p.K, bits, workspace, plan, stream))
-            return fail(LCD_ERR_HIP, "gemv launch: %s", hip_error_name(e));
-    }
+    GroupItem items[kMaxGroup];
+    for (int i = 0; i < count; ++i)
+        items[i] = GroupItem{problems[i].packed, problems[i].lut, problems[i].x, problems[i].s, problems[i].y, problems[i].N, problems[i].K};
+    if (int e = launch_decode_group(items, count, M, bits, stream)) return fail(LCD_ERR_HIP, "grouped gemv launch: %s", hip_error_name(e));
     return LCD_OK;
 }
 

@@ -140,19 +140,17 @@ __global__ void __launch_bounds__(256) build_lut_kernel(const uint16_t *__restri
 }
 
 // ---- activation smoothing: xs[m][k] = fp16( x[m][k] / s[k] )  (paper Sec. 3.4) -------------
-// One thread per group of 8 consecutive k.  Output order:
-//   LAYOUT 0: [M][K], inside each group of 8 the slot order 0,4,1,5,2,6,3,7 that the register
-//             dequantiser produces (batched decode path);
-//   LAYOUT 1: operand order of v_mfma_f32_32x32x16_f16 for the prefill path:
-//             [chunk k/256][token block m/32][half (k%256)/128][step g=(k%64)/8][(k%128)/64][m%32][8 slots],
-//             tokens padded with zeros up to Mpad (a multiple of 128).
-template <int LAYOUT>
+// Prefill path only (the decode kernels smooth in place).  One thread per group of 8 consecutive
+// k; inside a group the slot order is 0,4,1,5,2,6,3,7, the one the register dequantiser produces.
+// Output: operand order of v_mfma_f32_32x32x16_f16,
+//   [chunk k/256][token block m/32][half (k%256)/128][step g=(k%64)/8][(k%128)/64][m%32][8 slots],
+// tokens padded with zeros up to Mpad (a multiple of 128).
 __global__ void __launch_bounds__(256) smooth_kernel(const uint16_t *__restrict__ x, const float *__restrict__ s,
                                                      _Float16 *__restrict__ xs, int M, int Mpad, int K)
 {
     const long long grp = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     const int kg = K / 8;
-    const long long total = (long long)(LAYOUT == 0 ? M : Mpad) * kg;
+    const long long total = (long long)Mpad * kg;
     if (grp >= total) return;
     const int m = (int)(grp / kg);
     const int k = (int)(grp % kg) * 8;
@@ -171,40 +169,16 @@ __global__ void __launch_bounds__(256) smooth_kernel(const uint16_t *__restrict_
 #pragma unroll
         for (int e = 0; e < 8; ++e) o[e] = (_Float16)0.0f;
     }
-    size_t dst;
-    if (LAYOUT == 0) {
-        dst = (size_t)m * K + k;
-    } else {
-        const int c = k >> 8, h = (k >> 7) & 1, kh = (k >> 6) & 1, g = (k >> 3) & 7;
-        dst = ((((((size_t)c * (Mpad >> 5) + (m >> 5)) * 2 + h) * 8 + g) * 2 + kh) * 32 + (m & 31)) * 8;
-    }
+    const int c = k >> 8, h = (k >> 7) & 1, kh = (k >> 6) & 1, g = (k >> 3) & 7;
+    const size_t dst = ((((((size_t)c * (Mpad >> 5) + (m >> 5)) * 2 + h) * 8 + g) * 2 + kh) * 32 + (m & 31)) * 8;
     *reinterpret_cast<half8 *>(xs + dst) = o;
 }
 
-// ---- split-K reduction: y = fp16( sum_s partial[s] ), fixed order --------------------------
-__global__ void __launch_bounds__(256) reduce_kernel(const float *__restrict__ partial, uint16_t *__restrict__ y,
-                                                     int splits, long long total)
+int launch_smooth(const uint16_t *x, const float *s, void *xs, int M, int Mpad, int K, void *stream)
 {
-    const long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= total) return;
-    float acc = 0.f;
-    for (int sidx = 0; sidx < splits; ++sidx) acc += partial[(size_t)sidx * total + e];
-    y[e] = __builtin_bit_cast(uint16_t, (_Float16)acc);
-}
-
-int launch_smooth(const uint16_t *x, const float *s, void *xs, int M, int Mpad, int K, int layout, void *stream)
-{
-    const long long threads = (long long)(layout == 0 ? M : Mpad) * (K / 8);
+    const long long threads = (long long)Mpad * (K / 8);
     const dim3 grid((unsigned)((threads + 255) / 256)), block(256);
-    if (layout == 0) hipLaunchKernelGGL(smooth_kernel<0>, grid, block, 0, (hipStream_t)stream, x, s, (_Float16 *)xs, M, Mpad, K);
-    else hipLaunchKernelGGL(smooth_kernel<1>, grid, block, 0, (hipStream_t)stream, x, s, (_Float16 *)xs, M, Mpad, K);
-    return (int)hipGetLastError();
-}
-
-int launch_reduce(const float *partial, uint16_t *y, int splits, long long total, void *stream)
-{
-    hipLaunchKernelGGL(reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
-                       partial, y, splits, total);
+    hipLaunchKernelGGL(smooth_kernel, grid, block, 0, (hipStream_t)stream, x, s, (_Float16 *)xs, M, Mpad, K);
     return (int)hipGetLastError();
 }
 
