@@ -20,6 +20,7 @@
 // contiguous K range; their partial outputs meet in LDS (fixed order).  If K needs more than
 // one workgroup, fp32 partials go to the workspace and a second kernel adds them.
 #include <hip/hip_runtime.h>
+#include <algorithm>
 #include "lcd_internal.h"
 #include "lcd_device.h"
 
@@ -54,6 +55,10 @@ constexpr uint32_t kOob = 0xFFFFFFF0u;
 constexpr int kBW = 8;            // waves per workgroup
 constexpr int kBCH = 2;           // chunks per wave per segment (their activations stay in registers)
 constexpr int kBSeg = kBW * kBCH; // chunks per segment (one pass of the workgroup over K)
+// chunk `ch` of wave `wave` in segment `sg`: chunks go round the waves, so that a short last segment
+// spreads over as many waves (and SIMDs) as it has chunks
+template <int CH = 2>
+__device__ __forceinline__ int wave_chunk(int sg, int wave, int ch) { return sg * (kBW * CH) + ch * kBW + wave; }
 constexpr int kSets = 4;          // register sets in rotation (loads run kSets-1 steps ahead)
 constexpr int kVisitTiles = 32;   // row tiles per visit
 
@@ -130,7 +135,7 @@ __device__ __forceinline__ void issue_step_loads(StepRegs<BITS> &r, const Cursor
     const bool tv = !c.done && tile < c.v1;
 #pragma unroll
     for (int ch = 0; ch < kBCH; ++ch) {
-        const int chunk = c.sg * kBSeg + wave * kBCH + ch;
+        const int chunk = wave_chunk(c.sg, wave, ch);
         const bool v = tv && chunk < kc;
         const uint32_t o = ((uint32_t)tile * (uint32_t)kc + (uint32_t)chunk) * TB;
         r.lo[ch] = __builtin_amdgcn_raw_buffer_load_b128(rs, v ? o + 16 * lane : kOob, 0, 0);
@@ -181,11 +186,11 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const BucketBa
     // one segment ahead; the very first ones head the kernel, before the tile loads, because they
     // start the longest dependency chain.  Reads past the end of x / s return zero through the
     // buffer resource.
-    const int groups = kc * (kTileCols / 8);
     uint4v xv;
     float4v s0, s1;
     auto load_x = [&](int sg, bool valid) {
-        const uint32_t g = (uint32_t)sg * NT + threadIdx.x;
+        const uint32_t g = (uint32_t)wave_chunk(sg, wave, lane >> 5) * 32 + (lane & 31);   // group of 8 columns
+        valid = valid && g < (uint32_t)kc * 32;
         xv = __builtin_amdgcn_raw_buffer_load_b128(rs_x, valid ? g * 16 : kOob, 0, 0);
         s0 = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(rs_s, valid ? g * 32 : kOob, 0, 0));
         s1 = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(rs_s, valid ? g * 32 + 16 : kOob, 0, 0));
@@ -205,6 +210,7 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const BucketBa
     issue_step_loads<BITS>(r0, pf, rs_packed, kc, wave, lane); cursor_advance(pf, nseg);
 
     uint4v A[kBCH][8];   // this wave's smoothed activations of the current segment, 8 operands per chunk
+    bool chunk_in_k[kBCH] = {};   // wave-uniform: a short last segment leaves some of the wave's chunks empty
     half16 B1;        // constant routing matrix (index c -> column c), built after the prologue
     float *my_part = part + wave * (kVisitTiles * 16);
     LCD_STAMP(1);
@@ -214,6 +220,7 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const BucketBa
         float4v accx = {0.f, 0.f, 0.f, 0.f}, accy = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ch = 0; ch < kBCH; ++ch) {
+            if (!chunk_in_k[ch]) continue;
 #pragma unroll
             for (int d = 0; d < 4; ++d) {
                 const int idxreg = (int)r.lo[ch][d];
@@ -332,21 +339,23 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const BucketBa
         for (int b = 0; b < 16; ++b) B1[b] = ((b & 3) == j) ? (_Float16)1.0f : (_Float16)0.0f;
         for (cur.sg = 0; cur.sg < nseg; ++cur.sg) {
             {   // smooth this thread's 8 activations of the segment (loaded one segment ago)
-                const int g = cur.sg * NT + (int)threadIdx.x;
+                const bool in_k = wave_chunk(cur.sg, wave, lane >> 5) < kc;
                 half8 o;
 #pragma unroll
                 for (int e = 0; e < 8; ++e)
-                    o[e] = g < groups ? smooth_one((uint16_t)(xv[e >> 1] >> (16 * (e & 1))), e < 4 ? s0[e] : s1[e - 4]) : (_Float16)0.0f;
+                    o[e] = in_k ? smooth_one((uint16_t)(xv[e >> 1] >> (16 * (e & 1))), e < 4 ? s0[e] : s1[e - 4]) : (_Float16)0.0f;
                 *reinterpret_cast<half8 *>(&xs_lds[8 * threadIdx.x]) = o;
                 // next segment's activations: of this visit, or segment 0 again for the next visit
                 const bool more = cur.sg + 1 < nseg;
                 load_x(more ? cur.sg + 1 : 0, more || cur.v1 < cur.range_end);
             }
 #pragma unroll
-            for (int ch = 0; ch < kBCH; ++ch)
+            for (int ch = 0; ch < kBCH; ++ch) {
+                chunk_in_k[ch] = wave_chunk(cur.sg, wave, ch) < kc;
 #pragma unroll
                 for (int g = 0; g < 8; ++g)   // written by this wave only: no barrier
                     A[ch][g] = *reinterpret_cast<const uint4v *>(&xs_lds[(wave * kBCH + ch) * kTileCols + 64 * q + 8 * g]);
+            }
             for (cur.i = 0; cur.i < cur.steps;) four_steps();
         }
         LCD_STAMP(4);
@@ -374,33 +383,33 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const BucketBa
 // kSets-1 steps ahead), but the 16 columns of the matrix core's output tile are the tokens: the
 // packed indices are dequantised in registers (v_perm_b32 through per-row byte-split codebook
 // tables) into the A operand of v_mfma_f32_16x16x32_f16, and the smoothed activations of the
-// wave's two chunks, all tokens, stay in registers as B operands for a whole segment.
+// wave's CH chunks, all tokens, stay in registers as B operands for a whole segment.
 //   segment start  every wave smooths its own 512 columns of every token (Sec. 3.4: x / s) and
 //                  fans them out to the B-operand layout through its own LDS stage: no workgroup
 //                  synchronisation;
-//   step           one row tile: 16 MFMAs per wave; the 8 waves' 16x16 partial tiles meet in LDS
-//                  (double-buffered, one s_barrier per step, no wait on outstanding loads) and
-//                  256 threads add them in a fixed order.  With one segment the sum is rounded
+//   step           one row tile: 16 MFMAs per wave; after every second step the 8 waves' 16x16
+//                  partial tiles of both meet in LDS (double-buffered, one s_barrier, no wait on
+//                  outstanding loads) and the 512 threads add them in a fixed order.  With one segment the sum is rounded
 //                  and stored; with several it accumulates in LDS until the last segment.
 constexpr int kStageStride = kTileCols + 8;   // halfs per token row of a wave's stage (+16 B: no bank conflicts)
 
-template <int BITS>
+template <int BITS, int CH>
 struct TokStepRegs {
-    uint4v lo[kBCH];
-    uint2v hi[kBCH];
+    uint4v lo[CH];
+    uint2v hi[CH];
     uint4v tb;         // the lane's row of byte-split codebook tables
 };
 
-template <int BITS>
-__device__ __forceinline__ void issue_tok_loads(TokStepRegs<BITS> &r, const Cursor &c, __amdgpu_buffer_rsrc_t rs,
+template <int BITS, int CH>
+__device__ __forceinline__ void issue_tok_loads(TokStepRegs<BITS, CH> &r, const Cursor &c, __amdgpu_buffer_rsrc_t rs,
                                                 __amdgpu_buffer_rsrc_t rs_tb, int kc, int wave, int lane)
 {
     constexpr uint32_t TB = BITS == 2 ? 1024 : 1536;
     const int tile = c.v0 + c.i;
     const bool tv = !c.done && tile < c.v1;
 #pragma unroll
-    for (int ch = 0; ch < kBCH; ++ch) {
-        const int chunk = c.sg * kBSeg + wave * kBCH + ch;
+    for (int ch = 0; ch < CH; ++ch) {
+        const int chunk = wave_chunk<CH>(c.sg, wave, ch);
         const bool v = tv && chunk < kc;
         const uint32_t o = ((uint32_t)tile * (uint32_t)kc + (uint32_t)chunk) * TB;
         r.lo[ch] = __builtin_amdgcn_raw_buffer_load_b128(rs, v ? o + 16 * lane : kOob, 0, 0);
@@ -415,16 +424,16 @@ __device__ __forceinline__ void issue_tok_loads(TokStepRegs<BITS> &r, const Curs
     }
 }
 
-template <int BITS>
+template <int BITS, int CH>
 __global__ void __launch_bounds__(kBW * 64, 1) gemv_tokens_kernel(const BucketBatch batch, const int M)
 {
     constexpr int NC = BITS == 2 ? 4 : 8;
     constexpr uint32_t TB = BITS == 2 ? 1024 : 1536;
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
-    // LDS: [ stage: kBW x 16 tokens x kStageStride halfs ][ red: 2 x kBW x 256 floats ][ sums: kVisitTiles x 256 floats ]
+    // LDS: [ stage: kBW x 16 tokens x kStageStride halfs ][ red: 2 x 2 x kBW x 256 floats ][ sums: kVisitTiles x 256 floats ]
     _Float16 *stage = reinterpret_cast<_Float16 *>(smem) ;
     float *red = reinterpret_cast<float *>(smem + (size_t)kBW * 16 * kStageStride * 2);
-    float *sums = red + 2 * kBW * 256;
+    float *sums = red + 2 * 2 * kBW * 256;
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -436,7 +445,7 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_tokens_kernel(const BucketBa
     const int li = (int)blockIdx.x - batch.wg_begin[pi];
     const int ta = li * pb.tiles_base + min(li, pb.tiles_extra);
     const int tb_end = ta + pb.tiles_base + (li < pb.tiles_extra ? 1 : 0);
-    const int kc = pb.kc, nseg = (kc + kBSeg - 1) / kBSeg, K = kc * kTileCols, N = pb.nt * kTileRows;
+    const int kc = pb.kc, nseg = (kc + kBW * CH - 1) / (kBW * CH), K = kc * kTileCols, N = pb.nt * kTileRows;
     const __amdgpu_buffer_rsrc_t rs_packed = make_rsrc(pb.packed, (uint32_t)pb.nt * (uint32_t)kc * TB);
     const __amdgpu_buffer_rsrc_t rs_x = make_rsrc(pb.x, (uint32_t)M * (uint32_t)K * 2);
     const __amdgpu_buffer_rsrc_t rs_s = make_rsrc(pb.s, (uint32_t)K * 4);
@@ -447,19 +456,20 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_tokens_kernel(const BucketBa
     cur = pf;
     if (cur.done) return;
 
-    TokStepRegs<BITS> r0, r1, r2, r3;
-    uint4v Bx[kBCH][8];                      // B operands: lane (q, token j) holds 8 activations per MFMA
+    TokStepRegs<BITS, CH> r0, r1, r2, r3;
+    uint4v Bx[CH][8];                      // B operands: lane (q, token j) holds 8 activations per MFMA
+    bool chunk_in_k[CH] = {};                // wave-uniform: a short last segment leaves some chunks empty
     _Float16 *my_stage = stage + wave * (16 * kStageStride);
 
-    // Smooth the wave's two chunks of segment sg for all tokens and load them as B operands.
+    // Smooth the wave's CH chunks of segment sg for all tokens and load them as B operands.
     // Lane l covers the 8 columns [8*(l&31), +8) of a chunk for the tokens 8*(l>>5) .. +7.
-    auto load_activations = [&](int sg) {
+    uint4v xr[CH][8];
+    float4v sa[CH], sb[CH];
+    auto issue_activation_loads = [&](int sg) {
         const int kg = lane & 31, th = lane >> 5;
-        uint4v xr[kBCH][8];
-        float4v sa[kBCH], sb[kBCH];
 #pragma unroll
-        for (int ch = 0; ch < kBCH; ++ch) {
-            const int chunk = sg * kBSeg + wave * kBCH + ch;
+        for (int ch = 0; ch < CH; ++ch) {
+            const int chunk = wave_chunk<CH>(sg, wave, ch);
             const uint32_t k0 = (uint32_t)chunk * kTileCols + 8 * kg;
             const bool cv = chunk < kc;
             sa[ch] = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(rs_s, cv ? k0 * 4 : kOob, 0, 0));
@@ -470,9 +480,13 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_tokens_kernel(const BucketBa
                 xr[ch][mm] = __builtin_amdgcn_raw_buffer_load_b128(rs_x, (cv && m < M) ? ((uint32_t)m * (uint32_t)K + k0) * 2 : kOob, 0, 0);
             }
         }
+    };
+    auto finish_activations = [&](int sg) {
+        const int kg = lane & 31, th = lane >> 5;
 #pragma unroll
-        for (int ch = 0; ch < kBCH; ++ch) {
-            const bool cv = sg * kBSeg + wave * kBCH + ch < kc;
+        for (int ch = 0; ch < CH; ++ch) {
+            const bool cv = wave_chunk<CH>(sg, wave, ch) < kc;
+            chunk_in_k[ch] = cv;
             float rs[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) rs[e] = cv ? __builtin_amdgcn_rcpf(e < 4 ? sa[ch][e] : sb[ch][e - 4]) : 0.0f;
@@ -492,13 +506,14 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_tokens_kernel(const BucketBa
         }
     };
 
-    auto tile_product = [&](const TokStepRegs<BITS> &r) -> float4v {
+    auto tile_product = [&](const TokStepRegs<BITS, CH> &r) -> float4v {
         float4v acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
         RowTables t;
         if (BITS == 2) { t.lo[0] = r.tb[0]; t.hi[0] = r.tb[1]; t.lo[1] = 0; t.hi[1] = 0; }
         else { t.lo[0] = r.tb[0]; t.lo[1] = r.tb[1]; t.hi[0] = r.tb[2]; t.hi[1] = r.tb[3]; }
 #pragma unroll
-        for (int ch = 0; ch < kBCH; ++ch) {
+        for (int ch = 0; ch < CH; ++ch) {
+            if (!chunk_in_k[ch]) continue;
             HighBits hb{0u, 0u};
             if (BITS == 3) hb = regroup_high(r.hi[ch]);
             uint4v op0, op1;
@@ -518,52 +533,76 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_tokens_kernel(const BucketBa
         return acc0 + acc1;   // lane (bq, j): rows 4bq..4bq+3 of token j
     };
 
-    // one step: this wave's partial tile -> LDS; barrier; fixed-order sum over the waves
+    // two steps: this wave's two partial tiles -> LDS; one barrier; every thread adds one output of
+    // one of the two tiles over the waves, in a fixed order
     int phase = 0;
-    auto finish_step = [&](float4v p, int tl) {
-        float *buf = red + phase * (kBW * 256);
-        *reinterpret_cast<float4v *>(&buf[wave * 256 + j * 16 + 4 * bq]) = p;
+    auto finish_pair = [&](float4v p0, float4v p1, int tl, bool second) {
+        float *buf = red + phase * (2 * kBW * 256);
+        *reinterpret_cast<float4v *>(&buf[wave * 256 + j * 16 + 4 * bq]) = p0;
+        *reinterpret_cast<float4v *>(&buf[(kBW + wave) * 256 + j * 16 + 4 * bq]) = p1;
         // LDS writes done, then the barrier; outstanding global loads keep flying
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-        if (threadIdx.x < 256) {
-            const int m = threadIdx.x >> 4, row = threadIdx.x & 15;
+        const int which = threadIdx.x >> 8, o = threadIdx.x & 255;   // waves 0-3: first tile, waves 4-7: second
+        if (which == 0 || second) {
+            const int m = o >> 4, row = o & 15;
             float sum = 0.f;
 #pragma unroll
-            for (int w = 0; w < kBW; ++w) sum += buf[w * 256 + threadIdx.x];
+            for (int w = 0; w < kBW; ++w) sum += buf[(which * kBW + w) * 256 + o];
             if (nseg > 1) {
-                float *slot = &sums[tl * 256 + threadIdx.x];
+                float *slot = &sums[(tl + which) * 256 + o];
                 if (cur.sg > 0) sum += *slot;
                 if (cur.sg + 1 < nseg) *slot = sum;
             }
             if (cur.sg + 1 == nseg && m < M)
-                pb.y[(size_t)m * N + (size_t)(cur.v0 + tl) * kTileRows + row] = __builtin_bit_cast(uint16_t, (_Float16)sum);
+                pb.y[(size_t)m * N + (size_t)(cur.v0 + tl + which) * kTileRows + row] = __builtin_bit_cast(uint16_t, (_Float16)sum);
         }
         phase ^= 1;
     };
 
     auto four_steps = [&]() {
         const int left = (cur.v1 - cur.v0) - cur.i;   // tiles left in this run; padding steps skip their work
-        issue_tok_loads<BITS>(r3, pf, rs_packed, rs_tb, kc, wave, lane); cursor_advance(pf, nseg);
-        finish_step(tile_product(r0), cur.i);
-        issue_tok_loads<BITS>(r0, pf, rs_packed, rs_tb, kc, wave, lane); cursor_advance(pf, nseg);
-        if (left > 1) finish_step(tile_product(r1), cur.i + 1);
-        issue_tok_loads<BITS>(r1, pf, rs_packed, rs_tb, kc, wave, lane); cursor_advance(pf, nseg);
-        if (left > 2) finish_step(tile_product(r2), cur.i + 2);
-        issue_tok_loads<BITS>(r2, pf, rs_packed, rs_tb, kc, wave, lane); cursor_advance(pf, nseg);
-        if (left > 3) finish_step(tile_product(r3), cur.i + 3);
+        const float4v zero = {0.f, 0.f, 0.f, 0.f};
+        float4v p0, p1 = zero;
+        issue_tok_loads<BITS, CH>(r3, pf, rs_packed, rs_tb, kc, wave, lane); cursor_advance(pf, nseg);
+        p0 = tile_product(r0);
+        issue_tok_loads<BITS, CH>(r0, pf, rs_packed, rs_tb, kc, wave, lane); cursor_advance(pf, nseg);
+        if (left > 1) p1 = tile_product(r1);
+        finish_pair(p0, p1, cur.i, left > 1);
+        issue_tok_loads<BITS, CH>(r1, pf, rs_packed, rs_tb, kc, wave, lane); cursor_advance(pf, nseg);
+        p1 = zero;
+        if (left > 2) p0 = tile_product(r2);
+        issue_tok_loads<BITS, CH>(r2, pf, rs_packed, rs_tb, kc, wave, lane); cursor_advance(pf, nseg);
+        if (left > 3) p1 = tile_product(r3);
+        if (left > 2) finish_pair(p0, p1, cur.i + 2, left > 3);
         cur.i += 4;
     };
 
-    issue_tok_loads<BITS>(r0, pf, rs_packed, rs_tb, kc, wave, lane); cursor_advance(pf, nseg);
-    issue_tok_loads<BITS>(r1, pf, rs_packed, rs_tb, kc, wave, lane); cursor_advance(pf, nseg);
-    issue_tok_loads<BITS>(r2, pf, rs_packed, rs_tb, kc, wave, lane); cursor_advance(pf, nseg);
+    LCD_STAMP(0);
+    issue_activation_loads(0);   // they start the longest dependency chain: ahead of the tile loads
+    issue_tok_loads<BITS, CH>(r0, pf, rs_packed, rs_tb, kc, wave, lane); cursor_advance(pf, nseg);
+    issue_tok_loads<BITS, CH>(r1, pf, rs_packed, rs_tb, kc, wave, lane); cursor_advance(pf, nseg);
+    issue_tok_loads<BITS, CH>(r2, pf, rs_packed, rs_tb, kc, wave, lane); cursor_advance(pf, nseg);
+    LCD_STAMP(1);
+    finish_activations(0);
+    bool primed = true;   // the first segment's activations are in place
     while (!cur.done) {
         for (cur.sg = 0; cur.sg < nseg; ++cur.sg) {
-            load_activations(cur.sg);
+            if (!primed) {
+                issue_activation_loads(cur.sg);
+                finish_activations(cur.sg);
+            }
+            primed = false;
+#ifdef LCD_TRACE
+            if (cur.sg < 4) LCD_STAMP(2 + cur.sg);
+#endif
             for (cur.i = 0; cur.i < cur.steps;) four_steps();
+#ifdef LCD_TRACE
+            if (lane == 0 && batch.trace && cur.sg < 4) batch.trace[blockIdx.x * 16 + 8 + cur.sg * 2 + (wave >> 2)] = __builtin_amdgcn_s_memrealtime();
+#endif
         }
         cursor_next_visit(cur);
     }
+    LCD_STAMP(6);
 }
 
 #ifdef LCD_TRACE
@@ -594,46 +633,55 @@ int launch_decode_group(const GroupItem *items, int count, int M, int bits, void
         p.lutA = (const float *)items[i].lut;
         p.x = items[i].x; p.s = items[i].s; p.y = items[i].y;
         p.nt = items[i].N / kTileRows; p.kc = items[i].K / kTileCols;
-        cost[i] = (long long)p.nt * ((p.kc + kBSeg - 1) / kBSeg);   // steps: every row tile takes one step per segment
+        cost[i] = (long long)p.nt * p.kc;
         total += cost[i];
         tiles += p.nt;
     }
-    // Workgroups per layer.  A layer's time is that of its slowest workgroup, in units of steps:
-    // a fixed start-up, then for each K segment one step per row tile plus the cost of switching
-    // to the segment's activations.  A 2-bit step moves half the bytes and has no sign-flip
-    // arithmetic, so the fixed costs are worth more of them.  Start from 7/8 of the proportional
-    // share, then hand out the rest one by one to the layer that is slowest at that moment.
+    // Workgroups per layer.  A layer's time is that of its slowest workgroup, in units of two-chunk
+    // steps: a fixed start-up, then for each K segment one pass over its row tiles plus the cost of
+    // switching to the segment's activations.  A wave takes `ch` chunks of a full segment; a short
+    // last segment gives every wave ceil(rest / 8).  Start from 7/8 of the proportional share, then
+    // hand out the rest one by one to the layer that is slowest at that moment.
     int grid = num_cus();
     if (grid > tiles) grid = tiles;
     if (grid < count) grid = count;
     const double startup_steps = M > 1 ? 3.0 : bits == 2 ? 4.0 : 2.0;
-    const double segment_steps = M > 1 ? 1.2 : bits == 2 ? 0.8 : 0.4;
-    auto layer_time = [&](int i, int n) {
-        const int segs = (batch.p[i].kc + kBSeg - 1) / kBSeg;
-        const int t = (batch.p[i].nt + n - 1) / n, visits = (t + kVisitTiles - 1) / kVisitTiles;
-        return startup_steps + segs * (t + visits * segment_steps);
-    };
-    int nwg[kMaxGroup], used = 0;
-    for (int i = 0; i < count; ++i) {
-        long long n = cost[i] * grid * 7 / (total * 8);
-        if (n < 1) n = 1;
-        if (n > batch.p[i].nt) n = batch.p[i].nt;
-        nwg[i] = (int)n;
-        used += nwg[i];
-    }
-    while (used < grid) {
-        int best = -1;
-        double best_time = 0.0;
+    const double segment_steps = M > 1 ? 1.5 : bits == 2 ? 0.8 : 0.4;
+    const double step_overhead = M > 1 ? 0.3 : 0.1;   // per tile and segment: barrier / bookkeeping
+    auto split = [&](int ch, int *nwg) {
+        const int seg = kBW * ch;
+        auto layer_time = [&](int i, int n) {
+            const int kc = batch.p[i].kc, segs = (kc + seg - 1) / seg, rest = kc % seg;
+            const double steps_per_tile = (kc / seg) * (0.5 * ch + step_overhead) +
+                                          (rest ? 0.5 * ((rest + kBW - 1) / kBW) + step_overhead : 0.0);
+            const int t = (batch.p[i].nt + n - 1) / n, visits = (t + kVisitTiles - 1) / kVisitTiles;
+            return startup_steps + steps_per_tile * t + segs * visits * segment_steps;
+        };
+        int used = 0;
         for (int i = 0; i < count; ++i) {
-            if (nwg[i] >= batch.p[i].nt) continue;
-            const double t = layer_time(i, nwg[i]);
-            if (t > best_time) { best_time = t; best = i; }
+            long long n = cost[i] * grid * 7 / (total * 8);
+            if (n < 1) n = 1;
+            if (n > batch.p[i].nt) n = batch.p[i].nt;
+            nwg[i] = (int)n;
+            used += nwg[i];
         }
-        if (best < 0) break;
-        ++nwg[best];
-        ++used;
-    }
-    grid = used;
+        while (used < grid) {
+            int best = -1;
+            double best_time = 0.0;
+            for (int i = 0; i < count; ++i) {
+                if (nwg[i] >= batch.p[i].nt) continue;
+                const double t = layer_time(i, nwg[i]);
+                if (t > best_time) { best_time = t; best = i; }
+            }
+            if (best < 0) break;
+            ++nwg[best];
+            ++used;
+        }
+    };
+    int nwg[kMaxGroup];
+    split(kBCH, nwg);
+    grid = 0;
+    for (int i = 0; i < count; ++i) grid += nwg[i];
     int acc = 0;
     for (int i = 0; i < count; ++i) {
         batch.wg_begin[i] = acc;
@@ -653,21 +701,17 @@ int launch_decode_group(const GroupItem *items, int count, int M, int bits, void
         lds = (size_t)kBSeg * kTileCols * 2 + (size_t)kVisitTiles * 16 * NC * 4 + (size_t)kBW * kVisitTiles * 16 * 4;
         fn = bits == 2 ? (const void *)gemv_bucket_kernel<2> : (const void *)gemv_bucket_kernel<3>;
     } else {
-        lds = (size_t)kBW * 16 * kStageStride * 2 + (size_t)2 * kBW * 256 * 4 + (size_t)kVisitTiles * 256 * 4;
-        fn = bits == 2 ? (const void *)gemv_tokens_kernel<2> : (const void *)gemv_tokens_kernel<3>;
+        lds = (size_t)kBW * 16 * kStageStride * 2 + (size_t)2 * 2 * kBW * 256 * 4 + (size_t)kVisitTiles * 256 * 4;
+        fn = bits == 2 ? (const void *)gemv_tokens_kernel<2, kBCH> : (const void *)gemv_tokens_kernel<3, kBCH>;
     }
-    static bool lds_set[2][2] = {{false, false}, {false, false}};
-    if (!lds_set[M > 1][bits - 2]) {
+    static bool lds_set[2][2] = {};
+    const int variant = M == 1 ? 0 : 1;
+    if (!lds_set[variant][bits - 2]) {
         if (hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)) return (int)e;
-        lds_set[M > 1][bits - 2] = true;
+        lds_set[variant][bits - 2] = true;
     }
-    if (M == 1) {
-        if (bits == 2) hipLaunchKernelGGL(gemv_bucket_kernel<2>, dim3(grid), dim3(kBW * 64), lds, stream, batch);
-        else hipLaunchKernelGGL(gemv_bucket_kernel<3>, dim3(grid), dim3(kBW * 64), lds, stream, batch);
-    } else {
-        if (bits == 2) hipLaunchKernelGGL(gemv_tokens_kernel<2>, dim3(grid), dim3(kBW * 64), lds, stream, batch, M);
-        else hipLaunchKernelGGL(gemv_tokens_kernel<3>, dim3(grid), dim3(kBW * 64), lds, stream, batch, M);
-    }
+    void *args[] = {&batch, const_cast<int *>(&M)};
+    if (hipError_t e = hipLaunchKernel(fn, dim3(grid), dim3(kBW * 64), args, lds, stream)) return (int)e;
     return (int)hipGetLastError();
 }
 

@@ -12,7 +12,7 @@ pytestmark = pytest.mark.gpu
 
 @pytest.mark.parametrize("bits", [2, 3])
 @pytest.mark.parametrize("M", [2, 3, 8, 16])
-@pytest.mark.parametrize("shape", [(16, 256), (48, 768), (80, 2304), (64, 11008), (32, 28672)])
+@pytest.mark.parametrize("shape", [(16, 256), (48, 768), (80, 2304), (64, 11008), (32, 28672), (96, 5120), (48, 6656), (32, 13824), (8208, 1280)])
 def test_gemv_batched_small(bits, M, shape):
     N, K = shape
     layer = synth.make_layer(2, 0, N, K, bits, M, seed_offset=N + K + M)

@@ -11,7 +11,7 @@ pytestmark = pytest.mark.gpu
 
 
 @pytest.mark.parametrize("bits", [2, 3])
-@pytest.mark.parametrize("shape", [(16, 256), (48, 768), (80, 2304), (256, 4096), (64, 11008), (96, 8192), (32, 28672), (16, 69632), (1088, 4352), (139264, 512)])
+@pytest.mark.parametrize("shape", [(16, 256), (48, 768), (80, 2304), (256, 4096), (64, 11008), (96, 8192), (32, 28672), (16, 69632), (1088, 4352), (139264, 512), (64, 5120), (48, 13824)])
 def test_gemv_m1_small(bits, shape):
     N, K = shape
     layer = synth.make_layer(0, 0, N, K, bits, 1, variant="B", seed_offset=N + K)
