@@ -32,8 +32,8 @@ MFMA_F16_PEAK_TFLOPS = 2500.0
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--config", type=int, default=1, help="benchmark config index (1 = the metric's workload)")
     ap.add_argument("--m", type=int, default=None, help="token count (default: the config's first M)")
     ap.add_argument("--replicas", type=int, default=0, help="packed-matrix replicas in rotation (0 = enough for 600 MB)")

@@ -159,12 +159,26 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const BucketBa
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: keeps addresses scalar
     const int q = lane >> 4, j = lane & 15, bq = lane >> 4;
+#ifdef LCD_TRACE
+    const unsigned long long tt0 = __builtin_amdgcn_s_memrealtime();
+#endif
     LCD_STAMP(0);
 
     // which layer, which row tiles
+    // (entries past the last layer hold the total, so they never count: no loop over `count`, and
+    // the whole table comes in one scalar load)
     int pi = 0;
-    for (int i = 1; i < batch.count; ++i) pi += ((int)blockIdx.x >= batch.wg_begin[i]) ? 1 : 0;
+#pragma unroll
+    for (int i = 1; i < kMaxGroup; ++i) pi += (int)((uint32_t)(batch.wg_begin[i] - 1 - (int)blockIdx.x) >> 31);   // += (blockIdx.x >= wg_begin[i])
+#ifdef LCD_TRACE
+    asm volatile("" :: "s"(pi));
+    const unsigned long long tt1 = __builtin_amdgcn_s_memrealtime();
+#endif
     const BucketProblem pb = batch.p[pi];
+#ifdef LCD_TRACE
+    asm volatile("" :: "s"(pb.kc), "s"(pb.nt));
+    const unsigned long long tt2 = __builtin_amdgcn_s_memrealtime();
+#endif
     const int li = (int)blockIdx.x - batch.wg_begin[pi];
     const int ta = li * pb.tiles_base + min(li, pb.tiles_extra);
     const int tb = ta + pb.tiles_base + (li < pb.tiles_extra ? 1 : 0);
@@ -177,7 +191,6 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const BucketBa
     Cursor pf{}, cur{};
     cursor_begin(pf, ta, tb);
     cur = pf;
-    if (cur.done) return;
 
     // Activations.  A segment is kBSeg*256 = 8 * (threads of the workgroup) columns, and thread t of
     // wave w smooths columns [8t, 8t+8) of it -- which lie in wave w's own two chunks.  So a wave
@@ -195,6 +208,9 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const BucketBa
         s0 = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(rs_s, valid ? g * 32 : kOob, 0, 0));
         s1 = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(rs_s, valid ? g * 32 + 16 : kOob, 0, 0));
     };
+#ifdef LCD_TRACE
+    const unsigned long long tt3 = __builtin_amdgcn_s_memrealtime();
+#endif
     load_x(0, true);
     // multipliers of the first visit: (tiles * 4 * NC) float4, at most CFR per thread
     constexpr int CFR = kVisitTiles * 4 * NC / NT;
@@ -208,6 +224,7 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const BucketBa
     }
     StepRegs<BITS> r0, r1, r2, r3;
     issue_step_loads<BITS>(r0, pf, rs_packed, kc, wave, lane); cursor_advance(pf, nseg);
+    if (cur.done) return;   // no row tiles (the host never launches such a workgroup); the loads above moved nothing
 
     uint4v A[kBCH][8];   // this wave's smoothed activations of the current segment, 8 operands per chunk
     bool chunk_in_k[kBCH] = {};   // wave-uniform: a short last segment leaves some of the wave's chunks empty
@@ -315,6 +332,9 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const BucketBa
     };
 
     bool first_visit = true;
+#ifdef LCD_TRACE
+    bool first_stamp = true;
+#endif
     while (!cur.done) {
         // ---- visit prologue (the barrier that ended the previous visit protects the LDS reuse)
         if (first_visit) {
@@ -335,6 +355,9 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const BucketBa
         LCD_STAMP(2);
         __syncthreads();
         LCD_STAMP(3);
+#ifdef LCD_TRACE
+        if (threadIdx.x == 0 && batch.trace && first_stamp) { batch.trace[blockIdx.x * 16 + 13] = tt0; batch.trace[blockIdx.x * 16 + 14] = tt1; batch.trace[blockIdx.x * 16 + 15] = tt2; batch.trace[blockIdx.x * 16 + 12] = tt3; first_stamp = false; }
+#endif
 #pragma unroll
         for (int b = 0; b < 16; ++b) B1[b] = ((b & 3) == j) ? (_Float16)1.0f : (_Float16)0.0f;
         for (cur.sg = 0; cur.sg < nseg; ++cur.sg) {
@@ -360,7 +383,7 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const BucketBa
         }
         LCD_STAMP(4);
 #ifdef LCD_TRACE
-        if (lane == 0 && batch.trace && wave < 8) batch.trace[blockIdx.x * 16 + 8 + wave] = __builtin_amdgcn_s_memrealtime();
+        if (lane == 0 && batch.trace && wave < 4) batch.trace[blockIdx.x * 16 + 8 + wave] = __builtin_amdgcn_s_memrealtime();
 #endif
         __syncthreads();
         LCD_STAMP(5);
@@ -440,7 +463,8 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_tokens_kernel(const BucketBa
     const int q = lane >> 4, j = lane & 15, bq = lane >> 4;
 
     int pi = 0;
-    for (int i = 1; i < batch.count; ++i) pi += ((int)blockIdx.x >= batch.wg_begin[i]) ? 1 : 0;
+#pragma unroll
+    for (int i = 1; i < kMaxGroup; ++i) pi += (int)((uint32_t)(batch.wg_begin[i] - 1 - (int)blockIdx.x) >> 31);   // += (blockIdx.x >= wg_begin[i])
     const BucketProblem pb = batch.p[pi];
     const int li = (int)blockIdx.x - batch.wg_begin[pi];
     const int ta = li * pb.tiles_base + min(li, pb.tiles_extra);
@@ -454,7 +478,6 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_tokens_kernel(const BucketBa
     Cursor pf{}, cur{};
     cursor_begin(pf, ta, tb_end);
     cur = pf;
-    if (cur.done) return;
 
     TokStepRegs<BITS, CH> r0, r1, r2, r3;
     uint4v Bx[CH][8];                      // B operands: lane (q, token j) holds 8 activations per MFMA
@@ -583,6 +606,7 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_tokens_kernel(const BucketBa
     issue_tok_loads<BITS, CH>(r1, pf, rs_packed, rs_tb, kc, wave, lane); cursor_advance(pf, nseg);
     issue_tok_loads<BITS, CH>(r2, pf, rs_packed, rs_tb, kc, wave, lane); cursor_advance(pf, nseg);
     LCD_STAMP(1);
+    if (cur.done) return;   // no row tiles (the host never launches such a workgroup); the loads above moved nothing
     finish_activations(0);
     bool primed = true;   // the first segment's activations are in place
     while (!cur.done) {
