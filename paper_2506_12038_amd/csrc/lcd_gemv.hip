@@ -124,12 +124,19 @@ template <int BITS>
 struct StepRegs {
     uint4v lo[kBCH];   // the lane's 64 two-bit fields of this (tile, chunk)
     uint2v hi[kBCH];   // 3 bits only: its 64 third bits
+    uint4v cf;         // first step of a reduction group only: the lane's four per-bucket multipliers
 };
 
-template <int BITS>
-__device__ __forceinline__ void issue_step_loads(StepRegs<BITS> &r, const Cursor &c, __amdgpu_buffer_rsrc_t rs, int kc, int wave, int lane)
+// WITH_CF: this step opens a group of 16/NC row tiles that share one multiply-and-reduce; lane
+// (bq, j) then also fetches the multipliers of rows 4bq..4bq+3, bucket j % NC, of the group's
+// tile j / NC (fp32, accumulator order, straight from the table: every wave reads the same few
+// hundred bytes, so they come from the L1/L2 cache).
+template <int BITS, bool WITH_CF>
+__device__ __forceinline__ void issue_step_loads(StepRegs<BITS> &r, const Cursor &c, __amdgpu_buffer_rsrc_t rs,
+                                                 __amdgpu_buffer_rsrc_t rs_lut, int kc, int wave, int lane)
 {
     constexpr uint32_t TB = BITS == 2 ? 1024 : 1536;
+    constexpr int NC = BITS == 2 ? 4 : 8;
     // a finished cursor or a padding step issues loads that are out of range: zeros, no traffic
     const int tile = c.v0 + c.i;
     const bool tv = !c.done && tile < c.v1;
@@ -141,6 +148,11 @@ __device__ __forceinline__ void issue_step_loads(StepRegs<BITS> &r, const Cursor
         r.lo[ch] = __builtin_amdgcn_raw_buffer_load_b128(rs, v ? o + 16 * lane : kOob, 0, 0);
         if (BITS == 3) r.hi[ch] = __builtin_amdgcn_raw_buffer_load_b64(rs, v ? o + 1024 + 8 * lane : kOob, 0, 0);
     }
+    if (WITH_CF) {
+        const int j = lane & 15, bq = lane >> 4;
+        const int t = tile + j / NC;
+        r.cf = __builtin_amdgcn_raw_buffer_load_b128(rs_lut, (!c.done && t < c.v1) ? (uint32_t)((t * 4 + bq) * NC + (j % NC)) * 16 : kOob, 0, 0);
+    }
 }
 
 template <int BITS>
@@ -151,10 +163,9 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const BucketBa
     constexpr uint32_t TB = BITS == 2 ? 1024 : 1536;
     constexpr int NT = kBW * 64;
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
-    // LDS: [ xs: one segment, kBSeg*256 halfs ][ cf: kVisitTiles*16*NC floats ][ part: kBW*kVisitTiles*16 floats ]
+    // LDS: [ xs: one segment, kBSeg*256 halfs ][ part: kBW*kVisitTiles*16 floats ]
     _Float16 *xs_lds = reinterpret_cast<_Float16 *>(smem);
-    float *cf_lds = reinterpret_cast<float *>(smem + (size_t)kBSeg * kTileCols * 2);
-    float *part = cf_lds + kVisitTiles * 16 * NC;
+    float *part = reinterpret_cast<float *>(smem + (size_t)kBSeg * kTileCols * 2);
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: keeps addresses scalar
@@ -212,18 +223,8 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const BucketBa
     const unsigned long long tt3 = __builtin_amdgcn_s_memrealtime();
 #endif
     load_x(0, true);
-    // multipliers of the first visit: (tiles * 4 * NC) float4, at most CFR per thread
-    constexpr int CFR = kVisitTiles * 4 * NC / NT;
-    static_assert(CFR * NT == kVisitTiles * 4 * NC, "multiplier preload must cover a full visit");
-    const int nf4_first = (cur.v1 - cur.v0) * 4 * NC;
-    uint4v cfv[CFR];
-#pragma unroll
-    for (int u = 0; u < CFR; ++u) {
-        const int e = u * NT + (int)threadIdx.x;
-        cfv[u] = __builtin_amdgcn_raw_buffer_load_b128(rs_lut, e < nf4_first ? ((uint32_t)cur.v0 * 4 * NC + e) * 16 : kOob, 0, 0);
-    }
     StepRegs<BITS> r0, r1, r2, r3;
-    issue_step_loads<BITS>(r0, pf, rs_packed, kc, wave, lane); cursor_advance(pf, nseg);
+    issue_step_loads<BITS, true>(r0, pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
     if (cur.done) return;   // no row tiles (the host never launches such a workgroup); the loads above moved nothing
 
     uint4v A[kBCH][8];   // this wave's smoothed activations of the current segment, 8 operands per chunk
@@ -275,10 +276,9 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const BucketBa
     };
 
     // TG tiles share one multiply-and-reduce: tile u of the group moves to columns [u*NC, (u+1)*NC)
-    auto reduce_group = [&](float4v m, int tl0) {
+    auto reduce_group = [&](float4v m, int tl0, uint4v cfreg) {
         const int tl = tl0 + j / NC;                    // this lane's tile inside the visit
-        float4v cf = {0.f, 0.f, 0.f, 0.f};
-        if (cur.v0 + tl < cur.v1) cf = *reinterpret_cast<const float4v *>(&cf_lds[((tl * 4 + bq) * NC + (j % NC)) * 4]);
+        const float4v cf = __builtin_bit_cast(float4v, cfreg);   // zeros past the end of the visit
         float4v pv;
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
@@ -302,23 +302,25 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const BucketBa
         const int left = (cur.v1 - cur.v0) - cur.i;
         const float4v zero = {0.f, 0.f, 0.f, 0.f};
         float4v t0, t1 = zero, t3 = zero;
-        issue_step_loads<BITS>(r3, pf, rs_packed, kc, wave, lane); cursor_advance(pf, nseg);
+        issue_step_loads<BITS, false>(r3, pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
         t0 = tile_sums(r0);
-        issue_step_loads<BITS>(r0, pf, rs_packed, kc, wave, lane); cursor_advance(pf, nseg);
+        const uint4v cf_a = r0.cf;   // taken before the set is loaded again
+        issue_step_loads<BITS, true>(r0, pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
         if (left > 1) t1 = tile_sums(r1);
 #pragma unroll
         for (int u = 0; u < 4; ++u) t0[u] += dpp_f32<(TG == 2 ? 0x118 : 0x114)>(t1[u]);   // row_shr:8 / row_shr:4
-        if (TG == 2) reduce_group(t0, cur.i);
-        issue_step_loads<BITS>(r1, pf, rs_packed, kc, wave, lane); cursor_advance(pf, nseg);
+        if (TG == 2) reduce_group(t0, cur.i, cf_a);
+        issue_step_loads<BITS, false>(r1, pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
         t1 = zero;
         if (left > 2) t1 = tile_sums(r2);
-        issue_step_loads<BITS>(r2, pf, rs_packed, kc, wave, lane); cursor_advance(pf, nseg);
+        const uint4v cf_b = r2.cf;
+        issue_step_loads<BITS, TG == 2>(r2, pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
         if (left > 3) t3 = tile_sums(r3);
         if (TG == 2) {
             if (left > 2) {
 #pragma unroll
                 for (int u = 0; u < 4; ++u) t1[u] += dpp_f32<0x118>(t3[u]);
-                reduce_group(t1, cur.i + 2);
+                reduce_group(t1, cur.i + 2, cf_b);
             }
         } else {
 #pragma unroll
@@ -326,38 +328,21 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const BucketBa
                 t1[u] += dpp_f32<0x114>(t3[u]);
                 t0[u] += dpp_f32<0x118>(t1[u]);
             }
-            reduce_group(t0, cur.i);
+            reduce_group(t0, cur.i, cf_a);
         }
         cur.i += 4;
     };
 
-    bool first_visit = true;
+    // the remaining two sets of the pipeline
+    issue_step_loads<BITS, false>(r1, pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
+    issue_step_loads<BITS, TG == 2>(r2, pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
+    LCD_STAMP(2);
 #ifdef LCD_TRACE
-    bool first_stamp = true;
+    if (threadIdx.x == 0 && batch.trace) { batch.trace[blockIdx.x * 16 + 13] = tt0; batch.trace[blockIdx.x * 16 + 14] = tt1; batch.trace[blockIdx.x * 16 + 15] = tt2; batch.trace[blockIdx.x * 16 + 12] = tt3; }
 #endif
     while (!cur.done) {
-        // ---- visit prologue (the barrier that ended the previous visit protects the LDS reuse)
-        if (first_visit) {
-#pragma unroll
-            for (int u = 0; u < CFR; ++u) {
-                const int e = u * NT + (int)threadIdx.x;
-                if (e < nf4_first) reinterpret_cast<uint4v *>(cf_lds)[e] = cfv[u];
-            }
-            // the remaining two sets of the pipeline
-            issue_step_loads<BITS>(r1, pf, rs_packed, kc, wave, lane); cursor_advance(pf, nseg);
-            issue_step_loads<BITS>(r2, pf, rs_packed, kc, wave, lane); cursor_advance(pf, nseg);
-            first_visit = false;
-        } else {
-            const int nf4 = (cur.v1 - cur.v0) * 4 * NC;   // float4 count of the visit's multipliers
-            for (int e = threadIdx.x; e < nf4; e += NT)
-                reinterpret_cast<uint4v *>(cf_lds)[e] = __builtin_amdgcn_raw_buffer_load_b128(rs_lut, ((uint32_t)cur.v0 * 4 * NC + e) * 16, 0, 0);
-        }
-        LCD_STAMP(2);
-        __syncthreads();
-        LCD_STAMP(3);
-#ifdef LCD_TRACE
-        if (threadIdx.x == 0 && batch.trace && first_stamp) { batch.trace[blockIdx.x * 16 + 13] = tt0; batch.trace[blockIdx.x * 16 + 14] = tt1; batch.trace[blockIdx.x * 16 + 15] = tt2; batch.trace[blockIdx.x * 16 + 12] = tt3; first_stamp = false; }
-#endif
+        // (no workgroup synchronisation at the start of a visit: activations and multipliers are
+        // per wave; the barrier that ends a visit's epilogue protects the reuse of `part`)
 #pragma unroll
         for (int b = 0; b < 16; ++b) B1[b] = ((b & 3) == j) ? (_Float16)1.0f : (_Float16)0.0f;
         for (cur.sg = 0; cur.sg < nseg; ++cur.sg) {
@@ -395,6 +380,7 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const BucketBa
             pb.y[(size_t)cur.v0 * kTileRows + e] = __builtin_bit_cast(uint16_t, (_Float16)sum);
         }
         cursor_next_visit(cur);
+        if (!cur.done) __syncthreads();   // the next visit's waves overwrite their slots
         LCD_STAMP(6);
     }
 }
@@ -722,7 +708,7 @@ int launch_decode_group(const GroupItem *items, int count, int M, int bits, void
     size_t lds;
     const void *fn;
     if (M == 1) {
-        lds = (size_t)kBSeg * kTileCols * 2 + (size_t)kVisitTiles * 16 * NC * 4 + (size_t)kBW * kVisitTiles * 16 * 4;
+        lds = (size_t)kBSeg * kTileCols * 2 + (size_t)kBW * kVisitTiles * 16 * 4;
         fn = bits == 2 ? (const void *)gemv_bucket_kernel<2> : (const void *)gemv_bucket_kernel<3>;
     } else {
         lds = (size_t)kBW * 16 * kStageStride * 2 + (size_t)2 * 2 * kBW * 256 * 4 + (size_t)kVisitTiles * 256 * 4;
