@@ -69,23 +69,31 @@ __device__ __forceinline__ HighBits regroup_high(uint2v h)
 // 16d + [0,8)) and operand a=1 (weights 16d + [8,16)).  Register v of an operand holds the
 // fp16 pair (weight v, weight 4+v) of its 8 weights, so the activation operand must use the
 // slot order 0,4,1,5,2,6,3,7.
+// One quarter of decode_word: selector t (weights t, 4+t of operand 0 and of operand 1).
+template <int BITS, int D, int T>
+__device__ __forceinline__ void decode_quarter(uint32_t p, const HighBits &hb, const RowTables &tb, uint32_t &o0, uint32_t &o1)
+{
+    uint32_t sel = (p >> (2 * T)) & 0x03030303u;
+    if (BITS == 3) {
+        constexpr int beta = 2 * D + (T >> 1);            // in-byte position of the high bit
+        const uint32_t r = (T & 1) ? hb.odd : hb.even;
+        const uint32_t sh = beta >= 2 ? (r >> (beta - 2)) : (r << (2 - beta));
+        sel |= sh & 0x04040404u;
+    }
+    const uint32_t lo = perm(BITS == 3 ? tb.lo[1] : 0u, tb.lo[0], sel);
+    const uint32_t hi = perm(BITS == 3 ? tb.hi[1] : 0u, tb.hi[0], sel);
+    o0 = perm(hi, lo, 0x05010400u);
+    o1 = perm(hi, lo, 0x07030602u);
+}
+
 template <int BITS, int D>
 __device__ __forceinline__ void decode_word(uint32_t p, const HighBits &hb, const RowTables &tb, uint4v &op0, uint4v &op1)
 {
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-        uint32_t sel = (p >> (2 * t)) & 0x03030303u;
-        if (BITS == 3) {
-            const int beta = 2 * D + (t >> 1);            // in-byte position of the high bit
-            const uint32_t r = (t & 1) ? hb.odd : hb.even;
-            const uint32_t sh = beta >= 2 ? (r >> (beta - 2)) : (r << (2 - beta));
-            sel |= sh & 0x04040404u;
-        }
-        const uint32_t lo = perm(BITS == 3 ? tb.lo[1] : 0u, tb.lo[0], sel);
-        const uint32_t hi = perm(BITS == 3 ? tb.hi[1] : 0u, tb.hi[0], sel);
-        op0[t] = perm(hi, lo, 0x05010400u);
-        op1[t] = perm(hi, lo, 0x07030602u);
-    }
+    uint32_t a, b;
+    decode_quarter<BITS, D, 0>(p, hb, tb, a, b); op0[0] = a; op1[0] = b;
+    decode_quarter<BITS, D, 1>(p, hb, tb, a, b); op0[1] = a; op1[1] = b;
+    decode_quarter<BITS, D, 2>(p, hb, tb, a, b); op0[2] = a; op1[2] = b;
+    decode_quarter<BITS, D, 3>(p, hb, tb, a, b); op0[3] = a; op1[3] = b;
 }
 
 }  // namespace lcd

@@ -295,11 +295,13 @@ __device__ __forceinline__ void load_gemm_tiles(GemmTileRegs<BITS> &r, __amdgpu_
     }
 }
 
-// copy one 64 KiB stage: every wave copies 8 KiB as 8 wave-wide 1 KiB direct-to-LDS loads
-__device__ __forceinline__ void stage_copy(const uint8_t *__restrict__ src, uint8_t *lds_dst, int wave, int lane)
+// copy one 64 KiB stage: every wave copies 8 KiB as 8 wave-wide 1 KiB direct-to-LDS loads,
+// blocks [first, first + count) of them per call (the copy is spread over a word's matrix steps)
+__device__ __forceinline__ void stage_copy(const uint8_t *__restrict__ src, uint8_t *lds_dst, int wave, int lane, int first, int count)
 {
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
+        if (u < first || u >= first + count) continue;
         const int blk = wave * 8 + u;  // 1 KiB block index inside the stage
         __builtin_amdgcn_global_load_lds((glb_u32 *)(src + (size_t)blk * 1024 + lane * 16),
                                          (lds_u32 *)(lds_dst + blk * 1024), 16, 0, 0);
@@ -307,42 +309,77 @@ __device__ __forceinline__ void stage_copy(const uint8_t *__restrict__ src, uint
 }
 
 // B operands (16 bytes per lane) rotate through a window of four registers: the read for
-// matrix step s+3 is issued while step s computes, which covers the LDS latency with one wave
-// per SIMD.  A stage holds blocks [token block 4][half 2][k-step 8] of 1 KiB.
+// matrix step s+3 is issued while step s computes.  A stage holds blocks
+// [token block 4][half 2][k-step 8] of 1 KiB.  The reads and the waits for them are written out
+// (LDS reads of a wave return in order, so "at most n newer reads outstanding" is the exact
+// condition for a window slot; left to itself the compiler waited for ALL outstanding reads at
+// every fourth step, which emptied the window each time).
 struct BWindow { uint4v w[4]; };
 
-__device__ __forceinline__ uint4v read_b(const uint8_t *stage, int h, int g, int tb, int boff)
+// `base` = 32-bit LDS address of (stage + half * 8 KiB + the lane's 16 bytes)
+template <int G, int TBLK>
+__device__ __forceinline__ uint4v read_b(uint32_t base)
 {
-    return *reinterpret_cast<const uint4v *>(stage + ((tb * 2 + h) * 8 + g) * 1024 + boff);
+    uint4v v;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(base), "n"((TBLK * 16 + G) * 1024) : "memory");
+    return v;
+}
+template <int N>
+__device__ __forceinline__ void lds_wait()
+{
+    asm volatile("s_waitcnt lgkmcnt(%0)" : : "n"(N) : "memory");
+}
+__device__ __forceinline__ uint32_t lds_address(const uint8_t *p)
+{
+    return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) uint8_t *)p;
 }
 
+// Decoded A operands of one packed word: [pair][k-step of the word].
+struct WordOps { uint4v op[kGemmPairs][2]; };
+
 // One packed word per pair (16 weights per lane) = two k-steps x 4 token blocks = 8 matrix steps
-// of 2 MFMAs.  On entry the window holds steps 0..2 of this word; on exit steps 0..2 of the
-// next word (the next chunk's first word, from `next_stage`, after the last word of a chunk).
-template <int BITS, int D>
-__device__ __forceinline__ void gemm_word(const GemmTileRegs<BITS> &r, const HighBits (&hb)[kGemmPairs],
-                                          const RowTables (&tb)[kGemmPairs], const uint8_t *stage,
-                                          const uint8_t *next_stage, int h, int boff, BWindow &bw)
+// of 2 MFMAs.  The word's operands `cur` were decoded during the previous word; each matrix step
+// also decodes one eighth of the NEXT word (word DN of `rn`) into `nxt`, so that vector and
+// matrix instructions alternate in every wave's stream instead of coming in bursts (two waves of
+// a SIMD leave a barrier in phase; with bursts both would decode, then both would multiply).
+// COPY: the step also issues its share of the next stage's global -> LDS copy.
+// On entry the B window holds steps 0..2 of this word; on exit steps 0..2 of the next word of the
+// chunk (the caller primes it again after the last word).
+template <int BITS, int D, int DN, bool COPY>
+__device__ __forceinline__ void gemm_word(const WordOps &cur, WordOps &nxt, const GemmTileRegs<BITS> &rn,
+                                          const HighBits (&hbn)[kGemmPairs], const RowTables (&tb)[kGemmPairs],
+                                          uint32_t bbase, BWindow &bw,
+                                          const uint8_t *copy_src, uint8_t *copy_dst, int wave, int lane)
 {
-    uint4v op[kGemmPairs][2];
-#pragma unroll
-    for (int p = 0; p < kGemmPairs; ++p) decode_word<BITS, D>(r.lo[p][D], hb[p], tb[p], op[p][0], op[p][1]);
-    __builtin_amdgcn_sched_barrier(0);
 #define LCD_GEMM_STEP(ST)                                                                                   \
     {                                                                                                       \
-        constexpr int st = ST, a = st >> 2, blk = st & 3, nx = st + 3;                                      \
+        constexpr int st = ST, a = st >> 2, blk = st & 3, nx = st + 3, np = st >> 2, nt4 = st & 3;          \
         /* prefetch step st+3 into the slot that step st-1 used */                                          \
-        if (nx < 8) bw.w[nx & 3] = read_b(stage, h, 2 * D + (nx >> 2), nx & 3, boff);                       \
-        else if (D < 3) bw.w[nx & 3] = read_b(stage, h, 2 * D + 2, nx - 8, boff);                           \
-        else if (next_stage) bw.w[nx & 3] = read_b(next_stage, h, 0, nx - 8, boff);                         \
-        mfma_acc<blk>(op[0][a], bw.w[st & 3]);                                                              \
-        mfma_acc<4 + blk>(op[1][a], bw.w[st & 3]);                                                          \
+        if (nx < 8) bw.w[nx & 3] = read_b<2 * D + (nx >> 2), (nx & 3)>(bbase);                              \
+        else if (D < 3) bw.w[nx & 3] = read_b<(2 * D + 2) & 7, (nx - 8) & 3>(bbase);                        \
+        if (COPY && copy_src) stage_copy(copy_src, copy_dst, wave, lane, st, 1);                            \
+        {                                                                                                   \
+            uint32_t o0, o1;                                                                                \
+            decode_quarter<BITS, DN, nt4>(rn.lo[np][DN], hbn[np], tb[np], o0, o1);                          \
+            nxt.op[np][0][nt4] = o0; nxt.op[np][1][nt4] = o1;                                               \
+        }                                                                                                   \
+        /* reads newer than this step's operand: 3, fewer at the end of a chunk's last word */             \
+        lds_wait<(D < 3 || st <= 4) ? 3 : 7 - st>();                                                        \
+        mfma_acc<blk>(cur.op[0][a], bw.w[st & 3]);                                                          \
+        mfma_acc<4 + blk>(cur.op[1][a], bw.w[st & 3]);                                                      \
         __builtin_amdgcn_sched_barrier(0);                                                                  \
     }
     LCD_GEMM_STEP(0) LCD_GEMM_STEP(1) LCD_GEMM_STEP(2) LCD_GEMM_STEP(3)
     LCD_GEMM_STEP(4) LCD_GEMM_STEP(5) LCD_GEMM_STEP(6) LCD_GEMM_STEP(7)
 #undef LCD_GEMM_STEP
 }
+
+#ifdef LCD_TRACE
+__device__ unsigned long long *g_gemm_trace;   // debug builds only
+#define GEMM_STAMP(slot) do { if (lane == 0 && blockIdx.x == 0 && g_gemm_trace && (slot) < 120) g_gemm_trace[wave * 128 + (slot)] = __builtin_amdgcn_s_memrealtime(); } while (0)
+#else
+#define GEMM_STAMP(slot) do { } while (0)
+#endif
 
 template <int BITS>
 __global__ void __launch_bounds__(kGemmWaves * 64, 1)
@@ -391,49 +428,71 @@ gemm_kernel(const uint8_t *__restrict__ packed_, const uint8_t *__restrict__ lut
 
     GemmTileRegs<BITS> r0, r1;
     load_gemm_tiles<BITS>(r0, packed, t0, nt, kc, 0, khalf, lane);
-    stage_copy(xs_base, lds, wave, lane);
+    stage_copy(xs_base, lds, wave, lane, 0, 8);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
-    BWindow bw;
-    // Chunk c is computed from LDS stage c&1.  Its last word prefetches the first B operands of
-    // chunk c+1 from the other stage, so that stage must be resident before the last word: the
-    // wait + barrier for chunk c+1's copy sits just before it.
-    auto compute = [&](const GemmTileRegs<BITS> &r, const uint8_t *stage, const uint8_t *next_stage) {
-        HighBits hb[kGemmPairs];
+    auto high_bits = [&](const GemmTileRegs<BITS> &r, HighBits (&hb)[kGemmPairs]) {
 #pragma unroll
         for (int p = 0; p < kGemmPairs; ++p) {
             hb[p] = HighBits{0u, 0u};
             if (BITS == 3) hb[p] = regroup_high(r.hi[p]);
         }
-        gemm_word<BITS, 0>(r, hb, tb, stage, next_stage, khalf, boff, bw);
-        gemm_word<BITS, 1>(r, hb, tb, stage, next_stage, khalf, boff, bw);
-        gemm_word<BITS, 2>(r, hb, tb, stage, next_stage, khalf, boff, bw);
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();   // next chunk's stage (and packed words) have landed for every wave
-        gemm_word<BITS, 3>(r, hb, tb, stage, next_stage, khalf, boff, bw);
     };
 
-    bw.w[0] = read_b(lds, khalf, 0, 0, boff);
-    bw.w[1] = read_b(lds, khalf, 0, 1, boff);
-    bw.w[2] = read_b(lds, khalf, 0, 2, boff);
+    BWindow bw;
+    WordOps wa, wb;          // operands of the current / next word, swapping roles word by word
+    HighBits hb[kGemmPairs], hbn[kGemmPairs];
+    int stamp_base = 0;
+    // Chunk c is computed from LDS stage c&1 and register set r; word D's matrix steps decode word
+    // D+1, the last word's decode the first word of chunk c+1 (set rn, loaded at the top of chunk
+    // c).  The copy of chunk c+1's stage is issued during word 0 (the other stage was released by
+    // the barrier that ended chunk c-1) and has the whole chunk to land: one wait + one barrier
+    // per chunk, after which the B window is primed from the new stage.
+    auto compute = [&](const GemmTileRegs<BITS> &r, const GemmTileRegs<BITS> &rn, const uint8_t *stage,
+                       uint8_t *other_stage, const uint8_t *copy_src) {
+        const uint32_t bbase = lds_address(stage) + khalf * 8 * 1024 + boff;
+        const uint32_t obase = lds_address(other_stage) + khalf * 8 * 1024 + boff;
+        GEMM_STAMP(stamp_base + 0);
+        gemm_word<BITS, 0, 1, true>(wa, wb, r, hb, tb, bbase, bw, copy_src, other_stage, wave, lane);
+        gemm_word<BITS, 1, 2, false>(wb, wa, r, hb, tb, bbase, bw, nullptr, nullptr, wave, lane);
+        gemm_word<BITS, 2, 3, false>(wa, wb, r, hb, tb, bbase, bw, nullptr, nullptr, wave, lane);
+        GEMM_STAMP(stamp_base + 1);
+        high_bits(rn, hbn);
+        gemm_word<BITS, 3, 0, false>(wb, wa, rn, hbn, tb, bbase, bw, nullptr, nullptr, wave, lane);
+#pragma unroll
+        for (int p = 0; p < kGemmPairs; ++p) hb[p] = hbn[p];
+        GEMM_STAMP(stamp_base + 2);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        GEMM_STAMP(stamp_base + 3);
+        __syncthreads();   // the next stage has landed for every wave, and every wave is done with this one
+        GEMM_STAMP(stamp_base + 4);
+        bw.w[0] = read_b<0, 0>(obase);
+        bw.w[1] = read_b<0, 1>(obase);
+        bw.w[2] = read_b<0, 2>(obase);
+    };
+
+    // prologue: B operands of the first three steps, operands of the first word
+    {
+        const uint32_t base0 = lds_address(lds) + khalf * 8 * 1024 + boff;
+        bw.w[0] = read_b<0, 0>(base0);
+        bw.w[1] = read_b<0, 1>(base0);
+        bw.w[2] = read_b<0, 2>(base0);
+    }
+    high_bits(r0, hb);
+#pragma unroll
+    for (int p = 0; p < kGemmPairs; ++p) decode_word<BITS, 0>(r0.lo[p][0], hb[p], tb[p], wa.op[p][0], wa.op[p][1]);
     for (int c = 0; c < kc; c += 2) {
         // even chunk: compute from stage 0 / r0 while chunk c+1 lands in stage 1 / r1
         const bool more1 = c + 1 < kc;
-        if (more1) {
-            load_gemm_tiles<BITS>(r1, packed, t0, nt, kc, c + 1, khalf, lane);
-            stage_copy(xs_base + (size_t)(c + 1) * chunk_stride, lds + kStageBytes, wave, lane);
-        }
-        compute(r0, lds, more1 ? lds + kStageBytes : nullptr);
-        __syncthreads();   // every wave is done reading stage 0 before it is overwritten
+        if (more1) load_gemm_tiles<BITS>(r1, packed, t0, nt, kc, c + 1, khalf, lane);
+        compute(r0, r1, lds, lds + kStageBytes, more1 ? xs_base + (size_t)(c + 1) * chunk_stride : nullptr);
+        GEMM_STAMP(stamp_base + 5); stamp_base += 6;
         if (!more1) break;
         const bool more2 = c + 2 < kc;
-        if (more2) {
-            load_gemm_tiles<BITS>(r0, packed, t0, nt, kc, c + 2, khalf, lane);
-            stage_copy(xs_base + (size_t)(c + 2) * chunk_stride, lds, wave, lane);
-        }
-        compute(r1, lds + kStageBytes, more2 ? lds : nullptr);
-        __syncthreads();
+        if (more2) load_gemm_tiles<BITS>(r0, packed, t0, nt, kc, c + 2, khalf, lane);
+        compute(r1, r0, lds + kStageBytes, lds, more2 ? xs_base + (size_t)(c + 2) * chunk_stride : nullptr);
+        GEMM_STAMP(stamp_base + 5); stamp_base += 6;
     }
 
     // The wave that owns the second half of the chunks hands its accumulators to its partner
@@ -504,5 +563,9 @@ int launch_gemm(const void *packed, const void *lut, const uint16_t *x, const fl
     }
     return (int)hipGetLastError();
 }
+
+#ifdef LCD_TRACE
+extern "C" void lcd_debug_set_gemm_trace(unsigned long long *p) { hipMemcpyToSymbol(HIP_SYMBOL(g_gemm_trace), &p, sizeof(p)); }
+#endif
 
 }  // namespace lcd

@@ -140,44 +140,58 @@ __global__ void __launch_bounds__(256) build_lut_kernel(const uint16_t *__restri
 }
 
 // ---- activation smoothing: xs[m][k] = fp16( x[m][k] / s[k] )  (paper Sec. 3.4) -------------
-// Prefill path only (the decode kernels smooth in place).  One thread per group of 8 consecutive
-// k; inside a group the slot order is 0,4,1,5,2,6,3,7, the one the register dequantiser produces.
-// Output: operand order of v_mfma_f32_32x32x16_f16,
+// Prefill path only (the decode kernels smooth in place).  Output: operand order of
+// v_mfma_f32_32x32x16_f16,
 //   [chunk k/256][token block m/32][half (k%256)/128][step g=(k%64)/8][(k%128)/64][m%32][8 slots],
+// inside a group of 8 the slot order 0,4,1,5,2,6,3,7 that the register dequantiser produces;
 // tokens padded with zeros up to Mpad (a multiple of 128).
+// One workgroup per (chunk, token block): 32 tokens x 256 columns = 16 KiB in, 16 KiB out, both
+// contiguous per row / per block.  Rows are read coalesced (32 threads per 512-byte row), each
+// thread smooths 8 values, and the tile is turned into operand order through LDS so that the
+// stores are coalesced too (16-byte stores scattered 1 KiB apart ran at a third of the rate).
+constexpr int kSmoothRowBytes = 32 * 16 + 16;   // one [m 32][16 B] row of the tile in LDS, padded
 __global__ void __launch_bounds__(256) smooth_kernel(const uint16_t *__restrict__ x, const float *__restrict__ s,
                                                      _Float16 *__restrict__ xs, int M, int Mpad, int K)
 {
-    const long long grp = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    const int kg = K / 8;
-    const long long total = (long long)Mpad * kg;
-    if (grp >= total) return;
-    const int m = (int)(grp / kg);
-    const int k = (int)(grp % kg) * 8;
-    half8 o;
-    if (m < M) {
-        const uint4v xv = *reinterpret_cast<const uint4v *>(x + (size_t)m * K + k);
-        const float4v s0 = *reinterpret_cast<const float4v *>(s + k);
-        const float4v s1 = *reinterpret_cast<const float4v *>(s + k + 4);
+    __shared__ __attribute__((aligned(16))) uint8_t tile[32 * kSmoothRowBytes];
+    const int c = blockIdx.x, mb = blockIdx.y, t = threadIdx.x;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const uint16_t xb = (uint16_t)(xv[e >> 1] >> (16 * (e & 1)));
-            const int slot = e < 4 ? 2 * e : 2 * (e - 4) + 1;
-            o[slot] = smooth_one(xb, e < 4 ? s0[e] : s1[e - 4]);
+    for (int u = 0; u < 4; ++u) {
+        const int grp = t + 256 * u;            // input order: 32 groups of 8 columns per token row
+        const int ml = grp >> 5, kg = grp & 31;
+        const int m = mb * 32 + ml, k = c * kTileCols + 8 * kg;
+        half8 o;
+        if (m < M) {
+            const uint4v xv = *reinterpret_cast<const uint4v *>(x + (size_t)m * K + k);
+            const float4v s0 = *reinterpret_cast<const float4v *>(s + k);
+            const float4v s1 = *reinterpret_cast<const float4v *>(s + k + 4);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint16_t xb = (uint16_t)(xv[e >> 1] >> (16 * (e & 1)));
+                const int slot = e < 4 ? 2 * e : 2 * (e - 4) + 1;
+                o[slot] = smooth_one(xb, e < 4 ? s0[e] : s1[e - 4]);
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = (_Float16)0.0f;
         }
-    } else {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) o[e] = (_Float16)0.0f;
+        const int h = kg >> 4, kh = (kg >> 3) & 1, g = kg & 7;
+        const int row = (h * 8 + g) * 2 + kh;   // position of this group of 8 columns in operand order
+        *reinterpret_cast<half8 *>(tile + row * kSmoothRowBytes + ml * 16) = o;
     }
-    const int c = k >> 8, h = (k >> 7) & 1, kh = (k >> 6) & 1, g = (k >> 3) & 7;
-    const size_t dst = ((((((size_t)c * (Mpad >> 5) + (m >> 5)) * 2 + h) * 8 + g) * 2 + kh) * 32 + (m & 31)) * 8;
-    *reinterpret_cast<half8 *>(xs + dst) = o;
+    __syncthreads();
+    _Float16 *dst = xs + ((size_t)c * (Mpad >> 5) + mb) * (32 * 256);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int grp = t + 256 * u;            // output order: [row 32][m 32] groups of 8 halfs
+        const int row = grp >> 5, ml = grp & 31;
+        *reinterpret_cast<half8 *>(dst + (size_t)grp * 8) = *reinterpret_cast<const half8 *>(tile + row * kSmoothRowBytes + ml * 16);
+    }
 }
 
 int launch_smooth(const uint16_t *x, const float *s, void *xs, int M, int Mpad, int K, void *stream)
 {
-    const long long threads = (long long)Mpad * (K / 8);
-    const dim3 grid((unsigned)((threads + 255) / 256)), block(256);
+    const dim3 grid((unsigned)(K / kTileCols), (unsigned)(Mpad / 32)), block(256);
     hipLaunchKernelGGL(smooth_kernel, grid, block, 0, (hipStream_t)stream, x, s, (_Float16 *)xs, M, Mpad, K);
     return (int)hipGetLastError();
 }
