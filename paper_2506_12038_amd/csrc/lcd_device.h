@@ -69,9 +69,10 @@ __device__ __forceinline__ HighBits regroup_high(uint2v h)
 // 16d + [0,8)) and operand a=1 (weights 16d + [8,16)).  Register v of an operand holds the
 // fp16 pair (weight v, weight 4+v) of its 8 weights, so the activation operand must use the
 // slot order 0,4,1,5,2,6,3,7.
-// One quarter of decode_word: selector t (weights t, 4+t of operand 0 and of operand 1).
+// One quarter of decode_word (selector T: weights T, 4+T of operand 0 and of operand 1), in its
+// three dependent stages, so that a caller can interleave the stages of different quarters.
 template <int BITS, int D, int T>
-__device__ __forceinline__ void decode_quarter(uint32_t p, const HighBits &hb, const RowTables &tb, uint32_t &o0, uint32_t &o1)
+__device__ __forceinline__ uint32_t decode_select(uint32_t p, const HighBits &hb)
 {
     uint32_t sel = (p >> (2 * T)) & 0x03030303u;
     if (BITS == 3) {
@@ -80,10 +81,25 @@ __device__ __forceinline__ void decode_quarter(uint32_t p, const HighBits &hb, c
         const uint32_t sh = beta >= 2 ? (r >> (beta - 2)) : (r << (2 - beta));
         sel |= sh & 0x04040404u;
     }
-    const uint32_t lo = perm(BITS == 3 ? tb.lo[1] : 0u, tb.lo[0], sel);
-    const uint32_t hi = perm(BITS == 3 ? tb.hi[1] : 0u, tb.hi[0], sel);
+    return sel;
+}
+template <int BITS>
+__device__ __forceinline__ void decode_lookup(uint32_t sel, const RowTables &tb, uint32_t &lo, uint32_t &hi)
+{
+    lo = perm(BITS == 3 ? tb.lo[1] : 0u, tb.lo[0], sel);
+    hi = perm(BITS == 3 ? tb.hi[1] : 0u, tb.hi[0], sel);
+}
+__device__ __forceinline__ void decode_interleave(uint32_t lo, uint32_t hi, uint32_t &o0, uint32_t &o1)
+{
     o0 = perm(hi, lo, 0x05010400u);
     o1 = perm(hi, lo, 0x07030602u);
+}
+template <int BITS, int D, int T>
+__device__ __forceinline__ void decode_quarter(uint32_t p, const HighBits &hb, const RowTables &tb, uint32_t &o0, uint32_t &o1)
+{
+    uint32_t lo, hi;
+    decode_lookup<BITS>(decode_select<BITS, D, T>(p, hb), tb, lo, hi);
+    decode_interleave(lo, hi, o0, o1);
 }
 
 template <int BITS, int D>

@@ -351,23 +351,31 @@ __device__ __forceinline__ void gemm_word(const WordOps &cur, WordOps &nxt, cons
                                           uint32_t bbase, BWindow &bw,
                                           const uint8_t *copy_src, uint8_t *copy_dst, int wave, int lane)
 {
+#define LCD_GEMM_FENCE __builtin_amdgcn_sched_barrier(0);
+    uint32_t sel = 0;
 #define LCD_GEMM_STEP(ST)                                                                                   \
     {                                                                                                       \
         constexpr int st = ST, a = st >> 2, blk = st & 3, nx = st + 3, np = st >> 2, nt4 = st & 3;          \
+        uint32_t lo, hi, o0, o1;                                                                            \
         /* prefetch step st+3 into the slot that step st-1 used */                                          \
         if (nx < 8) bw.w[nx & 3] = read_b<2 * D + (nx >> 2), (nx & 3)>(bbase);                              \
         else if (D < 3) bw.w[nx & 3] = read_b<(2 * D + 2) & 7, (nx - 8) & 3>(bbase);                        \
-        if (COPY && copy_src) stage_copy(copy_src, copy_dst, wave, lane, st, 1);                            \
-        {                                                                                                   \
-            uint32_t o0, o1;                                                                                \
-            decode_quarter<BITS, DN, nt4>(rn.lo[np][DN], hbn[np], tb[np], o0, o1);                          \
-            nxt.op[np][0][nt4] = o0; nxt.op[np][1][nt4] = o1;                                               \
-        }                                                                                                   \
+        if (st == 0) sel = decode_select<BITS, DN, 0>(rn.lo[0][DN], hbn[0]);                                \
         /* reads newer than this step's operand: 3, fewer at the end of a chunk's last word */             \
         lds_wait<(D < 3 || st <= 4) ? 3 : 7 - st>();                                                        \
         mfma_acc<blk>(cur.op[0][a], bw.w[st & 3]);                                                          \
+        /* the vector work of the step is split behind the two matrix instructions: the second one     */ \
+        /* cannot issue before the first has left the pipe, and a wave issues in order.  Lookups of     */ \
+        /* quarter st, then the selector of quarter st+1, then the interleave: dependent instructions   */ \
+        /* stay a few issue slots apart.                                                                 */ \
+        if (COPY && copy_src) stage_copy(copy_src, copy_dst, wave, lane, st, 1);                            \
+        decode_lookup<BITS>(sel, tb[np], lo, hi);                                                           \
+        LCD_GEMM_FENCE                                                                                      \
         mfma_acc<4 + blk>(cur.op[1][a], bw.w[st & 3]);                                                      \
-        __builtin_amdgcn_sched_barrier(0);                                                                  \
+        if (st < 7) sel = decode_select<BITS, DN, (st + 1) & 3>(rn.lo[(st + 1) >> 2][DN], hbn[(st + 1) >> 2]); \
+        decode_interleave(lo, hi, o0, o1);                                                                  \
+        nxt.op[np][0][nt4] = o0; nxt.op[np][1][nt4] = o1;                                                   \
+        LCD_GEMM_FENCE                                                                                      \
     }
     LCD_GEMM_STEP(0) LCD_GEMM_STEP(1) LCD_GEMM_STEP(2) LCD_GEMM_STEP(3)
     LCD_GEMM_STEP(4) LCD_GEMM_STEP(5) LCD_GEMM_STEP(6) LCD_GEMM_STEP(7)
@@ -440,6 +448,9 @@ gemm_kernel(const uint8_t *__restrict__ packed_, const uint8_t *__restrict__ lut
         }
     };
 
+#ifdef LCD_TRACE
+    if (lane == 0 && blockIdx.x == 0 && g_gemm_trace) { g_gemm_trace[wave * 128 + 120] = __builtin_amdgcn_s_memtime(); g_gemm_trace[wave * 128 + 121] = __builtin_amdgcn_s_memrealtime(); }
+#endif
     BWindow bw;
     WordOps wa, wb;          // operands of the current / next word, swapping roles word by word
     HighBits hb[kGemmPairs], hbn[kGemmPairs];
@@ -495,6 +506,9 @@ gemm_kernel(const uint8_t *__restrict__ packed_, const uint8_t *__restrict__ lut
         GEMM_STAMP(stamp_base + 5); stamp_base += 6;
     }
 
+#ifdef LCD_TRACE
+    if (lane == 0 && blockIdx.x == 0 && g_gemm_trace) { g_gemm_trace[wave * 128 + 122] = __builtin_amdgcn_s_memtime(); g_gemm_trace[wave * 128 + 123] = __builtin_amdgcn_s_memrealtime(); }
+#endif
     // The wave that owns the second half of the chunks hands its accumulators to its partner
     // through LDS (the stages are free now): [row group][accumulator 8][register quad 4][lane] float4.
     float4v *xchg = reinterpret_cast<float4v *>(lds) + (size_t)rgrp * (8 * 4 * 64);
