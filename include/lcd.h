@@ -63,7 +63,9 @@ const char *lcd_status_string(lcd_status st);
 size_t lcd_packed_bytes(int N, int K, int bits);
 /* Bytes of the per-layer table lcd_build_lut writes (24*N for 2 bits, 48*N for 3 bits). */
 size_t lcd_lut_bytes(int N, int bits);
-/* Bytes of scratch lcd_lut_gemv / lcd_lut_gemm need for this problem (a multiple of 256). */
+/* Bytes of scratch the product entry points accept for this problem (a multiple of 256).  Only
+ * lcd_lut_gemm uses it (smoothed activations in matrix-operand order, about 2*K bytes per token);
+ * the decode entry points take the argument so that one buffer serves all of them. */
 size_t lcd_workspace_bytes(int M, int N, int K, int bits);
 
 /* ---- index packing (offline, once per layer; Sec. 4.1 "constructed ahead of time") ------- *
@@ -115,9 +117,12 @@ lcd_status lcd_build_lut(const uint16_t *codebook /*DEVICE*/, int N, int bits,
  * y       DEVICE fp16 [M][N] row-major (written, never read)
  * workspace  DEVICE, >= lcd_workspace_bytes(M,N,K,bits) bytes, contents ignored on entry.
  *
- * lcd_lut_gemv: decode path, 1 <= M <= 16.  Bandwidth-bound on the packed indices.
- * lcd_lut_gemm: prefill path, any M >= 1 (tuned for M >= 64): register dequantisation into
- *               fp16 MFMA operands.
+ * lcd_lut_gemv: decode path, 1 <= M <= 16, one kernel launch, any K.  M = 1: centroid-bucket
+ *               sums on the sparse matrix core (Sec. 4.2); 2 <= M <= 16: register dequantisation
+ *               into fp16 MFMA operands with the tokens as the matrix columns.  The smoothing
+ *               is fused into the kernel; the workspace is not touched.
+ * lcd_lut_gemm: prefill path, any M >= 1 (tuned for M >= 64): a smoothing kernel into the
+ *               workspace, then register dequantisation into fp16 MFMA operands.
  * Both give bit-identical results from run to run (fixed reduction order).
  */
 lcd_status lcd_lut_gemv(const void *packed, const void *lut, const uint16_t *x, const float *s,
@@ -133,9 +138,11 @@ lcd_status lcd_lut_gemm(const void *packed, const void *lut, const uint16_t *x, 
  * models); each is only a few MB of packed indices, so launching them one by one leaves the
  * GPU mostly idle.  lcd_lut_gemv_grouped runs `count` (1..16) independent products
  *     y_i = (x_i / s_i) . What_i^T            (same M and bits for all, any N_i, K_i)
- * with every argument of problems[i] as in lcd_lut_gemv.  `problems` is a HOST array, read
- * during the call only.  The layers' outputs must not overlap.  Workspace: at least
- * lcd_workspace_bytes_grouped(problems, count, M, bits) bytes (DEVICE).
+ * with every argument of problems[i] as in lcd_lut_gemv, in one kernel launch for any M in
+ * 1..16: the workgroups are shared out over the layers in proportion to their work.
+ * `problems` is a HOST array, read during the call only.  The layers' outputs must not overlap.
+ * Workspace: at least lcd_workspace_bytes_grouped(problems, count, M, bits) bytes (DEVICE),
+ * not touched.
  */
 typedef struct lcd_gemv_problem {
     const void *packed;   /* DEVICE */
