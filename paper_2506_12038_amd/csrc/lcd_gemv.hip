@@ -655,8 +655,8 @@ int launch_decode_group(const GroupItem *items, int count, int M, int bits, void
     int grid = num_cus();
     if (grid > tiles) grid = tiles;
     if (grid < count) grid = count;
-    const double startup_steps = M > 1 ? 3.0 : bits == 2 ? 4.0 : 2.0;
-    const double segment_steps = M > 1 ? 1.5 : bits == 2 ? 0.8 : 0.4;
+    const double startup_steps = M > 1 ? 3.0 : bits == 2 ? 3.5 : 2.0;
+    const double segment_steps = M > 1 ? 1.5 : bits == 2 ? 1.8 : 0.4;
     const double step_overhead = M > 1 ? 0.3 : 0.1;   // per tile and segment: barrier / bookkeeping
     auto split = [&](int ch, int *nwg) {
         const int seg = kBW * ch;
