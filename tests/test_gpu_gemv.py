@@ -99,3 +99,41 @@ def test_grouped_config1_full_size_sampled():
     for (packed, lut, x, s, y, N), (rs, Y) in zip(problems, layers):
         err = oracle.parity_errors(y.cpu().numpy()[:, rs], Y)
         assert err["max_rel_floored"] <= TOL, err
+
+
+@pytest.mark.parametrize("bits,M", [(3, 1), (2, 16)])
+def test_grouped_launch_replayed_from_a_hip_graph(bits, M):
+    # the launch configuration bench.py times: the grouped call captured once, replayed several times
+    # with eager work and synchronisations in between; every replay must reproduce the eager result
+    import torch
+    from paper_2506_12038_amd.binding import GemvGroup
+    shapes = [(256, 4096), (176, 2816), (64, 11008)]
+    problems, eager = [], []
+    for i, (N, K) in enumerate(shapes):
+        layer = synth.make_layer(1, i, N, K, bits, M, seed_offset=17 * i + bits + M)
+        packed = lcd.lcd_pack_indices(to_dev(layer["idx"]), bits)
+        lut = lcd.lcd_build_lut(to_dev(layer["codebook"]), bits)
+        x, s = to_dev(layer["x"]), to_dev(layer["s"])
+        y = torch.zeros((M, N), dtype=torch.float16, device="cuda")
+        problems.append((packed, lut, x, s, y, N))
+        Y = oracle.lut_matmul(layer["codebook"], layer["idx"], layer["x"], layer["s"], bits)
+        ref = lcd.lcd_lut_gemv(packed, lut, x, s, N, bits)
+        assert oracle.parity_errors(ref.cpu().numpy(), Y)["max_rel_floored"] <= TOL
+        eager.append(ref)
+    group = GemvGroup(problems, bits)
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        group(stream)                      # first call outside capture (lazy module load)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=stream):
+        group(stream)
+    for rep in range(3):
+        for p in problems:
+            p[4].fill_(float("nan"))       # eager work between the replays
+        torch.cuda.synchronize()
+        with torch.cuda.stream(stream):
+            graph.replay()
+        torch.cuda.synchronize()
+        for p, ref in zip(problems, eager):
+            assert torch.equal(p[4], ref), rep

@@ -49,7 +49,7 @@ def small_case(bits, M, N, K, seed):
 
 
 @pytest.mark.parametrize("bits", [2, 3])
-@pytest.mark.parametrize("shape", [(1, 4, 16), (3, 8, 64), (2, 5, 37)])
+@pytest.mark.parametrize("shape", [(1, 4, 16), (3, 8, 64), (2, 5, 37), (4, 4, 24)])   # the last one square in (M, N): catches a transposed output
 def test_exact_rational_brute_force(bits, shape):
     M, N, K = shape
     codebook, idx, x, s = small_case(bits, M, N, K, 100 + bits + K)
