@@ -11,11 +11,12 @@ from .lcd_oracle import (
     lut_matmul,
     bucket_matmul,
     input_transform,
+    quantised_lut_matmul,
     num_threads,
 )
 from .metrics import parity_errors
 
 __all__ = [
     "build_oracle", "half_to_double", "dequant", "smooth", "lut_matmul", "bucket_matmul",
-    "input_transform", "num_threads", "parity_errors",
+    "input_transform", "quantised_lut_matmul", "num_threads", "parity_errors",
 ]

@@ -150,3 +150,24 @@ void oracle_input_transform(const uint16_t *x, const float *s_m, double s_q, int
         }
     }
 }
+
+/* The same stage in the arithmetic a single-precision kernel uses, step by step:
+ * d = s_m * s_q rounded to binary32, v = x / d rounded to binary32, round half to even, clip.
+ * Where floating point decides an integer, oracle and kernel must decide in the same precision;
+ * this is the kernel's.  (volatile keeps every intermediate in binary32.) */
+void oracle_input_transform_f32(const uint16_t *x, const float *s_m, float s_q, int b,
+                                int M, int K, int32_t *q)
+{
+    float lo = -ldexpf(1.0f, b - 1), hi = ldexpf(1.0f, b - 1) - 1.0f;
+    for (int m = 0; m < M; m++) {
+        for (int k = 0; k < K; k++) {
+            volatile float d = s_m[k] * s_q;
+            volatile float xf = (float)oracle_half_to_double(x[(size_t)m * K + k]); /* exact */
+            volatile float v = xf / d;
+            float r = nearbyintf(v);
+            if (r < lo) r = lo;
+            if (r > hi) r = hi;
+            q[(size_t)m * K + k] = (int32_t)r;
+        }
+    }
+}

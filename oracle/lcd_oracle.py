@@ -54,6 +54,8 @@ def _load():
             fn.argtypes = [u16p, u8p, u16p, f32p, ci, ci, ci, ci, f64p]
         lib.oracle_input_transform.restype = None
         lib.oracle_input_transform.argtypes = [u16p, f32p, ctypes.c_double, ci, ci, ci, i32p]
+        lib.oracle_input_transform_f32.restype = None
+        lib.oracle_input_transform_f32.argtypes = [u16p, f32p, ctypes.c_float, ci, ci, ci, i32p]
         _lib = lib
     return _lib
 
@@ -131,12 +133,25 @@ def bucket_matmul(codebook, idx, x, s, bits: int) -> np.ndarray:
     return _matmul("oracle_bucket_matmul", codebook, idx, x, s, bits)
 
 
-def input_transform(x, s_m, s_q: float, b: int = 8) -> np.ndarray:
-    """q = clip(round(x/(s_m*s_q))) to the b-bit symmetric range (Sec. 4.1, Eq. 10-11)."""
+def input_transform(x, s_m, s_q: float, b: int = 8, single_precision: bool = False) -> np.ndarray:
+    """q = clip(round(x/(s_m*s_q))) to the b-bit symmetric range (Sec. 4.1, Eq. 10-11).
+
+    single_precision=False: fp64 throughout.  True: every step in binary32 (d = s_m*s_q, v = x/d,
+    round half to even), the precision in which a single-precision kernel takes the rounding decision."""
     xx = _as_half_bits(x)
     ss = np.ascontiguousarray(s_m, dtype=np.float32)
     M, K = xx.shape
     q = np.empty((M, K), dtype=np.int32)
-    _load().oracle_input_transform(_p(xx, ctypes.c_uint16), _p(ss, ctypes.c_float), float(s_q), int(b), M, K,
-                                   _p(q, ctypes.c_int32))
+    fn = _load().oracle_input_transform_f32 if single_precision else _load().oracle_input_transform
+    fn(_p(xx, ctypes.c_uint16), _p(ss, ctypes.c_float), float(s_q), int(b), M, K, _p(q, ctypes.c_int32))
     return q
+
+
+def quantised_lut_matmul(codebook, idx, x, s_m, s_q: float, bits: int, b: int = 8) -> np.ndarray:
+    """The product with the input transformation of Sec. 4.1 in front of it:
+    Y = s_q * sum_k q[m][k] * C[n][idx[n][k]], q from input_transform in single precision (fp64 sum)."""
+    q = input_transform(x, s_m, s_q, b, single_precision=True)
+    qh = q.astype(np.float16)                       # |q| <= 128: exact
+    assert np.array_equal(qh.astype(np.int32), q)
+    ones = np.ones(q.shape[1], dtype=np.float32)
+    return float(np.float32(s_q)) * lut_matmul(codebook, idx, qh, ones, bits)

@@ -234,6 +234,45 @@ def test_input_transform_hand_values():
     assert q.tolist() == [[7, -8]]
 
 
+def test_input_transform_single_precision():
+    # the hand-worked values are exact in binary32 too
+    x = np.array([[1.0, 1.0, 100.0, -0.375, 0.625, 0.875, -1000.0]], dtype=np.float16)
+    s_m = np.array([2, 0.5, 1, 1, 1, 1, 1], dtype=np.float32)
+    assert oracle.input_transform(x, s_m, 0.25, 8, single_precision=True).tolist() == [[2, 8, 127, -2, 2, 4, -128]]
+    # against an independent binary32 evaluation (numpy float32 arithmetic) on random data
+    rng = np.random.default_rng(5)
+    x = (rng.standard_normal((8, 512)) * 3).astype(np.float16)
+    s_m = (0.3 + rng.random(512) * 4).astype(np.float32)
+    s_q = np.float32(0.0371)
+    d = (s_m * s_q).astype(np.float32)
+    v = (x.astype(np.float32) / d).astype(np.float32)
+    ref = np.clip(np.rint(v), -128, 127).astype(np.int32)
+    q32 = oracle.input_transform(x, s_m, float(s_q), 8, single_precision=True)
+    assert np.array_equal(q32, ref)
+    # and against the fp64 version: codes differ by at most one, and only next to a rounding boundary
+    q64 = oracle.input_transform(x, s_m, float(s_q), 8)
+    diff = q32 != q64
+    assert np.abs(q32 - q64).max() <= 1 and diff.mean() < 1e-3
+    exact = x.astype(np.float64) / (s_m.astype(np.float64) * float(s_q))
+    assert np.all(np.abs(np.abs(exact[diff] - np.floor(exact[diff])) - 0.5) < 1e-5)
+    # a tie after the binary32 rounding of s_m: 1/(0.5 + 2^-30) is 2.0 in binary32, x/d = 0.5 exactly -> 0 (half to even)
+    x1 = np.array([[1.0]], dtype=np.float16)
+    s1 = np.array([1.0 / (0.5 + 2.0 ** -30)], dtype=np.float32)      # rounds to 2.0 in binary32
+    assert oracle.input_transform(x1, s1, 1.0, 8, single_precision=True).tolist() == [[0]]
+
+
+def test_quantised_product_definition():
+    # Y = s_q * sum_k q_k * C[n][idx]: exact small case by hand
+    codebook = np.array([[-0.5, -0.25, 0.25, 0.5]], dtype=np.float16)
+    idx = np.array([[0, 3, 2, 1]], dtype=np.uint8)
+    x = np.array([[1.0, 2.0, -3.0, 100.0]], dtype=np.float16)
+    s_m = np.array([1, 2, 1, 1], dtype=np.float32)
+    # s_q = 0.5: x/(s_m*s_q) = [2, 2, -6, 200] -> q = [2, 2, -6, 127]
+    # sum q*C = 2*(-0.5) + 2*0.5 + (-6)*0.25 + 127*(-0.25) = -33.25 ; times s_q = -16.625
+    Y = oracle.quantised_lut_matmul(codebook, idx, x, s_m, 0.5, 2)
+    assert Y.tolist() == [[-16.625]]
+
+
 def test_generators_follow_the_recipe():
     L = synth.make_layer(0, 0, 256, 4096, 2, 4)
     p = np.bincount(L["idx"].ravel(), minlength=4) / L["idx"].size
