@@ -40,6 +40,7 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the secondary measurements (other configs)")
     ap.add_argument("--per-layer", action="store_true", help="one lcd_lut_gemv call per matrix instead of one grouped call per step")
+    ap.add_argument("--act-int8", action="store_true", help="decode configs: INT8 activation codes (input transformation of Sec. 4.1) instead of fp16 x/s")
     ap.add_argument("--eager", action="store_true", help="launch every step from Python instead of replaying a HIP graph")
     return ap.parse_args()
 
@@ -47,7 +48,7 @@ def parse_args():
 class LayerSet:
     """Device-resident inputs of one config: per matrix R replicas of (packed, lut), x, s, y, workspace."""
 
-    def __init__(self, cfg_index, M, replicas, keep_host=False, per_layer=False):
+    def __init__(self, cfg_index, M, replicas, keep_host=False, per_layer=False, act_int8=False):
         import numpy as np
         import torch
         import synth
@@ -69,7 +70,9 @@ class LayerSet:
             packed = [packed0] + [packed0.clone() for _ in range(replicas - 1)]
             luts = [lut0] + [lut0.clone() for _ in range(replicas - 1)]
             ws = torch.empty(lcd.lcd_workspace_bytes(M, spec.N, spec.K, self.bits), dtype=torch.uint8, device="cuda")
-            self.mats.append(dict(spec=spec, packed=packed, lut=luts, x=dev(layer["x"]), s=dev(layer["s"]),
+            # INT8 activation variant: the quantisation step puts the 99th percentile of |x/s| at code 127
+            s_q = float(np.float32(np.quantile(np.abs(layer["x"].astype(np.float64) / layer["s"]), 0.99) / 127.0))
+            self.mats.append(dict(spec=spec, packed=packed, lut=luts, x=dev(layer["x"]), s=dev(layer["s"]), s_q=s_q,
                                   y=torch.empty((M, spec.N), dtype=torch.float16, device="cuda"), ws=ws))
             if keep_host:
                 self.host.append(layer)
@@ -83,7 +86,8 @@ class LayerSet:
         self.groups = None
         if M <= 16:
             self.groups = [lcd.GemvGroup([(m["packed"][r], m["lut"][r], m["x"], m["s"], m["y"], m["spec"].N) for m in self.mats],
-                                         self.bits) for r in range(replicas)]
+                                         self.bits, s_q=[m["s_q"] for m in self.mats] if act_int8 else None)
+                           for r in range(replicas)]
 
     def step(self, replica):
         if self.groups is not None and not self.per_layer:
@@ -211,19 +215,21 @@ def main():
     cfg = synth.get_config(args.config)
     M = args.m if args.m is not None else cfg.Ms[0]
     replicas = args.replicas or max(2, -(-600_000_000 // cfg.index_bytes()))
-    ls = LayerSet(args.config, M, replicas, per_layer=args.per_layer)
+    if args.act_int8 and (M > 16 or args.per_layer):
+        sys.exit("--act-int8 applies to the grouped decode path (M <= 16)")
+    ls = LayerSet(args.config, M, replicas, per_layer=args.per_layer, act_int8=args.act_int8)
     wall_ms, event_ms = time_steps(ls, replicas, args.steps, args.warmup, args.eager)
 
     decode = M <= 16
-    n_launch = 1 if (decode_group := (M == 1 and not args.per_layer)) else len(ls.mats)
+    n_launch = 1 if (decode and not args.per_layer) else len(ls.mats)
     if decode:
         metric, unit = "lut_gemv_effective_bandwidth_packed_index_bytes", "GB/s"
         value = ls.index_bytes / (wall_ms * 1e-3) / 1e9
         roofline = {
             "bound": "hbm", "achieved": ls.index_bytes / (event_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": ls.index_bytes / (event_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-            "traffic": measured_traffic("gemv_bucket_kernel" if M == 1 else "gemv_dense_kernel", args.config) if n_launch == 1 else None,
-            "kernel": "gemv_bucket_kernel" if M == 1 else "gemv_dense_kernel",
+            "traffic": measured_traffic("gemv_bucket_kernel" if M == 1 else "gemv_tokens_kernel", args.config) if n_launch == 1 else None,
+            "kernel": "gemv_bucket_kernel" if M == 1 else "gemv_tokens_kernel",
             "launches_per_step": n_launch, "algorithmic_bytes_per_step": ls.index_bytes,
             "avg_launch_us": event_ms * 1e3 / n_launch,
         }
@@ -242,6 +248,7 @@ def main():
         "dtype": "f16 operands, f32 accumulate", "data": "synthetic",
         "config": {"workload": f"config {args.config}: {cfg.label}", "M": M, "bits": cfg.bits,
                    "matrices": [f"{m['spec'].N}x{m['spec'].K}" for m in ls.mats],
+                   "activations": "int8 codes, input transformation of Sec. 4.1 (lcd_lut_gemv_q8_grouped)" if args.act_int8 else "fp16 x/s",
                    "index_bytes_per_step": ls.index_bytes, "replicas_in_rotation": replicas,
                    "launch": ("eager" if args.eager else "hip graph replay") + (", one grouped launch per step" if n_launch == 1 else ", one call per matrix")},
         "roofline": roofline,

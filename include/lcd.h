@@ -46,7 +46,8 @@ typedef enum {
     LCD_ERR_SIZE = 5,        /* a buffer-size argument is too small                 */
     LCD_ERR_INDEX_RANGE = 6, /* host packer: an index is >= 2^bits                  */
     LCD_ERR_ALIGN = 7,       /* a device pointer is not 16-byte aligned             */
-    LCD_ERR_HIP = 8          /* the HIP runtime reported an error at launch         */
+    LCD_ERR_HIP = 8,         /* the HIP runtime reported an error at launch         */
+    LCD_ERR_BAD_SCALE = 9    /* a quantisation scale is not positive and finite     */
 } lcd_status;
 
 /* Library version (major*10000 + minor*100 + patch) and the packed-layout revision. */
@@ -120,7 +121,9 @@ lcd_status lcd_build_lut(const uint16_t *codebook /*DEVICE*/, int N, int bits,
  * lcd_lut_gemv: decode path, 1 <= M <= 16, one kernel launch, any K.  M = 1: centroid-bucket
  *               sums on the sparse matrix core (Sec. 4.2); 2 <= M <= 16: register dequantisation
  *               into fp16 MFMA operands with the tokens as the matrix columns.  The smoothing
- *               is fused into the kernel; the workspace is not touched.
+ *               is fused into the kernel, except for M >= 2 with K >= 16384, where a small
+ *               kernel ahead of the product leaves the smoothed activations in the workspace
+ *               (same rounding, same result).
  * lcd_lut_gemm: prefill path, any M >= 1 (tuned for M >= 64): a smoothing kernel into the
  *               workspace, then register dequantisation into fp16 MFMA operands.
  * Both give bit-identical results from run to run (fixed reduction order).
@@ -132,6 +135,23 @@ lcd_status lcd_lut_gemm(const void *packed, const void *lut, const uint16_t *x, 
                         uint16_t *y, int M, int N, int K, int bits,
                         void *workspace, size_t workspace_bytes, void *stream);
 
+/* ---- decode with the paper's input transformation in front (Sec. 4.1, Eq. 10-11, b = 8) ---- *
+ *
+ * The activations are smoothed and quantised to INT8 codes in one step, as the paper's own
+ * inference path does,
+ *     q[m][k] = clip( round_half_even( X[m][k] / (s[k] * s_q) ), -128, 127 )
+ *     Y[m][n] = s_q * sum_k q[m][k] * C[n][ idx[n][k] ]
+ * with s_q > 0 the (per-layer) activation quantisation step.  Every step of the quantiser is
+ * IEEE binary32 (the product s[k]*s_q, the correctly rounded quotient, the rounding), so the
+ * codes are reproducible bit for bit on a CPU; the sum is fp32 (exact on the integer bucket
+ * sums), one rounding to fp16 at the store.  Precondition on the data: every s[k]*s_q lies in
+ * (2^-64, 2^64) and X is finite (the quotient is computed without range scaling).
+ * All other arguments as lcd_lut_gemv (1 <= M <= 16).
+ */
+lcd_status lcd_lut_gemv_q8(const void *packed, const void *lut, const uint16_t *x, const float *s, float s_q,
+                           uint16_t *y, int M, int N, int K, int bits,
+                           void *workspace, size_t workspace_bytes, void *stream);
+
 /* ---- grouped decode: several independent layers in ONE launch ---------------------------- *
  *
  * A decoder block applies several table-lookup linear layers per token (Sec. 5 evaluates whole
@@ -141,8 +161,9 @@ lcd_status lcd_lut_gemm(const void *packed, const void *lut, const uint16_t *x, 
  * with every argument of problems[i] as in lcd_lut_gemv, in one kernel launch for any M in
  * 1..16: the workgroups are shared out over the layers in proportion to their work.
  * `problems` is a HOST array, read during the call only.  The layers' outputs must not overlap.
- * Workspace: at least lcd_workspace_bytes_grouped(problems, count, M, bits) bytes (DEVICE),
- * not touched.
+ * Workspace: at least lcd_workspace_bytes_grouped(problems, count, M, bits) bytes (DEVICE);
+ * for M >= 2 it may receive the layers' transformed activations (at most M*K_i fp16 each).
+ * Calls that share a workspace must be ordered on one stream.
  */
 typedef struct lcd_gemv_problem {
     const void *packed;   /* DEVICE */
@@ -156,6 +177,11 @@ typedef struct lcd_gemv_problem {
 size_t lcd_workspace_bytes_grouped(const lcd_gemv_problem *problems /*HOST*/, int count, int M, int bits);
 lcd_status lcd_lut_gemv_grouped(const lcd_gemv_problem *problems /*HOST*/, int count, int M, int bits,
                                 void *workspace, size_t workspace_bytes, void *stream);
+
+/* The same with the input transformation of lcd_lut_gemv_q8 in front of every layer:
+ * s_q is a HOST array of `count` activation quantisation steps, one per layer. */
+lcd_status lcd_lut_gemv_q8_grouped(const lcd_gemv_problem *problems /*HOST*/, const float *s_q /*HOST*/, int count,
+                                   int M, int bits, void *workspace, size_t workspace_bytes, void *stream);
 
 #ifdef __cplusplus
 }

@@ -19,8 +19,8 @@ EXPORTS = (
     "lcd_version", "lcd_layout_revision", "lcd_last_error_string", "lcd_status_string",
     "lcd_packed_bytes", "lcd_lut_bytes", "lcd_workspace_bytes",
     "lcd_pack_indices", "lcd_unpack_indices", "lcd_pack_indices_host", "lcd_unpack_indices_host",
-    "lcd_build_lut", "lcd_lut_gemv", "lcd_lut_gemm",
-    "lcd_workspace_bytes_grouped", "lcd_lut_gemv_grouped",
+    "lcd_build_lut", "lcd_lut_gemv", "lcd_lut_gemm", "lcd_lut_gemv_q8",
+    "lcd_workspace_bytes_grouped", "lcd_lut_gemv_grouped", "lcd_lut_gemv_q8_grouped",
 )
 
 
@@ -72,10 +72,14 @@ def load_library():
         fn = getattr(lib, name)
         fn.restype = ci
         fn.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, vp, sz, vp]
+    lib.lcd_lut_gemv_q8.restype = ci
+    lib.lcd_lut_gemv_q8.argtypes = [vp, vp, vp, vp, ctypes.c_float, vp, ci, ci, ci, ci, vp, sz, vp]
     lib.lcd_workspace_bytes_grouped.restype = sz
     lib.lcd_workspace_bytes_grouped.argtypes = [ctypes.POINTER(_Problem), ci, ci, ci]
     lib.lcd_lut_gemv_grouped.restype = ci
     lib.lcd_lut_gemv_grouped.argtypes = [ctypes.POINTER(_Problem), ci, ci, ci, vp, sz, vp]
+    lib.lcd_lut_gemv_q8_grouped.restype = ci
+    lib.lcd_lut_gemv_q8_grouped.argtypes = [ctypes.POINTER(_Problem), ctypes.POINTER(ctypes.c_float), ci, ci, ci, vp, sz, vp]
     _lib = lib
     return lib
 
@@ -201,6 +205,22 @@ def lcd_lut_gemv(packed, lut, x, s, N: int, bits: int, y=None, workspace=None, s
     return _product("lcd_lut_gemv", packed, lut, x, s, N, bits, y, workspace, stream)
 
 
+def lcd_lut_gemv_q8(packed, lut, x, s, s_q: float, N: int, bits: int, y=None, workspace=None, stream=None):
+    """Decode path with the INT8 input transformation in front: y = s_q * sum_k q_k * C[n][idx], M <= 16."""
+    import torch
+    lib = load_library()
+    M, K = x.shape
+    if y is None:
+        y = torch.empty((M, N), dtype=torch.float16, device=x.device)
+    if workspace is None:
+        workspace = torch.empty(max(lib.lcd_workspace_bytes(M, N, K, bits), 256), dtype=torch.uint8, device=x.device)
+    _check(lib.lcd_lut_gemv_q8(
+        _dev(packed, torch.uint8, "packed"), _dev(lut, torch.uint8, "lut"), _dev(x, torch.float16, "x"),
+        _dev(s, torch.float32, "s"), float(s_q), _dev(y, torch.float16, "y"), M, N, K, bits,
+        _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream)))
+    return y
+
+
 def lcd_lut_gemm(packed, lut, x, s, N: int, bits: int, y=None, workspace=None, stream=None):
     """Prefill path, x: CUDA float16 [M, K] -> y float16 [M, N]."""
     return _product("lcd_lut_gemm", packed, lut, x, s, N, bits, y, workspace, stream)
@@ -210,9 +230,10 @@ class GemvGroup:
     """Marshalled argument block of lcd_lut_gemv_grouped: build once per layer set, call many times.
 
     problems: sequence of (packed, lut, x, s, y, N) with CUDA tensors as in lcd_lut_gemv.
+    s_q: optional sequence of per-layer activation quantisation steps (lcd_lut_gemv_q8_grouped).
     """
 
-    def __init__(self, problems, bits: int, workspace=None):
+    def __init__(self, problems, bits: int, workspace=None, s_q=None):
         import torch
         lib = load_library()
         self.bits = bits
@@ -229,6 +250,11 @@ class GemvGroup:
                               _dev(x, torch.float16, "x").value, _dev(s, torch.float32, "s").value,
                               _dev(y, torch.float16, "y").value, N, K)
         self._arr = arr
+        self._s_q = None
+        if s_q is not None:
+            if len(s_q) != self.count:
+                raise ValueError("one s_q per problem")
+            self._s_q = (ctypes.c_float * self.count)(*[float(v) for v in s_q])
         need = lib.lcd_workspace_bytes_grouped(arr, self.count, M, bits)
         if need == 0:
             raise ValueError("invalid group (shapes, M or bits)")
@@ -236,9 +262,13 @@ class GemvGroup:
 
     def __call__(self, stream=None):
         import torch
-        _check(load_library().lcd_lut_gemv_grouped(self._arr, self.count, self.M, self.bits,
-                                                   _dev(self.workspace, torch.uint8, "workspace"), self.workspace.numel(),
-                                                   _stream(stream)))
+        ws = _dev(self.workspace, torch.uint8, "workspace")
+        if self._s_q is None:
+            _check(load_library().lcd_lut_gemv_grouped(self._arr, self.count, self.M, self.bits, ws, self.workspace.numel(),
+                                                       _stream(stream)))
+        else:
+            _check(load_library().lcd_lut_gemv_q8_grouped(self._arr, self._s_q, self.count, self.M, self.bits, ws,
+                                                          self.workspace.numel(), _stream(stream)))
 
 
 def lcd_workspace_bytes_grouped(problems, bits: int) -> int:

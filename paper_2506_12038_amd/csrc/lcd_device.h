@@ -39,6 +39,39 @@ __device__ __forceinline__ _Float16 smooth_one(uint16_t xbits, float s)
     return (_Float16)(xf * __builtin_amdgcn_rcpf(s));
 }
 
+// Input transformation of paper Sec. 4.1 (Eq. 10-11, b = 8), the smoothing and the quantisation
+// fused: q = clip(round_half_even(x / (s * s_q)), -128, 127), every step in binary32 and the
+// quotient correctly rounded (the rounding decision must be reproducible on the CPU, so a product
+// with an approximate reciprocal is not enough).  The division is the usual reciprocal-refinement
+// scheme, split so that the part which depends on the divisor alone is computed once per column
+// and shared by all tokens: a Newton step on the hardware reciprocal, then per quotient a product
+// and two residual corrections, all fused multiply-adds.  Valid without range scaling because
+// |x| is a finite fp16 number and the caller keeps 2^-64 < s * s_q < 2^64.
+struct Divisor {
+    float neg_d;   // -(s * s_q)
+    float y;       // refined reciprocal of s * s_q
+};
+
+__device__ __forceinline__ Divisor make_divisor(float s, float s_q)
+{
+    const float d = s * s_q;
+    const float y0 = __builtin_amdgcn_rcpf(d);
+    const float e = __builtin_fmaf(-d, y0, 1.0f);
+    return Divisor{-d, __builtin_fmaf(e, y0, y0)};
+}
+
+// The code is returned as an fp16 number: integers up to 128 are exact.
+__device__ __forceinline__ _Float16 quantise_one(uint16_t xbits, Divisor dv)
+{
+    const float xf = (float)__builtin_bit_cast(_Float16, xbits);
+    float qt = xf * dv.y;
+    qt = __builtin_fmaf(__builtin_fmaf(dv.neg_d, qt, xf), dv.y, qt);
+    qt = __builtin_fmaf(__builtin_fmaf(dv.neg_d, qt, xf), dv.y, qt);
+    float r = __builtin_rintf(qt);
+    r = __builtin_fminf(__builtin_fmaxf(r, -128.0f), 127.0f);
+    return (_Float16)r;
+}
+
 // a ^ (b & c): one v_bitop3_b32.
 __device__ __forceinline__ uint32_t xor_and(uint32_t a, uint32_t b, uint32_t c) { return a ^ (b & c); }
 

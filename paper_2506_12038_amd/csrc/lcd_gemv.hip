@@ -70,6 +70,8 @@ struct BucketProblem {
     uint16_t *y;
     int nt, kc;
     int tiles_base, tiles_extra;  // workgroup i of this layer owns tiles_base (+1 if i < tiles_extra) row tiles
+    float act_scale;              // 0: fp16 activations x/s; s_q > 0: INT8 codes of Sec. 4.1, output scaled by s_q
+    int x_ready;                  // tokens kernel: x already holds the smoothed activations / the codes (transform_kernel)
 };
 struct BucketBatch {
     BucketProblem p[kMaxGroup];
@@ -194,6 +196,8 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const BucketBa
     const int ta = li * pb.tiles_base + min(li, pb.tiles_extra);
     const int tb = ta + pb.tiles_base + (li < pb.tiles_extra ? 1 : 0);
     const int kc = pb.kc, nseg = (kc + kBSeg - 1) / kBSeg;
+    const bool quantised = pb.act_scale != 0.0f;               // wave-uniform
+    const float out_scale = quantised ? pb.act_scale : 1.0f;
     const __amdgpu_buffer_rsrc_t rs_packed = make_rsrc(pb.packed, (uint32_t)pb.nt * (uint32_t)kc * TB);
     const __amdgpu_buffer_rsrc_t rs_x = make_rsrc(pb.x, (uint32_t)kc * kTileCols * 2);
     const __amdgpu_buffer_rsrc_t rs_s = make_rsrc(pb.s, (uint32_t)kc * kTileCols * 4);
@@ -349,9 +353,16 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const BucketBa
             {   // smooth this thread's 8 activations of the segment (loaded one segment ago)
                 const bool in_k = wave_chunk(cur.sg, wave, lane >> 5) < kc;
                 half8 o;
+                if (!quantised) {
 #pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    o[e] = in_k ? smooth_one((uint16_t)(xv[e >> 1] >> (16 * (e & 1))), e < 4 ? s0[e] : s1[e - 4]) : (_Float16)0.0f;
+                    for (int e = 0; e < 8; ++e)
+                        o[e] = !in_k ? (_Float16)0.0f : smooth_one((uint16_t)(xv[e >> 1] >> (16 * (e & 1))), e < 4 ? s0[e] : s1[e - 4]);
+                } else {   // wave-uniform branch
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        o[e] = !in_k ? (_Float16)0.0f
+                                     : quantise_one((uint16_t)(xv[e >> 1] >> (16 * (e & 1))), make_divisor(e < 4 ? s0[e] : s1[e - 4], pb.act_scale));
+                }
                 *reinterpret_cast<half8 *>(&xs_lds[8 * threadIdx.x]) = o;
                 // next segment's activations: of this visit, or segment 0 again for the next visit
                 const bool more = cur.sg + 1 < nseg;
@@ -377,7 +388,7 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const BucketBa
             float sum = 0.f;
 #pragma unroll
             for (int w = 0; w < kBW; ++w) sum += part[w * (kVisitTiles * 16) + e];
-            pb.y[(size_t)cur.v0 * kTileRows + e] = __builtin_bit_cast(uint16_t, (_Float16)sum);
+            pb.y[(size_t)cur.v0 * kTileRows + e] = __builtin_bit_cast(uint16_t, (_Float16)(sum * out_scale));
         }
         cursor_next_visit(cur);
         if (!cur.done) __syncthreads();   // the next visit's waves overwrite their slots
@@ -456,6 +467,8 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_tokens_kernel(const BucketBa
     const int ta = li * pb.tiles_base + min(li, pb.tiles_extra);
     const int tb_end = ta + pb.tiles_base + (li < pb.tiles_extra ? 1 : 0);
     const int kc = pb.kc, nseg = (kc + kBW * CH - 1) / (kBW * CH), K = kc * kTileCols, N = pb.nt * kTileRows;
+    const bool x_ready = pb.x_ready != 0;                       // wave-uniform
+    const float out_scale = pb.act_scale != 0.0f ? pb.act_scale : 1.0f;
     const __amdgpu_buffer_rsrc_t rs_packed = make_rsrc(pb.packed, (uint32_t)pb.nt * (uint32_t)kc * TB);
     const __amdgpu_buffer_rsrc_t rs_x = make_rsrc(pb.x, (uint32_t)M * (uint32_t)K * 2);
     const __amdgpu_buffer_rsrc_t rs_s = make_rsrc(pb.s, (uint32_t)K * 4);
@@ -496,18 +509,30 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_tokens_kernel(const BucketBa
         for (int ch = 0; ch < CH; ++ch) {
             const bool cv = wave_chunk<CH>(sg, wave, ch) < kc;
             chunk_in_k[ch] = cv;
-            float rs[8];
+            // operand slot order 0,4,1,5,2,6,3,7 (the dequantiser pairs weight v with weight 4+v)
+            if (!x_ready) {
+                float rs[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) rs[e] = cv ? __builtin_amdgcn_rcpf(e < 4 ? sa[ch][e] : sb[ch][e - 4]) : 0.0f;
+                for (int e = 0; e < 8; ++e) rs[e] = cv ? __builtin_amdgcn_rcpf(e < 4 ? sa[ch][e] : sb[ch][e - 4]) : 0.0f;
 #pragma unroll
-            for (int mm = 0; mm < 8; ++mm) {
-                half8 o;   // operand slot order 0,4,1,5,2,6,3,7 (the dequantiser pairs weight v with weight 4+v)
+                for (int mm = 0; mm < 8; ++mm) {
+                    half8 o;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const float xf = (float)__builtin_bit_cast(_Float16, (uint16_t)(xr[ch][mm][e >> 1] >> (16 * (e & 1))));
-                    o[(e & 3) * 2 + (e >> 2)] = (_Float16)(xf * rs[e]);
+                    for (int e = 0; e < 8; ++e) {
+                        const uint16_t xb = (uint16_t)(xr[ch][mm][e >> 1] >> (16 * (e & 1)));
+                        o[(e & 3) * 2 + (e >> 2)] = (_Float16)((float)__builtin_bit_cast(_Float16, xb) * rs[e]);
+                    }
+                    *reinterpret_cast<half8 *>(&my_stage[(th * 8 + mm) * kStageStride + 8 * kg]) = o;
                 }
-                *reinterpret_cast<half8 *>(&my_stage[(th * 8 + mm) * kStageStride + 8 * kg]) = o;
+            } else {   // wave-uniform branch: x already holds the operands, only the slot order is left
+#pragma unroll
+                for (int mm = 0; mm < 8; ++mm) {
+                    const uint4v v = xr[ch][mm];   // OOB loads returned zero
+                    uint4v o;
+                    o[0] = __builtin_amdgcn_perm(v[2], v[0], 0x05040100u); o[1] = __builtin_amdgcn_perm(v[2], v[0], 0x07060302u);
+                    o[2] = __builtin_amdgcn_perm(v[3], v[1], 0x05040100u); o[3] = __builtin_amdgcn_perm(v[3], v[1], 0x07060302u);
+                    *reinterpret_cast<uint4v *>(&my_stage[(th * 8 + mm) * kStageStride + 8 * kg]) = o;
+                }
             }
 #pragma unroll
             for (int g = 0; g < 8; ++g)   // written by this wave only: LDS operations of a wave stay in order
@@ -563,7 +588,7 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_tokens_kernel(const BucketBa
                 if (cur.sg + 1 < nseg) *slot = sum;
             }
             if (cur.sg + 1 == nseg && m < M)
-                pb.y[(size_t)m * N + (size_t)(cur.v0 + tl + which) * kTileRows + row] = __builtin_bit_cast(uint16_t, (_Float16)sum);
+                pb.y[(size_t)m * N + (size_t)(cur.v0 + tl + which) * kTileRows + row] = __builtin_bit_cast(uint16_t, (_Float16)(sum * out_scale));
         }
         phase ^= 1;
     };
@@ -615,6 +640,58 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_tokens_kernel(const BucketBa
     LCD_STAMP(6);
 }
 
+// ---- activation transformation ahead of the tokens kernel (Sec. 4.1) -----------------------------
+// For 2..16 tokens every workgroup of a layer stages the whole activation matrix, so whatever is
+// done to an activation is repeated by each of them.  This small kernel does it once per layer
+// and leaves the result, as fp16 numbers in the layout of x, in the workspace: the INT8 codes of
+// Eq. 10 (always: the divisions are expensive), or the smoothed activations x/s when K is large
+// enough for the saving to exceed the extra launch.  One thread takes 8 columns of a few tokens:
+// the divisor-only part of the division is shared by them.
+struct TransformItem {
+    const uint16_t *x;
+    const float *s;
+    uint16_t *codes;
+    int K;
+    float s_q;
+};
+struct TransformBatch {
+    TransformItem p[kMaxGroup];
+};
+constexpr int kQuantThreads = 64;
+constexpr int kQuantTokens = 4;
+constexpr int kPrepassMinK = 16384;   // widest layer of a group from which fp16 activations are smoothed ahead
+
+__global__ __launch_bounds__(kQuantThreads) void transform_kernel(TransformBatch batch, int M)
+{
+    const TransformItem it = batch.p[blockIdx.y];
+    const int k0 = ((int)blockIdx.x * kQuantThreads + (int)threadIdx.x) * 8;
+    if (k0 >= it.K) return;   // K is a multiple of 256: a thread's 8 columns are all inside or all outside
+    const float4v s0 = *reinterpret_cast<const float4v *>(it.s + k0), s1 = *reinterpret_cast<const float4v *>(it.s + k0 + 4);
+    const bool quantised = it.s_q != 0.0f;   // uniform
+    Divisor dv[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) dv[e] = make_divisor(e < 4 ? s0[e] : s1[e - 4], quantised ? it.s_q : 1.0f);
+    // blockIdx.z: a group of kQuantTokens tokens (short dependent chains, all loads in flight together)
+    const int m0 = (int)blockIdx.z * kQuantTokens;
+    uint4v v[kQuantTokens];
+#pragma unroll
+    for (int i = 0; i < kQuantTokens; ++i)
+        if (m0 + i < M) v[i] = *reinterpret_cast<const uint4v *>(it.x + (size_t)(m0 + i) * it.K + k0);
+#pragma unroll
+    for (int i = 0; i < kQuantTokens; ++i) {
+        if (m0 + i < M) {
+            half8 o;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint16_t xb = (uint16_t)(v[i][e >> 1] >> (16 * (e & 1)));
+                if (quantised) o[e] = quantise_one(xb, dv[e]);
+                else o[e] = smooth_one(xb, e < 4 ? s0[e] : s1[e - 4]);   // rounds as the fused path does
+            }
+            *reinterpret_cast<half8 *>(it.codes + (size_t)(m0 + i) * it.K + k0) = o;
+        }
+    }
+}
+
 #ifdef LCD_TRACE
 unsigned long long *g_trace = nullptr;
 extern "C" void lcd_debug_set_trace(unsigned long long *p) { g_trace = p; }
@@ -631,18 +708,42 @@ static int num_cus()
 }
 
 // One launch for a group of decode problems: the bucket kernel for one token, the tokens kernel for 2..16.
-int launch_decode_group(const GroupItem *items, int count, int M, int bits, void *stream_)
+int launch_decode_group(const GroupItem *items, int count, int M, int bits, void *workspace, void *stream_)
 {
     hipStream_t stream = (hipStream_t)stream_;
     BucketBatch batch{};
     long long cost[kMaxGroup], total = 0;
     int tiles = 0;
+    // several tokens: quantised activations are made once, ahead of the product, and so are smoothed
+    // ones when the layers are wide (measured: the launch costs about 3.6 us; re-smoothing in every
+    // workgroup costs 1.9 us for K = 4096 / 11008 and 4.3 us for K = 8192 / 28672)
+    const uint16_t *codes[kMaxGroup] = {};
+    int widest = 0;
+    for (int i = 0; i < count; ++i) widest = items[i].K > widest ? items[i].K : widest;
+    if (M > 1 && (items[0].act_scale != 0.0f || widest >= kPrepassMinK)) {
+        TransformBatch qb{};
+        size_t offset = 0;
+        int max_k = 0;
+        for (int i = 0; i < count; ++i) {
+            uint16_t *dst = reinterpret_cast<uint16_t *>(static_cast<char *>(workspace) + offset);
+            qb.p[i] = TransformItem{items[i].x, items[i].s, dst, items[i].K, items[i].act_scale};
+            codes[i] = dst;
+            offset += decode_codes_bytes(M, items[i].K);
+            if (items[i].K > max_k) max_k = items[i].K;
+        }
+        const int per_block = kQuantThreads * 8;
+        void *qargs[] = {&qb, const_cast<int *>(&M)};
+        if (hipError_t e = hipLaunchKernel((const void *)transform_kernel, dim3((max_k + per_block - 1) / per_block, count, (M + kQuantTokens - 1) / kQuantTokens),
+                                           dim3(kQuantThreads), qargs, 0, stream)) return (int)e;
+    }
     for (int i = 0; i < count; ++i) {
         BucketProblem &p = batch.p[i];
         p.packed = (const uint8_t *)items[i].packed;
         p.lutA = (const float *)items[i].lut;
-        p.x = items[i].x; p.s = items[i].s; p.y = items[i].y;
+        p.x = codes[i] ? codes[i] : items[i].x; p.s = items[i].s; p.y = items[i].y;
         p.nt = items[i].N / kTileRows; p.kc = items[i].K / kTileCols;
+        p.act_scale = items[i].act_scale;
+        p.x_ready = codes[i] != nullptr;
         cost[i] = (long long)p.nt * p.kc;
         total += cost[i];
         tiles += p.nt;
@@ -726,10 +827,10 @@ int launch_decode_group(const GroupItem *items, int count, int M, int bits, void
 }
 
 int launch_gemv(const void *packed, const void *lut, const uint16_t *x, const float *s, uint16_t *y,
-                int M, int N, int K, int bits, void *stream_)
+                int M, int N, int K, int bits, float act_scale, void *workspace, void *stream_)
 {
-    GroupItem it{packed, lut, x, s, y, N, K};
-    return launch_decode_group(&it, 1, M, bits, stream_);
+    GroupItem it{packed, lut, x, s, y, N, K, act_scale};
+    return launch_decode_group(&it, 1, M, bits, workspace, stream_);
 }
 
 }  // namespace lcd

@@ -87,6 +87,7 @@ const char *lcd_status_string(lcd_status st)
     case LCD_ERR_INDEX_RANGE: return "LCD_ERR_INDEX_RANGE";
     case LCD_ERR_ALIGN: return "LCD_ERR_ALIGN";
     case LCD_ERR_HIP: return "LCD_ERR_HIP";
+    case LCD_ERR_BAD_SCALE: return "LCD_ERR_BAD_SCALE";
     }
     return "LCD_ERR_UNKNOWN";
 }
@@ -106,7 +107,8 @@ size_t lcd_lut_bytes(int N, int bits)
 size_t lcd_workspace_bytes(int M, int N, int K, int bits)
 {
     if (check_shape(N, K, bits) != LCD_OK || M < 1) return 0;
-    // the decode path (lcd_lut_gemv) needs none; the prefill path keeps the smoothed activations there
+    // the prefill path keeps the smoothed activations there; the decode path only the activation
+    // codes of lcd_lut_gemv_q8 with M > 1 (M*K fp16 numbers, less than the prefill's M padded to 128)
     const GemmPlan m = plan_gemm(M, N, K, bits);
     return m.xs_bytes < 256 ? 256 : m.xs_bytes;
 }
@@ -221,7 +223,18 @@ lcd_status lcd_lut_gemv(const void *packed, const void *lut, const uint16_t *x, 
 {
     if (M > 16) return fail(LCD_ERR_BAD_M, "lcd_lut_gemv: M=%d > 16 (use lcd_lut_gemm)", M);
     if (lcd_status st = check_product(packed, lut, x, s, y, M, N, K, bits, workspace, workspace_bytes)) return st;
-    if (int e = launch_gemv(packed, lut, x, s, y, M, N, K, bits, stream))
+    if (int e = launch_gemv(packed, lut, x, s, y, M, N, K, bits, 0.0f, workspace, stream))
+        return fail(LCD_ERR_HIP, "gemv launch: %s", hip_error_name(e));
+    return LCD_OK;
+}
+
+lcd_status lcd_lut_gemv_q8(const void *packed, const void *lut, const uint16_t *x, const float *s, float s_q,
+                           uint16_t *y, int M, int N, int K, int bits, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (M > 16) return fail(LCD_ERR_BAD_M, "lcd_lut_gemv_q8: M=%d > 16", M);
+    if (!(s_q > 0.0f) || !(s_q < 3.0e38f)) return fail(LCD_ERR_BAD_SCALE, "s_q=%g must be positive and finite", (double)s_q);
+    if (lcd_status st = check_product(packed, lut, x, s, y, M, N, K, bits, workspace, workspace_bytes)) return st;
+    if (int e = launch_gemv(packed, lut, x, s, y, M, N, K, bits, s_q, workspace, stream))
         return fail(LCD_ERR_HIP, "gemv launch: %s", hip_error_name(e));
     return LCD_OK;
 }
@@ -229,30 +242,50 @@ lcd_status lcd_lut_gemv(const void *packed, const void *lut, const uint16_t *x, 
 size_t lcd_workspace_bytes_grouped(const lcd_gemv_problem *problems, int count, int M, int bits)
 {
     if (!problems || count < 1 || count > kMaxGroup || M < 1 || M > 16) return 0;
-    size_t need = 256;
+    size_t need = 256, codes = 0;   // the q8 variant keeps every layer's activation codes side by side
     for (int i = 0; i < count; ++i) {
         const size_t w = lcd_workspace_bytes(M, problems[i].N, problems[i].K, bits);
         if (w == 0) return 0;
         if (w > need) need = w;
+        codes += decode_codes_bytes(M, problems[i].K);
     }
-    return need;
+    return codes > need ? codes : need;
+}
+
+static lcd_status gemv_grouped(const lcd_gemv_problem *problems, const float *s_q, int count, int M, int bits,
+                               void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!problems) return fail(LCD_ERR_NULL, "problems is NULL");
+    if (count < 1 || count > kMaxGroup) return fail(LCD_ERR_SIZE, "count=%d must be in 1..%d", count, kMaxGroup);
+    if (M > 16) return fail(LCD_ERR_BAD_M, "grouped gemv: M=%d > 16", M);
+    size_t codes = 0;
+    for (int i = 0; i < count; ++i) {
+        const lcd_gemv_problem &p = problems[i];
+        if (lcd_status st = check_product(p.packed, p.lut, p.x, p.s, p.y, M, p.N, p.K, bits, workspace, workspace_bytes)) return st;
+        codes += decode_codes_bytes(M, p.K);
+        if (s_q && (!(s_q[i] > 0.0f) || !(s_q[i] < 3.0e38f)))
+            return fail(LCD_ERR_BAD_SCALE, "s_q[%d]=%g must be positive and finite", i, (double)s_q[i]);
+    }
+    if (M > 1 && workspace_bytes < codes) return fail(LCD_ERR_SIZE, "workspace_bytes=%zu < %zu", workspace_bytes, codes);
+    GroupItem items[kMaxGroup];
+    for (int i = 0; i < count; ++i)
+        items[i] = GroupItem{problems[i].packed, problems[i].lut, problems[i].x, problems[i].s, problems[i].y, problems[i].N, problems[i].K,
+                             s_q ? s_q[i] : 0.0f};
+    if (int e = launch_decode_group(items, count, M, bits, workspace, stream)) return fail(LCD_ERR_HIP, "grouped gemv launch: %s", hip_error_name(e));
+    return LCD_OK;
 }
 
 lcd_status lcd_lut_gemv_grouped(const lcd_gemv_problem *problems, int count, int M, int bits,
                                 void *workspace, size_t workspace_bytes, void *stream)
 {
-    if (!problems) return fail(LCD_ERR_NULL, "problems is NULL");
-    if (count < 1 || count > kMaxGroup) return fail(LCD_ERR_SIZE, "count=%d must be in 1..%d", count, kMaxGroup);
-    if (M > 16) return fail(LCD_ERR_BAD_M, "lcd_lut_gemv_grouped: M=%d > 16", M);
-    for (int i = 0; i < count; ++i) {
-        const lcd_gemv_problem &p = problems[i];
-        if (lcd_status st = check_product(p.packed, p.lut, p.x, p.s, p.y, M, p.N, p.K, bits, workspace, workspace_bytes)) return st;
-    }
-    GroupItem items[kMaxGroup];
-    for (int i = 0; i < count; ++i)
-        items[i] = GroupItem{problems[i].packed, problems[i].lut, problems[i].x, problems[i].s, problems[i].y, problems[i].N, problems[i].K};
-    if (int e = launch_decode_group(items, count, M, bits, stream)) return fail(LCD_ERR_HIP, "grouped gemv launch: %s", hip_error_name(e));
-    return LCD_OK;
+    return gemv_grouped(problems, nullptr, count, M, bits, workspace, workspace_bytes, stream);
+}
+
+lcd_status lcd_lut_gemv_q8_grouped(const lcd_gemv_problem *problems, const float *s_q, int count, int M, int bits,
+                                   void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!s_q) return fail(LCD_ERR_NULL, "s_q is NULL");
+    return gemv_grouped(problems, s_q, count, M, bits, workspace, workspace_bytes, stream);
 }
 
 lcd_status lcd_lut_gemm(const void *packed, const void *lut, const uint16_t *x, const float *s, uint16_t *y,

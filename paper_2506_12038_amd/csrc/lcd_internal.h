@@ -27,16 +27,19 @@ constexpr int kMaxGroup = 16;     // problems per grouped launch
 
 struct GroupItem {
     const void *packed; const void *lut; const uint16_t *x; const float *s; uint16_t *y; int N, K;
+    float act_scale;   // 0: fp16 activations; s_q > 0: INT8 activation codes (paper Sec. 4.1)
 };
 // one launch for `count` decode problems (1 <= M <= 16 tokens each)
-int launch_decode_group(const GroupItem *items, int count, int M, int bits, void *stream);
+// (workspace: decode_codes_bytes(M, K) per item, in item order, when M > 1 and act_scale != 0)
+int launch_decode_group(const GroupItem *items, int count, int M, int bits, void *workspace, void *stream);
+inline size_t decode_codes_bytes(int M, int K) { return ((size_t)M * K * 2 + 255) / 256 * 256; }
 
 // Launchers implemented in the .hip files.  All return hipError_t as int (0 = success).
 int launch_pack(const uint8_t *idx, int N, int K, int bits, void *packed, void *stream);
 int launch_unpack(const void *packed, int N, int K, int bits, uint8_t *idx, void *stream);
 int launch_build_lut(const uint16_t *codebook, int N, int bits, void *lut, void *stream);
 int launch_gemv(const void *packed, const void *lut, const uint16_t *x, const float *s, uint16_t *y,
-                int M, int N, int K, int bits, void *stream);
+                int M, int N, int K, int bits, float act_scale, void *workspace, void *stream);
 int launch_gemm(const void *packed, const void *lut, const uint16_t *x, const float *s, uint16_t *y,
                 int M, int N, int K, int bits, void *workspace, const GemmPlan &plan, void *stream);
 const char *hip_error_name(int err);

@@ -137,3 +137,96 @@ def test_grouped_launch_replayed_from_a_hip_graph(bits, M):
         torch.cuda.synchronize()
         for p, ref in zip(problems, eager):
             assert torch.equal(p[4], ref), rep
+
+
+@pytest.mark.parametrize("bits", [2, 3])
+@pytest.mark.parametrize("M", [1, 5, 16])
+@pytest.mark.parametrize("shape", [(64, 1024), (48, 11008)])
+def test_gemv_q8_matches_the_quantised_oracle(bits, M, shape):
+    # input transformation (Eq. 10-11, b = 8) in front of the product; s_q such that ~1 % of the codes clip
+    N, K = shape
+    layer = synth.make_layer(1, 0, N, K, bits, M, seed_offset=N + K + M + 7)
+    xs = layer["x"].astype(np.float64) / layer["s"].astype(np.float64)
+    s_q = float(np.float32(np.quantile(np.abs(xs), 0.99) / 127.0))
+    packed = lcd.lcd_pack_indices(to_dev(layer["idx"]), bits)
+    lut = lcd.lcd_build_lut(to_dev(layer["codebook"]), bits)
+    y = lcd.lcd_lut_gemv_q8(packed, lut, to_dev(layer["x"]), to_dev(layer["s"]), s_q, N, bits).cpu().numpy()
+    Y = oracle.quantised_lut_matmul(layer["codebook"], layer["idx"], layer["x"], layer["s"], s_q, bits)
+    err = oracle.parity_errors(y, Y)
+    assert err["max_rel_floored"] <= 1e-3, err      # only fp32 accumulation and the fp16 store differ
+
+
+@pytest.mark.parametrize("M", [1, 4, 16])
+def test_gemv_q8_codes_are_bit_exact(M):
+    # identity layer (row n reads column n through a one-hot codebook): y[m][n] = s_q * q[m][n], so the
+    # quantiser's integer decisions are visible one by one; s_q = 2^-3 keeps the scaling exact.
+    import torch
+    bits, N, K = 2, 2048, 2048
+    codebook = np.zeros((N, 4), dtype=np.float16); codebook[:, 0] = 1.0
+    idx = np.ones((N, K), dtype=np.uint8); idx[np.arange(N), np.arange(K)] = 0
+    rng = np.random.default_rng(11)
+    x = (rng.standard_normal((M, K)) * 6).astype(np.float16)
+    s = (0.25 + rng.random(K) * 3).astype(np.float32)
+    s_q = 0.125
+    # plant exact ties and clip cases: s = 1 -> x / s_q = 8x
+    s[:8] = 1.0
+    x[0, :8] = np.array([0.0625, 0.1875, -0.0625, -0.1875, 15.9375, 100.0, -100.0, 16.0], dtype=np.float16)
+    q = oracle.input_transform(x, s, s_q, 8, single_precision=True)
+    assert q[0, :8].tolist() == [0, 2, 0, -2, 127, 127, -128, 127]
+    packed = lcd.lcd_pack_indices(to_dev(idx), bits)
+    lut = lcd.lcd_build_lut(to_dev(codebook), bits)
+    y = lcd.lcd_lut_gemv_q8(packed, lut, to_dev(x), to_dev(s), s_q, N, bits).cpu().numpy()
+    assert np.array_equal(y.astype(np.float64) / s_q, q.astype(np.float64))
+
+
+@pytest.mark.parametrize("bits,M", [(3, 1), (2, 1), (2, 8)])
+def test_grouped_q8_matches_oracle_and_single_calls(bits, M):
+    # one launch over layers with different shapes and different quantisation steps
+    import torch
+    from paper_2506_12038_amd.binding import GemvGroup
+    shapes = [(64, 1024), (208, 512), (48, 2816), (96, 4352)]
+    problems, layers, singles, steps = [], [], [], []
+    for i, (N, K) in enumerate(shapes):
+        layer = synth.make_layer(1, i, N, K, bits, M, seed_offset=5 * i + bits + M)
+        xs = layer["x"].astype(np.float64) / layer["s"].astype(np.float64)
+        s_q = float(np.float32(np.quantile(np.abs(xs), 0.99) / 127.0))
+        packed = lcd.lcd_pack_indices(to_dev(layer["idx"]), bits)
+        lut = lcd.lcd_build_lut(to_dev(layer["codebook"]), bits)
+        x, s = to_dev(layer["x"]), to_dev(layer["s"])
+        y = torch.full((M, N), float("nan"), dtype=torch.float16, device="cuda")
+        problems.append((packed, lut, x, s, y, N))
+        layers.append(layer)
+        steps.append(s_q)
+        singles.append(lcd.lcd_lut_gemv_q8(packed, lut, x, s, s_q, N, bits))
+    GemvGroup(problems, bits, s_q=steps)()
+    torch.cuda.synchronize()
+    for (packed, lut, x, s, y, N), layer, single, s_q in zip(problems, layers, singles, steps):
+        Y = oracle.quantised_lut_matmul(layer["codebook"], layer["idx"], layer["x"], layer["s"], s_q, bits)
+        err = oracle.parity_errors(y.cpu().numpy(), Y)
+        assert err["max_rel_floored"] <= 1e-3, err
+        assert torch.equal(y, single)
+
+
+@pytest.mark.parametrize("bits,M", [(2, 3), (3, 16)])
+def test_grouped_wide_and_narrow_layers(bits, M):
+    # a group with one layer wide enough for the activations to be smoothed ahead of the product:
+    # then all its layers take that route, while the single calls of the narrow ones smooth inside
+    # the kernel; both round the same way, so the outputs must agree bit for bit
+    import torch
+    shapes = [(32, 16384), (64, 1024), (48, 2816)]
+    problems, layers, singles = [], [], []
+    for i, (N, K) in enumerate(shapes):
+        layer = synth.make_layer(1, i, N, K, bits, M, seed_offset=11 * i + bits + M)
+        packed = lcd.lcd_pack_indices(to_dev(layer["idx"]), bits)
+        lut = lcd.lcd_build_lut(to_dev(layer["codebook"]), bits)
+        x, s = to_dev(layer["x"]), to_dev(layer["s"])
+        y = torch.full((M, N), float("nan"), dtype=torch.float16, device="cuda")
+        problems.append((packed, lut, x, s, y, N))
+        layers.append(layer)
+        singles.append(lcd.lcd_lut_gemv(packed, lut, x, s, N, bits))
+    lcd.lcd_lut_gemv_grouped(problems, bits)
+    torch.cuda.synchronize()
+    for (packed, lut, x, s, y, N), layer, single in zip(problems, layers, singles):
+        Y = oracle.lut_matmul(layer["codebook"], layer["idx"], layer["x"], layer["s"], bits)
+        assert oracle.parity_errors(y.cpu().numpy(), Y)["max_rel_floored"] <= TOL
+        assert torch.equal(y, single)

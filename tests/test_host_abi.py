@@ -116,6 +116,12 @@ def test_device_entry_points_validate_before_launch():
     assert st(lib.lcd_lut_gemv(a, a, a, a, a, 0, 16, 256, 2, a, big, None)) == b"LCD_ERR_BAD_M"
     assert st(lib.lcd_lut_gemv(a, a, a, a, a, 1, 16, 256, 2, a, 0, None)) == b"LCD_ERR_SIZE"
     assert st(lib.lcd_lut_gemv(a, a, a, odd, a, 1, 16, 256, 2, a, big, None)) == b"LCD_ERR_ALIGN"
+    lib.lcd_lut_gemv_q8.argtypes = [ctypes.c_void_p] * 4 + [ctypes.c_float, ctypes.c_void_p] + [ctypes.c_int] * 4 + [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    assert st(lib.lcd_lut_gemv_q8(a, a, a, a, 0.0, a, 1, 16, 256, 2, a, big, None)) == b"LCD_ERR_BAD_SCALE"
+    assert st(lib.lcd_lut_gemv_q8(a, a, a, a, float("nan"), a, 1, 16, 256, 2, a, big, None)) == b"LCD_ERR_BAD_SCALE"
+    assert st(lib.lcd_lut_gemv_q8(a, a, a, a, -1.0, a, 1, 16, 256, 2, a, big, None)) == b"LCD_ERR_BAD_SCALE"
+    assert st(lib.lcd_lut_gemv_q8(a, a, a, a, 0.5, a, 17, 16, 256, 2, a, big, None)) == b"LCD_ERR_BAD_M"
+    assert st(lib.lcd_lut_gemv_q8(a, None, a, a, 0.5, a, 1, 16, 256, 2, a, big, None)) == b"LCD_ERR_NULL"
     assert st(lib.lcd_lut_gemm(a, a, None, a, a, 64, 16, 256, 3, a, big, None)) == b"LCD_ERR_NULL"
     assert st(lib.lcd_lut_gemm(a, a, a, a, a, 64, 16, 256, 1, a, big, None)) == b"LCD_ERR_BAD_BITS"
 
@@ -139,3 +145,15 @@ def test_grouped_entry_point_validates_on_host():
     arr[1].K = 512
     arr[1].y = 0x1002
     assert st(lib.lcd_lut_gemv_grouped(arr, 2, 1, 2, ctypes.c_void_p(a), big, None)) == b"LCD_ERR_ALIGN"
+    arr[1].y = a
+    # the quantised variant: one positive finite step per layer, in a host array
+    sq = (ctypes.c_float * 2)(0.05, 0.0)
+    assert st(lib.lcd_lut_gemv_q8_grouped(arr, None, 2, 1, 2, ctypes.c_void_p(a), big, None)) == b"LCD_ERR_NULL"
+    assert st(lib.lcd_lut_gemv_q8_grouped(arr, sq, 2, 1, 2, ctypes.c_void_p(a), big, None)) == b"LCD_ERR_BAD_SCALE"
+    sq[1] = float("inf")
+    assert st(lib.lcd_lut_gemv_q8_grouped(arr, sq, 2, 4, 2, ctypes.c_void_p(a), big, None)) == b"LCD_ERR_BAD_SCALE"
+    sq[1] = 0.25
+    # several tokens: the workspace holds every layer's activation codes side by side
+    need = lib.lcd_workspace_bytes_grouped(arr, 2, 16, 2)
+    assert need >= 16 * (256 + 512) * 2
+    assert st(lib.lcd_lut_gemv_q8_grouped(arr, sq, 2, 16, 2, ctypes.c_void_p(a), 16 * 512 * 2, None)) == b"LCD_ERR_SIZE"
