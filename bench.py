@@ -40,21 +40,32 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the secondary measurements (other configs)")
     ap.add_argument("--per-layer", action="store_true", help="one lcd_lut_gemv call per matrix instead of one grouped call per step")
+    ap.add_argument("--bits", type=int, default=None, choices=[2, 3, 4], help="override the config's index width (4: the 16-centroid container)")
     ap.add_argument("--act-int8", action="store_true", help="decode configs: INT8 activation codes (input transformation of Sec. 4.1) instead of fp16 x/s")
     ap.add_argument("--eager", action="store_true", help="launch every step from Python instead of replaying a HIP graph")
     return ap.parse_args()
 
 
+def resolve_config(index, bits=None):
+    """A config of synth.configs, optionally with another index width on the same shapes."""
+    import dataclasses
+    import synth
+    cfg = synth.get_config(index)
+    if bits is not None and bits != cfg.bits:
+        cfg = dataclasses.replace(cfg, bits=bits, label=f"{cfg.label} [shapes only: index width set to {bits} bits]")
+    return cfg
+
+
 class LayerSet:
     """Device-resident inputs of one config: per matrix R replicas of (packed, lut), x, s, y, workspace."""
 
-    def __init__(self, cfg_index, M, replicas, keep_host=False, per_layer=False, act_int8=False):
+    def __init__(self, cfg_index, M, replicas, keep_host=False, per_layer=False, act_int8=False, bits=None):
         import numpy as np
         import torch
         import synth
         import paper_2506_12038_amd as lcd
 
-        self.cfg = synth.get_config(cfg_index)
+        self.cfg = resolve_config(cfg_index, bits)
         self.per_layer = per_layer
         self.bits = self.cfg.bits
         self.M = M
@@ -151,14 +162,14 @@ def time_steps(ls, replicas, steps, warmup, eager):
     return (t1 - t0) * 1e3 / steps, e0.elapsed_time(e1) / steps
 
 
-def cpu_baseline(cfg_index, M, budget_s=12.0):
+def cpu_baseline(cfg_index, M, budget_s=12.0, bits=None):
     """The oracle as it stands, on this machine's host cores, on a bounded sample of the workload:
     every distinct matrix shape of the config once (rows capped for large M), repeated until about
     `budget_s` seconds of oracle time have been spent; the best pass is reported."""
     import oracle
     import synth
 
-    cfg = synth.get_config(cfg_index)
+    cfg = resolve_config(cfg_index, bits)
     cap_weights = 4.0e8 / max(M, 1)          # per shape: keeps one pass at seconds, not minutes
     seen, layers, desc = set(), [], []
     for mid, spec in cfg.matrices():
@@ -212,24 +223,25 @@ def main():
     lcd.load_library()  # fail loudly if the HIP library is missing
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    cfg = synth.get_config(args.config)
+    cfg = resolve_config(args.config, args.bits)
     M = args.m if args.m is not None else cfg.Ms[0]
     replicas = args.replicas or max(2, -(-600_000_000 // cfg.index_bytes()))
     if args.act_int8 and (M > 16 or args.per_layer):
         sys.exit("--act-int8 applies to the grouped decode path (M <= 16)")
-    ls = LayerSet(args.config, M, replicas, per_layer=args.per_layer, act_int8=args.act_int8)
+    ls = LayerSet(args.config, M, replicas, per_layer=args.per_layer, act_int8=args.act_int8, bits=args.bits)
     wall_ms, event_ms = time_steps(ls, replicas, args.steps, args.warmup, args.eager)
 
     decode = M <= 16
     n_launch = 1 if (decode and not args.per_layer) else len(ls.mats)
+    decode_kernel = "gemv_bucket_kernel" if (M == 1 and cfg.bits < 4) else "gemv_tokens_kernel"
     if decode:
         metric, unit = "lut_gemv_effective_bandwidth_packed_index_bytes", "GB/s"
         value = ls.index_bytes / (wall_ms * 1e-3) / 1e9
         roofline = {
             "bound": "hbm", "achieved": ls.index_bytes / (event_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": ls.index_bytes / (event_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-            "traffic": measured_traffic("gemv_bucket_kernel" if M == 1 else "gemv_tokens_kernel", args.config) if n_launch == 1 else None,
-            "kernel": "gemv_bucket_kernel" if M == 1 else "gemv_tokens_kernel",
+            "traffic": measured_traffic(decode_kernel, args.config) if (n_launch == 1 and args.bits is None and not args.act_int8) else None,
+            "kernel": decode_kernel,
             "launches_per_step": n_launch, "algorithmic_bytes_per_step": ls.index_bytes,
             "avg_launch_us": event_ms * 1e3 / n_launch,
         }
@@ -256,7 +268,7 @@ def main():
     del ls
     torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(args.config, M)
+        out["cpu_baseline"] = cpu_baseline(args.config, M, bits=args.bits)
     print(json.dumps(out))
 
 

@@ -40,7 +40,7 @@ extern "C" {
 typedef enum {
     LCD_OK = 0,
     LCD_ERR_NULL = 1,        /* a required pointer is NULL                          */
-    LCD_ERR_BAD_BITS = 2,    /* bits not in {2,3}                                   */
+    LCD_ERR_BAD_BITS = 2,    /* bits not in {2,3,4}                                 */
     LCD_ERR_BAD_SHAPE = 3,   /* N or K not positive / not a multiple of the tile    */
     LCD_ERR_BAD_M = 4,       /* M out of range for the entry point                  */
     LCD_ERR_SIZE = 5,        /* a buffer-size argument is too small                 */
@@ -62,7 +62,7 @@ const char *lcd_status_string(lcd_status st);
 
 /* Bytes of the packed index matrix: exactly N*K*bits/8 (Sec. 4.2: compact low-bit indices). */
 size_t lcd_packed_bytes(int N, int K, int bits);
-/* Bytes of the per-layer table lcd_build_lut writes (24*N for 2 bits, 48*N for 3 bits). */
+/* Bytes of the per-layer table lcd_build_lut writes (24*N for 2 bits, 48*N for 3, 32*N for 4). */
 size_t lcd_lut_bytes(int N, int bits);
 /* Bytes of scratch the product entry points accept for this problem (a multiple of 256).  Only
  * lcd_lut_gemm uses it (smoothed activations in matrix-operand order, about 2*K bytes per token);
@@ -74,14 +74,19 @@ size_t lcd_workspace_bytes(int M, int N, int K, int bits);
  * Input:  idx[N][K], row-major, one index per byte.
  * Output: the packed layout (revision 1), made for 16-byte-per-lane, 1 KiB-per-wavefront
  * contiguous loads.  The matrix is cut into tiles of 16 rows x 256 columns; tile
- * (t = n/16, c = k/256) starts at byte (t*(K/256) + c) * T with T = 1024 (2 bits) or 1536
- * (3 bits).  Inside a tile, "lane" l = 16*q + i covers row i = n%16 and the 64 columns
+ * (t = n/16, c = k/256) starts at byte (t*(K/256) + c) * T with T = 1024 (2 bits), 1536
+ * (3 bits) or 2048 (4 bits).  Inside a tile, "lane" l = 16*q + i covers row i = n%16 and the 64 columns
  * k%256 in [64q, 64q+64); let w = k%64.
  *   - bytes [16*l, 16*l+16) of the tile are a 128-bit little-endian word whose bits
  *     [2w+1 : 2w] hold idx & 3;
  *   - 3 bits only: bytes [1024 + 8*l, 1024 + 8*l + 8) are two 32-bit little-endian words.
  *     With w = 16*d + 8*a + e (d<4, a<2, e<8), bit (idx >> 2) is stored in word a at bit
  *     8*((e>>2) + 2*(e&1)) + 2*d + ((e&3)>>1).
+ *   - 4 bits only (the container for up to 16 centroids, Sec. 4.2): bytes [1024 + 16*l,
+ *     1024 + 16*l + 16) are a second 128-bit little-endian word whose bits [2w+1 : 2w] hold
+ *     idx >> 2.
+ * A codebook with fewer centroids than its container holds (5, 6, 10, ...) simply never uses
+ * the upper codes; their codebook entries must be finite (zero is the natural choice).
  * The mapping is a bijection: lcd_unpack_indices(lcd_pack_indices(idx)) == idx, and the
  * device and host packers produce identical bytes.
  *
@@ -105,7 +110,7 @@ lcd_status lcd_unpack_indices_host(const void *packed /*HOST*/, int N, int K, in
  * lut:      DEVICE, lcd_lut_bytes(N,bits) bytes, opaque.  It holds the codebook re-laid out
  *           for the kernels: fp32 per-bucket multipliers in accumulator order for the decode
  *           path (Sec. 4.2: one bucket per weight centroid), and byte-split tables for the
- *           register dequantiser of the batched paths.
+ *           register dequantiser of the batched paths (4 bits: these tables only).
  */
 lcd_status lcd_build_lut(const uint16_t *codebook /*DEVICE*/, int N, int bits,
                          void *lut /*DEVICE*/, size_t lut_bytes, void *stream);
@@ -119,8 +124,9 @@ lcd_status lcd_build_lut(const uint16_t *codebook /*DEVICE*/, int N, int bits,
  * workspace  DEVICE, >= lcd_workspace_bytes(M,N,K,bits) bytes, contents ignored on entry.
  *
  * lcd_lut_gemv: decode path, 1 <= M <= 16, one kernel launch, any K.  M = 1: centroid-bucket
- *               sums on the sparse matrix core (Sec. 4.2); 2 <= M <= 16: register dequantisation
- *               into fp16 MFMA operands with the tokens as the matrix columns.  The smoothing
+ *               sums on the sparse matrix core (Sec. 4.2); 2 <= M <= 16, and every M with
+ *               4 bits: register dequantisation into fp16 MFMA operands with the tokens as the
+ *               matrix columns.  The smoothing
  *               is fused into the kernel, except for M >= 2 with K >= 16384, where a small
  *               kernel ahead of the product leaves the smoothed activations in the workspace
  *               (same rounding, same result).

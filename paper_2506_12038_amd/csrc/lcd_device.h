@@ -135,6 +135,45 @@ __device__ __forceinline__ void decode_quarter(uint32_t p, const HighBits &hb, c
     decode_interleave(lo, hi, o0, o1);
 }
 
+// ---- 4 bits: 16 centroids per row ------------------------------------------------------------
+// A byte permute reaches 8 table bytes, so the table is two pools (centroids 0..7 and 8..15):
+// both are looked up with the low three index bits as selector and a third permute takes, byte by
+// byte, the pool the fourth bit names.  p is the lane's low-plane word d, p2 its high-plane word d
+// (same bit positions, index bits 2 and 3).
+struct RowTables4 { uint32_t lo[4]; uint32_t hi[4]; };   // low / high bytes of centroids 4i..4i+3
+
+template <int T>
+__device__ __forceinline__ void decode_select4(uint32_t p, uint32_t p2, uint32_t &sel, uint32_t &pool)
+{
+    const uint32_t a = p >> (2 * T);
+    const uint32_t b = T == 0 ? (p2 << 2) : (p2 >> (T == 0 ? 0 : 2 * T - 2));   // index bit 2 to in-byte bit 2
+    const uint32_t c = T == 0 ? (p2 << 1) : (p2 >> (T == 0 ? 0 : 2 * T - 1));   // index bit 3 to in-byte bit 2
+    sel = (a & 0x03030303u) | (b & 0x04040404u);
+    pool = (c & 0x04040404u) | 0x03020100u;      // byte b: b (first pool) or 4 + b (second pool)
+}
+__device__ __forceinline__ void decode_lookup4(uint32_t sel, uint32_t pool, const RowTables4 &tb, uint32_t &lo, uint32_t &hi)
+{
+    lo = perm(perm(tb.lo[3], tb.lo[2], sel), perm(tb.lo[1], tb.lo[0], sel), pool);
+    hi = perm(perm(tb.hi[3], tb.hi[2], sel), perm(tb.hi[1], tb.hi[0], sel), pool);
+}
+template <int T>
+__device__ __forceinline__ void decode_quarter4(uint32_t p, uint32_t p2, const RowTables4 &tb, uint32_t &o0, uint32_t &o1)
+{
+    uint32_t sel, pool, lo, hi;
+    decode_select4<T>(p, p2, sel, pool);
+    decode_lookup4(sel, pool, tb, lo, hi);
+    decode_interleave(lo, hi, o0, o1);
+}
+// Same operand convention as decode_word below.
+__device__ __forceinline__ void decode_word4(uint32_t p, uint32_t p2, const RowTables4 &tb, uint4v &op0, uint4v &op1)
+{
+    uint32_t a, b;
+    decode_quarter4<0>(p, p2, tb, a, b); op0[0] = a; op1[0] = b;
+    decode_quarter4<1>(p, p2, tb, a, b); op0[1] = a; op1[1] = b;
+    decode_quarter4<2>(p, p2, tb, a, b); op0[2] = a; op1[2] = b;
+    decode_quarter4<3>(p, p2, tb, a, b); op0[3] = a; op1[3] = b;
+}
+
 template <int BITS, int D>
 __device__ __forceinline__ void decode_word(uint32_t p, const HighBits &hb, const RowTables &tb, uint4v &op0, uint4v &op1)
 {

@@ -275,14 +275,19 @@ __device__ __forceinline__ void zero_accs()
 template <int BITS>
 struct GemmTileRegs {
     uint4v lo[kGemmPairs];
-    uint2v hi[kGemmPairs];
+    uint2v hi[kGemmPairs];    // 3 bits: the third-bit words
+    uint4v hi4[kGemmPairs];   // 4 bits: the second plane
 };
+
+// byte-split codebook of a lane's row: two words of each kind up to 3 bits, four with 4 bits
+template <int BITS> struct GemmTables { typedef RowTables type; };
+template <> struct GemmTables<4> { typedef RowTables4 type; };
 
 template <int BITS>
 __device__ __forceinline__ void load_gemm_tiles(GemmTileRegs<BITS> &r, __amdgpu_buffer_rsrc_t packed, int t0, int nt,
                                                 int kc, int c, int h, int lane)
 {
-    constexpr uint32_t TB = BITS == 2 ? 1024 : 1536;
+    constexpr uint32_t TB = kTileRows * kTileCols * BITS / 8;
     const int sub = (lane >> 4) & 1, kh = lane >> 5, i = lane & 15;
 #pragma unroll
     for (int p = 0; p < kGemmPairs; ++p) {
@@ -292,6 +297,7 @@ __device__ __forceinline__ void load_gemm_tiles(GemmTileRegs<BITS> &r, __amdgpu_
         const bool v = tile < nt;
         r.lo[p] = __builtin_amdgcn_raw_buffer_load_b128(packed, v ? base + 16 * slot : 0xFFFFFFF0u, 0, 0);
         if (BITS == 3) r.hi[p] = __builtin_amdgcn_raw_buffer_load_b64(packed, v ? base + 1024 + 8 * slot : 0xFFFFFFF0u, 0, 0);
+        if (BITS == 4) r.hi4[p] = __builtin_amdgcn_raw_buffer_load_b128(packed, v ? base + 1024 + 16 * slot : 0xFFFFFFF0u, 0, 0);
     }
 }
 
@@ -334,6 +340,21 @@ __device__ __forceinline__ uint32_t lds_address(const uint8_t *p)
     return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) uint8_t *)p;
 }
 
+// The dequantiser's first two stages for quarter T of word DN of pair P, for any width: the selector
+// (4 bits: and the pool word), then the table lookups.
+template <int BITS, int DN, int T>
+__device__ __forceinline__ void gemm_select(const GemmTileRegs<BITS> &r, int p, const HighBits &hb, uint32_t &sel, uint32_t &pool)
+{
+    if constexpr (BITS == 4) decode_select4<T>(r.lo[p][DN], r.hi4[p][DN], sel, pool);
+    else sel = decode_select<BITS, DN, T>(r.lo[p][DN], hb);
+}
+template <int BITS>
+__device__ __forceinline__ void gemm_lookup(uint32_t sel, uint32_t pool, const typename GemmTables<BITS>::type &tb, uint32_t &lo, uint32_t &hi)
+{
+    if constexpr (BITS == 4) decode_lookup4(sel, pool, tb, lo, hi);
+    else decode_lookup<BITS>(sel, tb, lo, hi);
+}
+
 // Decoded A operands of one packed word: [pair][k-step of the word].
 struct WordOps { uint4v op[kGemmPairs][2]; };
 
@@ -347,12 +368,12 @@ struct WordOps { uint4v op[kGemmPairs][2]; };
 // chunk (the caller primes it again after the last word).
 template <int BITS, int D, int DN, bool COPY>
 __device__ __forceinline__ void gemm_word(const WordOps &cur, WordOps &nxt, const GemmTileRegs<BITS> &rn,
-                                          const HighBits (&hbn)[kGemmPairs], const RowTables (&tb)[kGemmPairs],
+                                          const HighBits (&hbn)[kGemmPairs], const typename GemmTables<BITS>::type (&tb)[kGemmPairs],
                                           uint32_t bbase, BWindow &bw,
                                           const uint8_t *copy_src, uint8_t *copy_dst, int wave, int lane)
 {
 #define LCD_GEMM_FENCE __builtin_amdgcn_sched_barrier(0);
-    uint32_t sel = 0;
+    uint32_t sel = 0, pool = 0;
 #define LCD_GEMM_STEP(ST)                                                                                   \
     {                                                                                                       \
         constexpr int st = ST, a = st >> 2, blk = st & 3, nx = st + 3, np = st >> 2, nt4 = st & 3;          \
@@ -360,7 +381,7 @@ __device__ __forceinline__ void gemm_word(const WordOps &cur, WordOps &nxt, cons
         /* prefetch step st+3 into the slot that step st-1 used */                                          \
         if (nx < 8) bw.w[nx & 3] = read_b<2 * D + (nx >> 2), (nx & 3)>(bbase);                              \
         else if (D < 3) bw.w[nx & 3] = read_b<(2 * D + 2) & 7, (nx - 8) & 3>(bbase);                        \
-        if (st == 0) sel = decode_select<BITS, DN, 0>(rn.lo[0][DN], hbn[0]);                                \
+        if (st == 0) gemm_select<BITS, DN, 0>(rn, 0, hbn[0], sel, pool);                                    \
         /* reads newer than this step's operand: 3, fewer at the end of a chunk's last word */             \
         lds_wait<(D < 3 || st <= 4) ? 3 : 7 - st>();                                                        \
         mfma_acc<blk>(cur.op[0][a], bw.w[st & 3]);                                                          \
@@ -369,10 +390,10 @@ __device__ __forceinline__ void gemm_word(const WordOps &cur, WordOps &nxt, cons
         /* quarter st, then the selector of quarter st+1, then the interleave: dependent instructions   */ \
         /* stay a few issue slots apart.                                                                 */ \
         if (COPY && copy_src) stage_copy(copy_src, copy_dst, wave, lane, st, 1);                            \
-        decode_lookup<BITS>(sel, tb[np], lo, hi);                                                           \
+        gemm_lookup<BITS>(sel, pool, tb[np], lo, hi);                                                       \
         LCD_GEMM_FENCE                                                                                      \
         mfma_acc<4 + blk>(cur.op[1][a], bw.w[st & 3]);                                                      \
-        if (st < 7) sel = decode_select<BITS, DN, (st + 1) & 3>(rn.lo[(st + 1) >> 2][DN], hbn[(st + 1) >> 2]); \
+        if (st < 7) gemm_select<BITS, DN, (st + 1) & 3>(rn, (st + 1) >> 2, hbn[(st + 1) >> 2], sel, pool);  \
         decode_interleave(lo, hi, o0, o1);                                                                  \
         nxt.op[np][0][nt4] = o0; nxt.op[np][1][nt4] = o1;                                                   \
         LCD_GEMM_FENCE                                                                                      \
@@ -395,7 +416,7 @@ gemm_kernel(const uint8_t *__restrict__ packed_, const uint8_t *__restrict__ lut
             uint16_t *__restrict__ y, int M, int Mpad, int N, int K, int grid_rows, int tiles_per_xcd)
 {
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];  // 2 stages x 64 KiB
-    constexpr uint32_t TB = BITS == 2 ? 1024 : 1536;
+    constexpr uint32_t TB = kTileRows * kTileCols * BITS / 8;
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: keeps addresses scalar
@@ -419,17 +440,22 @@ gemm_kernel(const uint8_t *__restrict__ packed_, const uint8_t *__restrict__ lut
     const uint8_t *xs_base = xs + (size_t)tb0 * 16 * 1024;
 
     // this lane's row in each pair, and its byte-split codebook
-    RowTables tb[kGemmPairs];
+    typename GemmTables<BITS>::type tb[kGemmPairs];
 #pragma unroll
     for (int p = 0; p < kGemmPairs; ++p) {
         const int tile = min(t0 + 2 * p + ((lane >> 4) & 1), nt - 1);
         const int row = tile * kTileRows + (lane & 15);
-        if (BITS == 2) {
+        if constexpr (BITS == 2) {
             const uint2v v = *reinterpret_cast<const uint2v *>(lutB + (size_t)row * 8);
             tb[p].lo[0] = v[0]; tb[p].hi[0] = v[1]; tb[p].lo[1] = 0; tb[p].hi[1] = 0;
-        } else {
+        } else if constexpr (BITS == 3) {
             const uint4v v = *reinterpret_cast<const uint4v *>(lutB + (size_t)row * 16);
             tb[p].lo[0] = v[0]; tb[p].lo[1] = v[1]; tb[p].hi[0] = v[2]; tb[p].hi[1] = v[3];
+        } else {
+            const uint4v v = *reinterpret_cast<const uint4v *>(lutB + (size_t)row * 32);
+            const uint4v w = *reinterpret_cast<const uint4v *>(lutB + (size_t)row * 32 + 16);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) { tb[p].lo[u] = v[u]; tb[p].hi[u] = w[u]; }
         }
     }
     zero_accs();
@@ -492,7 +518,10 @@ gemm_kernel(const uint8_t *__restrict__ packed_, const uint8_t *__restrict__ lut
     }
     high_bits(r0, hb);
 #pragma unroll
-    for (int p = 0; p < kGemmPairs; ++p) decode_word<BITS, 0>(r0.lo[p][0], hb[p], tb[p], wa.op[p][0], wa.op[p][1]);
+    for (int p = 0; p < kGemmPairs; ++p) {
+        if constexpr (BITS == 4) decode_word4(r0.lo[p][0], r0.hi4[p][0], tb[p], wa.op[p][0], wa.op[p][1]);
+        else decode_word<BITS, 0>(r0.lo[p][0], hb[p], tb[p], wa.op[p][0], wa.op[p][1]);
+    }
     for (int c = 0; c < kc; c += 2) {
         // even chunk: compute from stage 0 / r0 while chunk c+1 lands in stage 1 / r1
         const bool more1 = c + 1 < kc;
@@ -551,7 +580,8 @@ int launch_gemm(const void *packed, const void *lut, const uint16_t *x, const fl
     hipStream_t stream = (hipStream_t)stream_;
     const int Mpad = plan.m_pad;
     if (int e = launch_smooth(x, s, workspace, M, Mpad, K, stream)) return e;
-    const uint8_t *lutB = static_cast<const uint8_t *>(lut) + (size_t)N * (bits == 2 ? 4 : 8) * 4;
+    // byte-split tables: behind the bucket multipliers (2 and 3 bits), the whole table (4 bits)
+    const uint8_t *lutB = static_cast<const uint8_t *>(lut) + (bits == 4 ? 0 : (size_t)N * (bits == 2 ? 4 : 8) * 4);
     const int nt = N / kTileRows;
     const int tiles_per_wg = kGemmRowGroups * 2 * kGemmPairs;
     const int grid_rows = (nt + tiles_per_wg - 1) / tiles_per_wg;
@@ -559,22 +589,16 @@ int launch_gemm(const void *packed, const void *lut, const uint16_t *x, const fl
     const int tiles_per_xcd = (total_tiles + kXcds - 1) / kXcds;
     const dim3 grid(tiles_per_xcd * kXcds), block(kGemmWaves * 64);
     const size_t lds_bytes = 2 * kStageBytes;
-    static bool attr_set[2] = {false, false};
-    if (bits == 2) {
-        if (!attr_set[0]) {
-            if (hipError_t e = hipFuncSetAttribute((const void *)gemm_kernel<2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes)) return (int)e;
-            attr_set[0] = true;
-        }
-        hipLaunchKernelGGL(gemm_kernel<2>, grid, block, lds_bytes, stream, (const uint8_t *)packed, lutB,
-                           (const uint8_t *)workspace, y, M, Mpad, N, K, grid_rows, tiles_per_xcd);
-    } else {
-        if (!attr_set[1]) {
-            if (hipError_t e = hipFuncSetAttribute((const void *)gemm_kernel<3>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes)) return (int)e;
-            attr_set[1] = true;
-        }
-        hipLaunchKernelGGL(gemm_kernel<3>, grid, block, lds_bytes, stream, (const uint8_t *)packed, lutB,
-                           (const uint8_t *)workspace, y, M, Mpad, N, K, grid_rows, tiles_per_xcd);
+    static bool attr_set[3] = {false, false, false};
+    const void *fn = bits == 2 ? (const void *)gemm_kernel<2> : bits == 3 ? (const void *)gemm_kernel<3> : (const void *)gemm_kernel<4>;
+    if (!attr_set[bits - 2]) {
+        if (hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes)) return (int)e;
+        attr_set[bits - 2] = true;
     }
+    const uint8_t *packed_arg = static_cast<const uint8_t *>(packed), *xs_arg = static_cast<const uint8_t *>(workspace);
+    int M_arg = M, Mpad_arg = Mpad, N_arg = N, K_arg = K, rows_arg = grid_rows, xcd_arg = tiles_per_xcd;
+    void *args[] = {&packed_arg, &lutB, &xs_arg, &y, &M_arg, &Mpad_arg, &N_arg, &K_arg, &rows_arg, &xcd_arg};
+    if (hipError_t e = hipLaunchKernel(fn, grid, block, args, lds_bytes, stream)) return (int)e;
     return (int)hipGetLastError();
 }
 

@@ -416,15 +416,17 @@ constexpr int kStageStride = kTileCols + 8;   // halfs per token row of a wave's
 template <int BITS, int CH>
 struct TokStepRegs {
     uint4v lo[CH];
-    uint2v hi[CH];
-    uint4v tb;         // the lane's row of byte-split codebook tables
+    uint2v hi[CH];     // 3 bits: the third-bit words
+    uint4v hi4[CH];    // 4 bits: the second plane
+    uint4v tb;         // the lane's row of byte-split codebook tables (4 bits: the low bytes)
+    uint4v tb2;        // 4 bits: the high bytes
 };
 
 template <int BITS, int CH>
 __device__ __forceinline__ void issue_tok_loads(TokStepRegs<BITS, CH> &r, const Cursor &c, __amdgpu_buffer_rsrc_t rs,
                                                 __amdgpu_buffer_rsrc_t rs_tb, int kc, int wave, int lane)
 {
-    constexpr uint32_t TB = BITS == 2 ? 1024 : 1536;
+    constexpr uint32_t TB = kTileRows * kTileCols * BITS / 8;
     const int tile = c.v0 + c.i;
     const bool tv = !c.done && tile < c.v1;
 #pragma unroll
@@ -434,13 +436,17 @@ __device__ __forceinline__ void issue_tok_loads(TokStepRegs<BITS, CH> &r, const 
         const uint32_t o = ((uint32_t)tile * (uint32_t)kc + (uint32_t)chunk) * TB;
         r.lo[ch] = __builtin_amdgcn_raw_buffer_load_b128(rs, v ? o + 16 * lane : kOob, 0, 0);
         if (BITS == 3) r.hi[ch] = __builtin_amdgcn_raw_buffer_load_b64(rs, v ? o + 1024 + 8 * lane : kOob, 0, 0);
+        if (BITS == 4) r.hi4[ch] = __builtin_amdgcn_raw_buffer_load_b128(rs, v ? o + 1024 + 16 * lane : kOob, 0, 0);
     }
     const uint32_t row = (uint32_t)tile * kTileRows + (lane & 15);
     if (BITS == 2) {
         const uint2v t = __builtin_amdgcn_raw_buffer_load_b64(rs_tb, tv ? row * 8 : kOob, 0, 0);
         r.tb = uint4v{t[0], t[1], 0u, 0u};
-    } else {
+    } else if (BITS == 3) {
         r.tb = __builtin_amdgcn_raw_buffer_load_b128(rs_tb, tv ? row * 16 : kOob, 0, 0);
+    } else {
+        r.tb = __builtin_amdgcn_raw_buffer_load_b128(rs_tb, tv ? row * 32 : kOob, 0, 0);
+        r.tb2 = __builtin_amdgcn_raw_buffer_load_b128(rs_tb, tv ? row * 32 + 16 : kOob, 0, 0);
     }
 }
 
@@ -448,7 +454,7 @@ template <int BITS, int CH>
 __global__ void __launch_bounds__(kBW * 64, 1) gemv_tokens_kernel(const BucketBatch batch, const int M)
 {
     constexpr int NC = BITS == 2 ? 4 : 8;
-    constexpr uint32_t TB = BITS == 2 ? 1024 : 1536;
+    constexpr uint32_t TB = kTileRows * kTileCols * BITS / 8;
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     // LDS: [ stage: kBW x 16 tokens x kStageStride halfs ][ red: 2 x 2 x kBW x 256 floats ][ sums: kVisitTiles x 256 floats ]
     _Float16 *stage = reinterpret_cast<_Float16 *>(smem) ;
@@ -472,7 +478,9 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_tokens_kernel(const BucketBa
     const __amdgpu_buffer_rsrc_t rs_packed = make_rsrc(pb.packed, (uint32_t)pb.nt * (uint32_t)kc * TB);
     const __amdgpu_buffer_rsrc_t rs_x = make_rsrc(pb.x, (uint32_t)M * (uint32_t)K * 2);
     const __amdgpu_buffer_rsrc_t rs_s = make_rsrc(pb.s, (uint32_t)K * 4);
-    const __amdgpu_buffer_rsrc_t rs_tb = make_rsrc(reinterpret_cast<const uint8_t *>(pb.lutA) + (size_t)N * NC * 4, (uint32_t)N * (BITS == 2 ? 8 : 16));
+    // byte-split tables: behind the bucket multipliers (2 and 3 bits), the whole table (4 bits)
+    const __amdgpu_buffer_rsrc_t rs_tb = make_rsrc(reinterpret_cast<const uint8_t *>(pb.lutA) + (BITS == 4 ? 0 : (size_t)N * NC * 4),
+                                                   (uint32_t)N * (BITS == 2 ? 8 : BITS == 3 ? 16 : 32));
 
     Cursor pf{}, cur{};
     cursor_begin(pf, ta, tb_end);
@@ -544,13 +552,24 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_tokens_kernel(const BucketBa
         float4v acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
         RowTables t;
         if (BITS == 2) { t.lo[0] = r.tb[0]; t.hi[0] = r.tb[1]; t.lo[1] = 0; t.hi[1] = 0; }
+        else if (BITS == 4) { t.lo[0] = t.lo[1] = t.hi[0] = t.hi[1] = 0; }
         else { t.lo[0] = r.tb[0]; t.lo[1] = r.tb[1]; t.hi[0] = r.tb[2]; t.hi[1] = r.tb[3]; }
 #pragma unroll
         for (int ch = 0; ch < CH; ++ch) {
             if (!chunk_in_k[ch]) continue;
+            uint4v op0, op1;
+            if (BITS == 4) {
+                const RowTables4 t4{{r.tb[0], r.tb[1], r.tb[2], r.tb[3]}, {r.tb2[0], r.tb2[1], r.tb2[2], r.tb2[3]}};
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                    decode_word4(r.lo[ch][d], r.hi4[ch][d], t4, op0, op1);
+                    acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(op0), as_half8(Bx[ch][2 * d]), acc0, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(op1), as_half8(Bx[ch][2 * d + 1]), acc1, 0, 0, 0);
+                }
+                continue;
+            }
             HighBits hb{0u, 0u};
             if (BITS == 3) hb = regroup_high(r.hi[ch]);
-            uint4v op0, op1;
             decode_word<BITS, 0>(r.lo[ch][0], hb, t, op0, op1);
             acc0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(op0), as_half8(Bx[ch][0]), acc0, 0, 0, 0);
             acc1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(op1), as_half8(Bx[ch][1]), acc1, 0, 0, 0);
@@ -714,13 +733,14 @@ int launch_decode_group(const GroupItem *items, int count, int M, int bits, void
     BucketBatch batch{};
     long long cost[kMaxGroup], total = 0;
     int tiles = 0;
+    const bool tokens_path = M > 1 || bits == 4;   // 4 bits: the register dequantiser serves one token too
     // several tokens: quantised activations are made once, ahead of the product, and so are smoothed
     // ones when the layers are wide (measured: the launch costs about 3.6 us; re-smoothing in every
     // workgroup costs 1.9 us for K = 4096 / 11008 and 4.3 us for K = 8192 / 28672)
     const uint16_t *codes[kMaxGroup] = {};
     int widest = 0;
     for (int i = 0; i < count; ++i) widest = items[i].K > widest ? items[i].K : widest;
-    if (M > 1 && (items[0].act_scale != 0.0f || widest >= kPrepassMinK)) {
+    if (tokens_path && (items[0].act_scale != 0.0f || widest >= kPrepassMinK)) {
         TransformBatch qb{};
         size_t offset = 0;
         int max_k = 0;
@@ -756,9 +776,9 @@ int launch_decode_group(const GroupItem *items, int count, int M, int bits, void
     int grid = num_cus();
     if (grid > tiles) grid = tiles;
     if (grid < count) grid = count;
-    const double startup_steps = M > 1 ? 3.0 : bits == 2 ? 3.5 : 2.0;
-    const double segment_steps = M > 1 ? 1.5 : bits == 2 ? 1.8 : 0.4;
-    const double step_overhead = M > 1 ? 0.3 : 0.1;   // per tile and segment: barrier / bookkeeping
+    const double startup_steps = tokens_path ? 3.0 : bits == 2 ? 3.5 : 2.0;
+    const double segment_steps = tokens_path ? 1.5 : bits == 2 ? 1.8 : 0.4;
+    const double step_overhead = tokens_path ? 0.3 : 0.1;   // per tile and segment: barrier / bookkeeping
     auto split = [&](int ch, int *nwg) {
         const int seg = kBW * ch;
         auto layer_time = [&](int i, int n) {
@@ -808,15 +828,16 @@ int launch_decode_group(const GroupItem *items, int count, int M, int bits, void
     const int NC = bits == 2 ? 4 : 8;
     size_t lds;
     const void *fn;
-    if (M == 1) {
+    if (!tokens_path) {
         lds = (size_t)kBSeg * kTileCols * 2 + (size_t)kBW * kVisitTiles * 16 * 4;
         fn = bits == 2 ? (const void *)gemv_bucket_kernel<2> : (const void *)gemv_bucket_kernel<3>;
     } else {
         lds = (size_t)kBW * 16 * kStageStride * 2 + (size_t)2 * 2 * kBW * 256 * 4 + (size_t)kVisitTiles * 256 * 4;
-        fn = bits == 2 ? (const void *)gemv_tokens_kernel<2, kBCH> : (const void *)gemv_tokens_kernel<3, kBCH>;
+        fn = bits == 2 ? (const void *)gemv_tokens_kernel<2, kBCH> : bits == 3 ? (const void *)gemv_tokens_kernel<3, kBCH>
+                                                                              : (const void *)gemv_tokens_kernel<4, kBCH>;
     }
-    static bool lds_set[2][2] = {};
-    const int variant = M == 1 ? 0 : 1;
+    static bool lds_set[2][3] = {};
+    const int variant = tokens_path ? 1 : 0;
     if (!lds_set[variant][bits - 2]) {
         if (hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)) return (int)e;
         lds_set[variant][bits - 2] = true;

@@ -21,7 +21,7 @@ lcd_status fail(lcd_status st, const char *fmt, ...)
 
 static lcd_status check_shape(int N, int K, int bits)
 {
-    if (bits != 2 && bits != 3) return fail(LCD_ERR_BAD_BITS, "bits=%d: only 2 and 3 are supported", bits);
+    if (bits < 2 || bits > 4) return fail(LCD_ERR_BAD_BITS, "bits=%d: only 2, 3 and 4 are supported", bits);
     if (N <= 0 || K <= 0 || N % kTileRows != 0 || K % kTileCols != 0)
         return fail(LCD_ERR_BAD_SHAPE, "N=%d must be a positive multiple of %d and K=%d of %d", N, kTileRows, K, kTileCols);
     if ((long long)N * (long long)K * bits / 8 >= (1ll << 32)) return fail(LCD_ERR_BAD_SHAPE, "packed matrix must be smaller than 4 GiB");
@@ -47,10 +47,10 @@ GemmPlan plan_gemm(int M, int N, int K, int bits)
 }
 
 // ---- host packer: walks tiles and lanes, builds each lane's words -----------------------
-static void lane_words(const uint8_t *row64, int bits, uint32_t lo[4], uint32_t hi[2])
+static void lane_words(const uint8_t *row64, int bits, uint32_t lo[4], uint32_t hi[4])
 {
     lo[0] = lo[1] = lo[2] = lo[3] = 0;
-    hi[0] = hi[1] = 0;
+    hi[0] = hi[1] = hi[2] = hi[3] = 0;
     for (int w = 0; w < 64; ++w) {
         const uint32_t v = row64[w];
         lo[w >> 4] |= (v & 3u) << (2 * (w & 15));
@@ -59,6 +59,7 @@ static void lane_words(const uint8_t *row64, int bits, uint32_t lo[4], uint32_t 
             const int bit = 8 * ((e >> 2) + 2 * (e & 1)) + 2 * d + ((e & 3) >> 1);
             hi[a] |= ((v >> 2) & 1u) << bit;
         }
+        if (bits == 4) hi[w >> 4] |= ((v >> 2) & 3u) << (2 * (w & 15));
     }
 }
 
@@ -100,8 +101,8 @@ size_t lcd_packed_bytes(int N, int K, int bits)
 
 size_t lcd_lut_bytes(int N, int bits)
 {
-    if ((bits != 2 && bits != 3) || N <= 0 || N % kTileRows != 0) return 0;
-    return (size_t)N * (bits == 2 ? 24 : 48);
+    if (bits < 2 || bits > 4 || N <= 0 || N % kTileRows != 0) return 0;
+    return (size_t)N * (bits == 2 ? 24 : bits == 3 ? 48 : 32);   // 4 bits: the byte-split tables only
 }
 
 size_t lcd_workspace_bytes(int M, int N, int K, int bits)
@@ -131,10 +132,11 @@ lcd_status lcd_pack_indices_host(const uint8_t *idx, int N, int K, int bits, voi
             uint8_t *tile = out + ((size_t)t * kc + c) * tb;
             for (int l = 0; l < 64; ++l) {
                 const int q = l >> 4, i = l & 15;
-                uint32_t lo[4], hi[2];
+                uint32_t lo[4], hi[4];
                 lane_words(idx + (size_t)(t * kTileRows + i) * K + (size_t)c * kTileCols + q * kLaneCols, bits, lo, hi);
                 for (int d = 0; d < 4; ++d) put32(tile + 16 * l + 4 * d, lo[d]);
                 if (bits == 3) { put32(tile + 1024 + 8 * l, hi[0]); put32(tile + 1024 + 8 * l + 4, hi[1]); }
+                if (bits == 4) for (int d = 0; d < 4; ++d) put32(tile + 1024 + 16 * l + 4 * d, hi[d]);
             }
         }
     return LCD_OK;
@@ -163,6 +165,7 @@ lcd_status lcd_unpack_indices_host(const void *packed, int N, int K, int bits, u
                         const int bit = 8 * ((e >> 2) + 2 * (e & 1)) + 2 * d + ((e & 3) >> 1);
                         v |= ((hi[a] >> bit) & 1u) << 2;
                     }
+                    if (bits == 4) v |= ((get32(tile + 1024 + 16 * l + 4 * (w >> 4)) >> (2 * (w & 15))) & 3u) << 2;
                     row64[w] = (uint8_t)v;
                 }
             }
@@ -192,7 +195,7 @@ lcd_status lcd_unpack_indices(const void *packed, int N, int K, int bits, uint8_
 
 lcd_status lcd_build_lut(const uint16_t *codebook, int N, int bits, void *lut, size_t lut_bytes, void *stream)
 {
-    if (bits != 2 && bits != 3) return fail(LCD_ERR_BAD_BITS, "bits=%d: only 2 and 3 are supported", bits);
+    if (bits < 2 || bits > 4) return fail(LCD_ERR_BAD_BITS, "bits=%d: only 2, 3 and 4 are supported", bits);
     if (N <= 0 || N % kTileRows != 0) return fail(LCD_ERR_BAD_SHAPE, "N=%d must be a positive multiple of %d", N, kTileRows);
     if (lcd_status st = check_aligned(codebook, "codebook")) return st;
     if (lcd_status st = check_aligned(lut, "lut")) return st;
@@ -266,7 +269,7 @@ static lcd_status gemv_grouped(const lcd_gemv_problem *problems, const float *s_
         if (s_q && (!(s_q[i] > 0.0f) || !(s_q[i] < 3.0e38f)))
             return fail(LCD_ERR_BAD_SCALE, "s_q[%d]=%g must be positive and finite", i, (double)s_q[i]);
     }
-    if (M > 1 && workspace_bytes < codes) return fail(LCD_ERR_SIZE, "workspace_bytes=%zu < %zu", workspace_bytes, codes);
+    if (workspace_bytes < codes) return fail(LCD_ERR_SIZE, "workspace_bytes=%zu < %zu", workspace_bytes, codes);
     GroupItem items[kMaxGroup];
     for (int i = 0; i < count; ++i)
         items[i] = GroupItem{problems[i].packed, problems[i].lut, problems[i].x, problems[i].s, problems[i].y, problems[i].N, problems[i].K,

@@ -13,7 +13,7 @@ constexpr int kTileRows = 16;    // rows of the index matrix per tile
 constexpr int kTileCols = 256;   // columns per tile (one 16-byte load per lane of a wave)
 constexpr int kLaneCols = 64;    // columns one lane's 128-bit word covers
 
-inline size_t tile_bytes(int bits) { return bits == 2 ? 1024 : 1536; }
+inline size_t tile_bytes(int bits) { return (size_t)kTileRows * kTileCols * bits / 8; }   // 1024, 1536, 2048
 
 lcd_status fail(lcd_status st, const char *fmt, ...);
 

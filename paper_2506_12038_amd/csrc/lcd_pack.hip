@@ -20,7 +20,7 @@ __global__ void __launch_bounds__(256) pack_kernel(const uint8_t *__restrict__ i
     const long long t = tile / kc;
     const int q = l >> 4, i = l & 15;
     const uint4v *src = reinterpret_cast<const uint4v *>(idx + (size_t)(t * kTileRows + i) * K + (size_t)c * kTileCols + q * kLaneCols);
-    uint32_t lo[4] = {0, 0, 0, 0}, hi[2] = {0, 0};
+    uint32_t lo[4] = {0, 0, 0, 0}, hi[4] = {0, 0, 0, 0};
 #pragma unroll
     for (int d = 0; d < 4; ++d) {
         const uint4v v = src[d];  // 16 indices, one per byte
@@ -37,15 +37,20 @@ __global__ void __launch_bounds__(256) pack_kernel(const uint8_t *__restrict__ i
                     const int bit = 8 * ((e >> 2) + 2 * (e & 1)) + 2 * d + ((e & 3) >> 1);
                     hi[a] |= (val >> 2) << bit;
                 }
+                if (BITS == 4) hi[d] |= (val >> 2) << (2 * e16);
             }
         }
     }
-    uint8_t *tile_ptr = packed + (size_t)tile * (BITS == 2 ? 1024 : 1536);
+    uint8_t *tile_ptr = packed + (size_t)tile * (kTileRows * kTileCols * BITS / 8);
     uint4v o = {lo[0], lo[1], lo[2], lo[3]};
     *reinterpret_cast<uint4v *>(tile_ptr + 16 * l) = o;
     if (BITS == 3) {
         uint2v h = {hi[0], hi[1]};
         *reinterpret_cast<uint2v *>(tile_ptr + 1024 + 8 * l) = h;
+    }
+    if (BITS == 4) {
+        uint4v h = {hi[0], hi[1], hi[2], hi[3]};
+        *reinterpret_cast<uint4v *>(tile_ptr + 1024 + 16 * l) = h;
     }
 }
 
@@ -61,10 +66,12 @@ __global__ void __launch_bounds__(256) unpack_kernel(const uint8_t *__restrict__
     const int c = (int)(tile % kc);
     const long long t = tile / kc;
     const int q = l >> 4, i = l & 15;
-    const uint8_t *tile_ptr = packed + (size_t)tile * (BITS == 2 ? 1024 : 1536);
+    const uint8_t *tile_ptr = packed + (size_t)tile * (kTileRows * kTileCols * BITS / 8);
     const uint4v lo = *reinterpret_cast<const uint4v *>(tile_ptr + 16 * l);
     uint2v hi = {0, 0};
+    uint4v hi4 = {0, 0, 0, 0};
     if (BITS == 3) hi = *reinterpret_cast<const uint2v *>(tile_ptr + 1024 + 8 * l);
+    if (BITS == 4) hi4 = *reinterpret_cast<const uint4v *>(tile_ptr + 1024 + 16 * l);
     uint4v *dst = reinterpret_cast<uint4v *>(idx + (size_t)(t * kTileRows + i) * K + (size_t)c * kTileCols + q * kLaneCols);
 #pragma unroll
     for (int d = 0; d < 4; ++d) {
@@ -81,6 +88,7 @@ __global__ void __launch_bounds__(256) unpack_kernel(const uint8_t *__restrict__
                     const int bit = 8 * ((e >> 2) + 2 * (e & 1)) + 2 * d + ((e & 3) >> 1);
                     val |= ((hi[a] >> bit) & 1u) << 2;
                 }
+                if (BITS == 4) val |= ((hi4[d] >> (2 * e16)) & 3u) << 2;
                 word |= val << (8 * b);
             }
             out[j] = word;
@@ -96,6 +104,8 @@ __global__ void __launch_bounds__(256) unpack_kernel(const uint8_t *__restrict__
 // Section B (byte-split tables for v_perm_b32), starting at byte N*NC*4:
 //   2 bits: per row {low bytes of C[n][0..3], high bytes of C[n][0..3]}            (8 bytes)
 //   3 bits: per row {low 0..3, low 4..7, high 0..3, high 4..7}                      (16 bytes)
+// 4 bits: no section A (the single-token case runs on the register dequantiser too); per row
+//   {low bytes of C[n][0..15], high bytes of C[n][0..15]}                                      (32 bytes)
 template <int BITS>
 __global__ void __launch_bounds__(256) build_lut_kernel(const uint16_t *__restrict__ codebook, uint8_t *__restrict__ lut, int N)
 {
@@ -106,6 +116,18 @@ __global__ void __launch_bounds__(256) build_lut_kernel(const uint16_t *__restri
     uint16_t c[NCENT];
 #pragma unroll
     for (int j = 0; j < NCENT; ++j) c[j] = codebook[(size_t)n * NCENT + j];
+    if (BITS == 4) {
+        uint32_t w[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            w[j >> 2] |= (uint32_t)(c[j] & 255) << (8 * (j & 3));
+            w[4 + (j >> 2)] |= (uint32_t)(c[j] >> 8) << (8 * (j & 3));
+        }
+        uint4v *dst = reinterpret_cast<uint4v *>(lut) + 2 * (size_t)n;
+        dst[0] = uint4v{w[0], w[1], w[2], w[3]};
+        dst[1] = uint4v{w[4], w[5], w[6], w[7]};
+        return;
+    }
     float *secA = reinterpret_cast<float *>(lut);
     const size_t baseA = (size_t)(n >> 2) * NC * 4 + (n & 3);
     if (BITS == 2) {
@@ -201,7 +223,8 @@ int launch_pack(const uint8_t *idx, int N, int K, int bits, void *packed, void *
     const long long total = (long long)(N / kTileRows) * (K / kTileCols) * 64;
     const dim3 grid((unsigned)((total + 255) / 256)), block(256);
     if (bits == 2) hipLaunchKernelGGL(pack_kernel<2>, grid, block, 0, (hipStream_t)stream, idx, (uint8_t *)packed, N, K, total);
-    else hipLaunchKernelGGL(pack_kernel<3>, grid, block, 0, (hipStream_t)stream, idx, (uint8_t *)packed, N, K, total);
+    else if (bits == 3) hipLaunchKernelGGL(pack_kernel<3>, grid, block, 0, (hipStream_t)stream, idx, (uint8_t *)packed, N, K, total);
+    else hipLaunchKernelGGL(pack_kernel<4>, grid, block, 0, (hipStream_t)stream, idx, (uint8_t *)packed, N, K, total);
     return (int)hipGetLastError();
 }
 
@@ -210,7 +233,8 @@ int launch_unpack(const void *packed, int N, int K, int bits, uint8_t *idx, void
     const long long total = (long long)(N / kTileRows) * (K / kTileCols) * 64;
     const dim3 grid((unsigned)((total + 255) / 256)), block(256);
     if (bits == 2) hipLaunchKernelGGL(unpack_kernel<2>, grid, block, 0, (hipStream_t)stream, (const uint8_t *)packed, idx, N, K, total);
-    else hipLaunchKernelGGL(unpack_kernel<3>, grid, block, 0, (hipStream_t)stream, (const uint8_t *)packed, idx, N, K, total);
+    else if (bits == 3) hipLaunchKernelGGL(unpack_kernel<3>, grid, block, 0, (hipStream_t)stream, (const uint8_t *)packed, idx, N, K, total);
+    else hipLaunchKernelGGL(unpack_kernel<4>, grid, block, 0, (hipStream_t)stream, (const uint8_t *)packed, idx, N, K, total);
     return (int)hipGetLastError();
 }
 
@@ -218,7 +242,8 @@ int launch_build_lut(const uint16_t *codebook, int N, int bits, void *lut, void 
 {
     const dim3 grid((unsigned)((N + 255) / 256)), block(256);
     if (bits == 2) hipLaunchKernelGGL(build_lut_kernel<2>, grid, block, 0, (hipStream_t)stream, codebook, (uint8_t *)lut, N);
-    else hipLaunchKernelGGL(build_lut_kernel<3>, grid, block, 0, (hipStream_t)stream, codebook, (uint8_t *)lut, N);
+    else if (bits == 3) hipLaunchKernelGGL(build_lut_kernel<3>, grid, block, 0, (hipStream_t)stream, codebook, (uint8_t *)lut, N);
+    else hipLaunchKernelGGL(build_lut_kernel<4>, grid, block, 0, (hipStream_t)stream, codebook, (uint8_t *)lut, N);
     return (int)hipGetLastError();
 }
 

@@ -10,7 +10,7 @@ from gpu_common import TOL, check_layer, run_hip, to_dev
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("bits", [2, 3])
+@pytest.mark.parametrize("bits", [2, 3, 4])
 @pytest.mark.parametrize("M", [2, 3, 8, 16])
 @pytest.mark.parametrize("shape", [(16, 256), (48, 768), (80, 2304), (64, 11008), (32, 28672), (96, 5120), (48, 6656), (32, 13824), (8208, 1280)])
 def test_gemv_batched_small(bits, M, shape):
@@ -19,7 +19,7 @@ def test_gemv_batched_small(bits, M, shape):
     check_layer(layer, bits, "gemv")
 
 
-@pytest.mark.parametrize("bits", [2, 3])
+@pytest.mark.parametrize("bits", [2, 3, 4])
 @pytest.mark.parametrize("M", [1, 5, 64, 130, 257])
 @pytest.mark.parametrize("shape", [(16, 256), (48, 768), (272, 1024), (1040, 512)])
 def test_gemm_small(bits, M, shape):
@@ -28,7 +28,7 @@ def test_gemm_small(bits, M, shape):
     check_layer(layer, bits, "gemm")
 
 
-@pytest.mark.parametrize("bits", [2, 3])
+@pytest.mark.parametrize("bits", [2, 3, 4])
 @pytest.mark.parametrize("entry", ["gemv", "gemm"])
 def test_batched_one_hot_rows_are_exact(bits, entry):
     # token m has x = e_{k_m}, s = 1: y[m][n] = C[n][idx[n][k_m]] exactly
@@ -95,3 +95,17 @@ def test_config4_70b_mlp_full_size(M):
             continue
         seen.add((spec.N, spec.K))
         _sampled_check(4, mid, spec, config.bits, M, "gemv", rows=128, toks=8)
+
+
+@pytest.mark.parametrize("bits,ncent", [(3, 5), (3, 6), (4, 10), (4, 13)])
+@pytest.mark.parametrize("M,entry", [(1, "gemv"), (6, "gemv"), (70, "gemm")])
+def test_codebooks_with_fewer_centroids_than_the_container_holds(bits, ncent, M, entry):
+    # centroid counts that are no power of two (the paper's per-layer counts: 5, 6, 10, ...) live in the
+    # next container; the codes above the count are never used and their table entries are zero
+    N, K = 80, 1280
+    layer = synth.make_layer(1, 3, N, K, bits, M, seed_offset=bits + ncent + M)
+    layer["idx"] = (layer["idx"] % ncent).astype(np.uint8)
+    layer["codebook"] = layer["codebook"].copy()
+    layer["codebook"][:, ncent:] = 0
+    assert int(layer["idx"].max()) == ncent - 1
+    check_layer(layer, bits, entry)

@@ -10,7 +10,7 @@ from gpu_common import TOL, check_layer, run_hip, to_dev
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("bits", [2, 3])
+@pytest.mark.parametrize("bits", [2, 3, 4])
 @pytest.mark.parametrize("shape", [(16, 256), (48, 768), (80, 2304), (256, 4096), (64, 11008), (96, 8192), (32, 28672), (16, 69632), (1088, 4352), (139264, 512), (64, 5120), (48, 13824)])
 def test_gemv_m1_small(bits, shape):
     N, K = shape
@@ -19,7 +19,7 @@ def test_gemv_m1_small(bits, shape):
     print(shape, bits, err)
 
 
-@pytest.mark.parametrize("bits", [2, 3])
+@pytest.mark.parametrize("bits", [2, 3, 4])
 def test_gemv_m1_one_hot_reads_single_centroids(bits):
     # x = e_k, s = 1: y[n] must be exactly C[n][idx[n,k]] -- sweeps every bit position of a tile
     import torch
@@ -56,7 +56,7 @@ def test_gemv_is_deterministic():
     assert np.array_equal(y1.view(np.uint16), y2.view(np.uint16))
 
 
-@pytest.mark.parametrize("bits,M", [(3, 1), (2, 1), (2, 4)])
+@pytest.mark.parametrize("bits,M", [(3, 1), (2, 1), (2, 4), (4, 1), (4, 7)])
 def test_grouped_launch_matches_oracle_and_single_calls(bits, M):
     # a mixed group: different N and K per layer, one launch
     import torch
@@ -139,7 +139,7 @@ def test_grouped_launch_replayed_from_a_hip_graph(bits, M):
             assert torch.equal(p[4], ref), rep
 
 
-@pytest.mark.parametrize("bits", [2, 3])
+@pytest.mark.parametrize("bits", [2, 3, 4])
 @pytest.mark.parametrize("M", [1, 5, 16])
 @pytest.mark.parametrize("shape", [(64, 1024), (48, 11008)])
 def test_gemv_q8_matches_the_quantised_oracle(bits, M, shape):
@@ -179,7 +179,7 @@ def test_gemv_q8_codes_are_bit_exact(M):
     assert np.array_equal(y.astype(np.float64) / s_q, q.astype(np.float64))
 
 
-@pytest.mark.parametrize("bits,M", [(3, 1), (2, 1), (2, 8)])
+@pytest.mark.parametrize("bits,M", [(3, 1), (2, 1), (2, 8), (4, 1), (4, 5)])
 def test_grouped_q8_matches_oracle_and_single_calls(bits, M):
     # one launch over layers with different shapes and different quantisation steps
     import torch
@@ -207,7 +207,7 @@ def test_grouped_q8_matches_oracle_and_single_calls(bits, M):
         assert torch.equal(y, single)
 
 
-@pytest.mark.parametrize("bits,M", [(2, 3), (3, 16)])
+@pytest.mark.parametrize("bits,M", [(2, 3), (3, 16), (4, 1), (4, 9)])
 def test_grouped_wide_and_narrow_layers(bits, M):
     # a group with one layer wide enough for the activations to be smoothed ahead of the product:
     # then all its layers take that route, while the single calls of the narrow ones smooth inside

@@ -9,7 +9,7 @@ from gpu_common import to_dev
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("bits", [2, 3])
+@pytest.mark.parametrize("bits", [2, 3, 4])
 @pytest.mark.parametrize("shape", [(16, 256), (48, 768), (4096, 4096), (11008, 4096), (4096, 11008)])
 def test_device_pack_is_bit_exact(bits, shape):
     import torch
@@ -31,7 +31,7 @@ def test_device_pack_is_bit_exact(bits, shape):
 def test_device_pack_masks_out_of_range_indices():
     import torch
     idx = np.random.default_rng(1).integers(0, 256, size=(16, 256), dtype=np.uint8)
-    for bits in (2, 3):
+    for bits in (2, 3, 4):
         packed = lcd.lcd_pack_indices(to_dev(idx), bits)
         torch.cuda.synchronize()
         assert np.array_equal(packed.cpu().numpy(), lcd.lcd_pack_indices_host(idx & ((1 << bits) - 1), bits))

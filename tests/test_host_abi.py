@@ -33,16 +33,17 @@ def test_size_functions():
     assert lcd.lcd_packed_bytes(4096, 4096, 3) == 6291456
     assert lcd.lcd_packed_bytes(11008, 4096, 3) == 16908288
     assert lcd.lcd_packed_bytes(28672, 8192, 2) == 58720256
-    assert lcd.lcd_packed_bytes(4096, 4096, 4) == 0
+    assert lcd.lcd_packed_bytes(4096, 4096, 4) == 8388608
+    assert lcd.lcd_packed_bytes(4096, 4096, 5) == 0 and lcd.lcd_packed_bytes(4096, 4096, 1) == 0
     assert lcd.lcd_packed_bytes(4100, 4096, 2) == 0 and lcd.lcd_packed_bytes(4096, 4100, 2) == 0
-    assert lcd.lcd_lut_bytes(4096, 2) == 4096 * 24 and lcd.lcd_lut_bytes(4096, 3) == 4096 * 48
+    assert lcd.lcd_lut_bytes(4096, 2) == 4096 * 24 and lcd.lcd_lut_bytes(4096, 3) == 4096 * 48 and lcd.lcd_lut_bytes(4096, 4) == 4096 * 32
     for M, N, K, bits in [(1, 4096, 4096, 2), (16, 11008, 4096, 2), (2048, 4096, 11008, 3), (8, 8192, 28672, 2)]:
         w = lcd.lcd_workspace_bytes(M, N, K, bits)
         assert w >= 256 and w % 256 == 0
     assert lcd.lcd_workspace_bytes(0, 4096, 4096, 2) == 0
 
 
-@pytest.mark.parametrize("bits", [2, 3])
+@pytest.mark.parametrize("bits", [2, 3, 4])
 @pytest.mark.parametrize("shape", [(16, 256), (48, 768), (32, 1024)])
 def test_host_packer_matches_layout_definition(bits, shape):
     N, K = shape
@@ -78,6 +79,18 @@ def test_golden_bytes_hand_worked():
     e3[0] = 0x03; e3[17] = 0x08
     e3[1024] = 0x01; e3[1024 + 8 + 3] = 0x01; e3[1024 + 144 + 4 + 2] = 0x08
     assert np.array_equal(p3, e3)
+    # 4-bit: the low fields as before, index bits 3:2 in the same arrangement 1024 bytes further on.
+    #  (n=0,k=0)=15    -> low byte 0 = 0x03, high field: bits [1:0] of tile byte 1024      -> 0x03
+    #  (n=1,k=5)=9     -> low = 1: byte 17 = 0x04; high = 2: bits [11:10] at byte 1024+16  -> byte 1041 = 0x08
+    #  (n=2,k=64)=4    -> low = 0; high = 1: lane 18, word at byte 1024+288                -> byte 1312 = 0x01
+    #  (n=15,k=255)=14 -> low = 2: byte 1023 = 0x80; high = 3: byte 2047 = 0xC0
+    idx4 = np.zeros((16, 256), dtype=np.uint8)
+    idx4[0, 0] = 15; idx4[1, 5] = 9; idx4[2, 64] = 4; idx4[15, 255] = 14
+    p4 = lcd.lcd_pack_indices_host(idx4, 4)
+    e4 = np.zeros(2048, dtype=np.uint8)
+    e4[0] = 0x03; e4[17] = 0x04; e4[1023] = 0x80
+    e4[1024] = 0x03; e4[1041] = 0x08; e4[1312] = 0x01; e4[2047] = 0xC0
+    assert np.array_equal(p4, e4)
 
 
 def test_host_packer_rejects_out_of_range_and_bad_shapes():
@@ -109,7 +122,7 @@ def test_device_entry_points_validate_before_launch():
     assert st(lib.lcd_pack_indices(odd, 16, 256, 2, a, 1024, None)) == b"LCD_ERR_ALIGN"
     assert st(lib.lcd_pack_indices(a, 16, 256, 2, a, 1000, None)) == b"LCD_ERR_SIZE"
     assert st(lib.lcd_unpack_indices(a, 16, 250, 2, a, None)) == b"LCD_ERR_BAD_SHAPE"
-    assert st(lib.lcd_build_lut(a, 16, 4, a, 4096, None)) == b"LCD_ERR_BAD_BITS"
+    assert st(lib.lcd_build_lut(a, 16, 5, a, 4096, None)) == b"LCD_ERR_BAD_BITS"
     assert st(lib.lcd_build_lut(a, 16, 2, a, 10, None)) == b"LCD_ERR_SIZE"
     big = 1 << 30
     assert st(lib.lcd_lut_gemv(a, a, a, a, a, 17, 16, 256, 2, a, big, None)) == b"LCD_ERR_BAD_M"

@@ -48,7 +48,7 @@ def small_case(bits, M, N, K, seed):
     return codebook, idx, x, s
 
 
-@pytest.mark.parametrize("bits", [2, 3])
+@pytest.mark.parametrize("bits", [2, 3, 4])
 @pytest.mark.parametrize("shape", [(1, 4, 16), (3, 8, 64), (2, 5, 37), (4, 4, 24)])   # the last one square in (M, N): catches a transposed output
 def test_exact_rational_brute_force(bits, shape):
     M, N, K = shape
@@ -66,7 +66,7 @@ def test_exact_rational_brute_force(bits, shape):
             assert abs(Fraction(Yb[m, n]) - exact) <= tol
 
 
-@pytest.mark.parametrize("bits", [2, 3])
+@pytest.mark.parametrize("bits", [2, 3, 4])
 def test_bucket_sum_identity(bits):
     L = synth.make_layer(0, 0, 96, 512, bits, 3)
     Y = oracle.lut_matmul(L["codebook"], L["idx"], L["x"], L["s"], bits)
@@ -82,7 +82,7 @@ def test_bucket_sum_identity(bits):
     assert np.all(np.abs(Y - Yn) <= scale * 1e-13)
 
 
-@pytest.mark.parametrize("bits", [2, 3])
+@pytest.mark.parametrize("bits", [2, 3, 4])
 def test_codebook_permutation_invariance(bits):
     codebook, idx, x, s = small_case(bits, 2, 24, 128, 7)
     rng = np.random.default_rng(8)
@@ -99,7 +99,7 @@ def test_codebook_permutation_invariance(bits):
     assert np.array_equal(Y1, Y2)  # bit-identical: What is identical and the k order is fixed
 
 
-@pytest.mark.parametrize("bits", [2, 3])
+@pytest.mark.parametrize("bits", [2, 3, 4])
 def test_one_hot_probes_read_single_columns(bits):
     N, K = 12, 40
     codebook, idx, _, _ = small_case(bits, 1, N, K, 21)
@@ -114,7 +114,7 @@ def test_one_hot_probes_read_single_columns(bits):
             assert np.array_equal(Y[0], expect)
 
 
-@pytest.mark.parametrize("bits", [2, 3])
+@pytest.mark.parametrize("bits", [2, 3, 4])
 def test_constant_index(bits):
     codebook, idx, x, s = small_case(bits, 2, 9, 50, 33)
     for c in range(1 << bits):
@@ -148,7 +148,7 @@ def test_uniform_grid_reduces_to_integer_matmul():
     assert np.array_equal(Y2, expect)
 
 
-@pytest.mark.parametrize("bits", [2, 3])
+@pytest.mark.parametrize("bits", [2, 3, 4])
 def test_shared_codebook_matches_numpy_matmul(bits):
     L = synth.make_layer(1, 0, 64, 256, bits, 5, variant="A")
     Y = oracle.lut_matmul(L["codebook"], L["idx"], L["x"], L["s"], bits)
@@ -172,7 +172,7 @@ def test_scaling_and_linearity():
     assert np.allclose(Y12, Y, rtol=0, atol=1e-12)
 
 
-@pytest.mark.parametrize("bits", [2, 3])
+@pytest.mark.parametrize("bits", [2, 3, 4])
 def test_row_dependence(bits):
     codebook, idx, x, s = small_case(bits, 2, 10, 48, 91)
     Y = oracle.lut_matmul(codebook, idx, x, s, bits)
