@@ -184,6 +184,14 @@ size_t lcd_workspace_bytes_grouped(const lcd_gemv_problem *problems /*HOST*/, in
 lcd_status lcd_lut_gemv_grouped(const lcd_gemv_problem *problems /*HOST*/, int count, int M, int bits,
                                 void *workspace, size_t workspace_bytes, void *stream);
 
+/* Layers of different index widths in one call (the paper assigns a centroid count per layer,
+ * Sec. 5: 5, 6, 10, ... centroids): bits is a HOST array of `count` widths, each 2, 3 or 4.
+ * All layers are validated first; then the layers of each width that occurs go out as one
+ * launch, in the order 2, 3, 4, on `stream`.  Workspace as for lcd_lut_gemv_grouped (its size
+ * does not depend on the width). */
+lcd_status lcd_lut_gemv_grouped_mixed(const lcd_gemv_problem *problems /*HOST*/, const int *bits /*HOST*/, int count,
+                                      int M, void *workspace, size_t workspace_bytes, void *stream);
+
 /* The same with the input transformation of lcd_lut_gemv_q8 in front of every layer:
  * s_q is a HOST array of `count` activation quantisation steps, one per layer. */
 lcd_status lcd_lut_gemv_q8_grouped(const lcd_gemv_problem *problems /*HOST*/, const float *s_q /*HOST*/, int count,

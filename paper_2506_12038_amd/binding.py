@@ -20,7 +20,7 @@ EXPORTS = (
     "lcd_packed_bytes", "lcd_lut_bytes", "lcd_workspace_bytes",
     "lcd_pack_indices", "lcd_unpack_indices", "lcd_pack_indices_host", "lcd_unpack_indices_host",
     "lcd_build_lut", "lcd_lut_gemv", "lcd_lut_gemm", "lcd_lut_gemv_q8",
-    "lcd_workspace_bytes_grouped", "lcd_lut_gemv_grouped", "lcd_lut_gemv_q8_grouped",
+    "lcd_workspace_bytes_grouped", "lcd_lut_gemv_grouped", "lcd_lut_gemv_q8_grouped", "lcd_lut_gemv_grouped_mixed",
 )
 
 
@@ -80,6 +80,8 @@ def load_library():
     lib.lcd_lut_gemv_grouped.argtypes = [ctypes.POINTER(_Problem), ci, ci, ci, vp, sz, vp]
     lib.lcd_lut_gemv_q8_grouped.restype = ci
     lib.lcd_lut_gemv_q8_grouped.argtypes = [ctypes.POINTER(_Problem), ctypes.POINTER(ctypes.c_float), ci, ci, ci, vp, sz, vp]
+    lib.lcd_lut_gemv_grouped_mixed.restype = ci
+    lib.lcd_lut_gemv_grouped_mixed.argtypes = [ctypes.POINTER(_Problem), ctypes.POINTER(ci), ci, ci, vp, sz, vp]
     _lib = lib
     return lib
 
@@ -230,14 +232,24 @@ class GemvGroup:
     """Marshalled argument block of lcd_lut_gemv_grouped: build once per layer set, call many times.
 
     problems: sequence of (packed, lut, x, s, y, N) with CUDA tensors as in lcd_lut_gemv.
+    bits: one index width for all layers, or a sequence with one width per layer
+          (lcd_lut_gemv_grouped_mixed).
     s_q: optional sequence of per-layer activation quantisation steps (lcd_lut_gemv_q8_grouped).
     """
 
     def __init__(self, problems, bits: int, workspace=None, s_q=None):
         import torch
         lib = load_library()
-        self.bits = bits
         self.count = len(problems)
+        self._bits_arr = None
+        if not isinstance(bits, int):
+            if len(bits) != self.count:
+                raise ValueError("one index width per problem")
+            if s_q is not None:
+                raise ValueError("mixed index widths and quantised activations are separate entry points")
+            self._bits_arr = (ctypes.c_int * self.count)(*[int(b) for b in bits])
+            bits = int(bits[0])     # the workspace size does not depend on the width
+        self.bits = bits
         self._keep = list(problems)
         M = problems[0][2].shape[0]
         self.M = M
@@ -263,7 +275,10 @@ class GemvGroup:
     def __call__(self, stream=None):
         import torch
         ws = _dev(self.workspace, torch.uint8, "workspace")
-        if self._s_q is None:
+        if self._bits_arr is not None:
+            _check(load_library().lcd_lut_gemv_grouped_mixed(self._arr, self._bits_arr, self.count, self.M, ws,
+                                                             self.workspace.numel(), _stream(stream)))
+        elif self._s_q is None:
             _check(load_library().lcd_lut_gemv_grouped(self._arr, self.count, self.M, self.bits, ws, self.workspace.numel(),
                                                        _stream(stream)))
         else:

@@ -291,6 +291,34 @@ lcd_status lcd_lut_gemv_q8_grouped(const lcd_gemv_problem *problems, const float
     return gemv_grouped(problems, s_q, count, M, bits, workspace, workspace_bytes, stream);
 }
 
+lcd_status lcd_lut_gemv_grouped_mixed(const lcd_gemv_problem *problems, const int *bits, int count, int M,
+                                      void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!problems) return fail(LCD_ERR_NULL, "problems is NULL");
+    if (!bits) return fail(LCD_ERR_NULL, "bits is NULL");
+    if (count < 1 || count > kMaxGroup) return fail(LCD_ERR_SIZE, "count=%d must be in 1..%d", count, kMaxGroup);
+    for (int i = 0; i < count; ++i)
+        if (bits[i] < 2 || bits[i] > 4) return fail(LCD_ERR_BAD_BITS, "bits[%d]=%d: only 2, 3 and 4 are supported", i, bits[i]);
+    // validate every layer before the first launch, then one launch per index width that occurs
+    for (int pass = 0; pass < 2; ++pass)
+        for (int b = 2; b <= 4; ++b) {
+            lcd_gemv_problem sub[kMaxGroup];
+            int n = 0;
+            for (int i = 0; i < count; ++i)
+                if (bits[i] == b) sub[n++] = problems[i];
+            if (n == 0) continue;
+            if (pass == 0) {
+                if (M > 16) return fail(LCD_ERR_BAD_M, "grouped gemv: M=%d > 16", M);
+                for (int i = 0; i < n; ++i)
+                    if (lcd_status st = check_product(sub[i].packed, sub[i].lut, sub[i].x, sub[i].s, sub[i].y, M, sub[i].N, sub[i].K, b,
+                                                      workspace, workspace_bytes)) return st;
+            } else if (lcd_status st = gemv_grouped(sub, nullptr, n, M, b, workspace, workspace_bytes, stream)) {
+                return st;
+            }
+        }
+    return LCD_OK;
+}
+
 lcd_status lcd_lut_gemm(const void *packed, const void *lut, const uint16_t *x, const float *s, uint16_t *y,
                         int M, int N, int K, int bits, void *workspace, size_t workspace_bytes, void *stream)
 {

@@ -230,3 +230,28 @@ def test_grouped_wide_and_narrow_layers(bits, M):
         Y = oracle.lut_matmul(layer["codebook"], layer["idx"], layer["x"], layer["s"], bits)
         assert oracle.parity_errors(y.cpu().numpy(), Y)["max_rel_floored"] <= TOL
         assert torch.equal(y, single)
+
+
+@pytest.mark.parametrize("M", [1, 6])
+def test_grouped_layers_of_mixed_index_widths(M):
+    # per-layer centroid counts: 4, 6 (3-bit container), 10 (4-bit container), 8, 16 in one call
+    import torch
+    from paper_2506_12038_amd.binding import GemvGroup
+    specs = [(64, 1024, 2, 4), (208, 512, 3, 6), (48, 2816, 4, 10), (96, 1280, 3, 8), (32, 768, 4, 16)]
+    problems, layers = [], []
+    for i, (N, K, bits, ncent) in enumerate(specs):
+        layer = synth.make_layer(1, i, N, K, bits, M, seed_offset=13 * i + M)
+        layer["idx"] = (layer["idx"] % ncent).astype(np.uint8)
+        layer["codebook"] = layer["codebook"].copy()
+        layer["codebook"][:, ncent:] = 0
+        packed = lcd.lcd_pack_indices(to_dev(layer["idx"]), bits)
+        lut = lcd.lcd_build_lut(to_dev(layer["codebook"]), bits)
+        y = torch.full((M, N), float("nan"), dtype=torch.float16, device="cuda")
+        problems.append((packed, lut, to_dev(layer["x"]), to_dev(layer["s"]), y, N))
+        layers.append((layer, bits))
+    GemvGroup(problems, [b for _, _, b, _ in specs])()
+    torch.cuda.synchronize()
+    for (packed, lut, x, s, y, N), (layer, bits) in zip(problems, layers):
+        Y = oracle.lut_matmul(layer["codebook"], layer["idx"], layer["x"], layer["s"], bits)
+        assert oracle.parity_errors(y.cpu().numpy(), Y)["max_rel_floored"] <= TOL
+        assert torch.equal(y, lcd.lcd_lut_gemv(packed, lut, x, s, N, bits))

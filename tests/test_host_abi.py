@@ -170,3 +170,13 @@ def test_grouped_entry_point_validates_on_host():
     need = lib.lcd_workspace_bytes_grouped(arr, 2, 16, 2)
     assert need >= 16 * (256 + 512) * 2
     assert st(lib.lcd_lut_gemv_q8_grouped(arr, sq, 2, 16, 2, ctypes.c_void_p(a), 16 * 512 * 2, None)) == b"LCD_ERR_SIZE"
+    # mixed index widths: a host array of widths, validated like everything else
+    widths = (ctypes.c_int * 2)(2, 5)
+    assert st(lib.lcd_lut_gemv_grouped_mixed(arr, None, 2, 1, ctypes.c_void_p(a), big, None)) == b"LCD_ERR_NULL"
+    assert st(lib.lcd_lut_gemv_grouped_mixed(arr, widths, 2, 1, ctypes.c_void_p(a), big, None)) == b"LCD_ERR_BAD_BITS"
+    widths[1] = 4
+    assert st(lib.lcd_lut_gemv_grouped_mixed(arr, widths, 2, 17, ctypes.c_void_p(a), big, None)) == b"LCD_ERR_BAD_M"
+    arr[0].K = 100
+    assert st(lib.lcd_lut_gemv_grouped_mixed(arr, widths, 2, 1, ctypes.c_void_p(a), big, None)) == b"LCD_ERR_BAD_SHAPE"
+    arr[0].K = 256
+    assert st(lib.lcd_lut_gemv_grouped_mixed(arr, widths, 2, 4, ctypes.c_void_p(a), 256, None)) == b"LCD_ERR_SIZE"
