@@ -15,8 +15,10 @@ from .lcd_oracle import (
     num_threads,
 )
 from .metrics import parity_errors
+from .cluster_oracle import assign_nearest, cluster_counts, merge_closest
 
 __all__ = [
     "build_oracle", "half_to_double", "dequant", "smooth", "lut_matmul", "bucket_matmul",
     "input_transform", "quantised_lut_matmul", "num_threads", "parity_errors",
+    "assign_nearest", "cluster_counts", "merge_closest",
 ]

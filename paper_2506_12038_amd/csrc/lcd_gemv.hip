@@ -380,6 +380,9 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const BucketBa
         LCD_STAMP(4);
 #ifdef LCD_TRACE
         if (lane == 0 && batch.trace && wave < 4) batch.trace[blockIdx.x * 16 + 8 + wave] = __builtin_amdgcn_s_memrealtime();
+#ifdef LCD_TRACE_WAVES
+        if (lane == 0 && batch.trace && wave >= 4) batch.trace[blockIdx.x * 16 + 8 + wave] = __builtin_amdgcn_s_memrealtime();
+#endif
 #endif
         __syncthreads();
         LCD_STAMP(5);
