@@ -42,6 +42,7 @@ def parse_args():
     ap.add_argument("--per-layer", action="store_true", help="one lcd_lut_gemv call per matrix instead of one grouped call per step")
     ap.add_argument("--bits", type=int, default=None, choices=[2, 3, 4], help="override the config's index width (4: the 16-centroid container)")
     ap.add_argument("--act-int8", action="store_true", help="decode configs: INT8 activation codes (input transformation of Sec. 4.1) instead of fp16 x/s")
+    ap.add_argument("--offline", action="store_true", help="time the offline kernels (assign, counts, merge, pack, table build) on the config's largest matrix instead of the hot path")
     ap.add_argument("--eager", action="store_true", help="launch every step from Python instead of replaying a HIP graph")
     return ap.parse_args()
 
@@ -211,6 +212,55 @@ def measured_traffic(kernel, cfg_index):
     return None
 
 
+def bench_offline(cfg, steps, warmup):
+    """Offline kernels on the largest matrix of the config: HIP-event time per call and the rate in
+    algorithmic bytes (what the kernel must read and write once).  One JSON line."""
+    import numpy as np
+    import torch
+    import paper_2506_12038_amd as lcd
+
+    spec = max((s for _, s in cfg.matrices()), key=lambda s: s.N * s.K)
+    N, K, bits = spec.N, spec.K, cfg.bits
+    ncent = 1 << bits
+    g = torch.Generator(device="cuda"); g.manual_seed(1)
+    w = (torch.randn((N, K), device="cuda", generator=g) * 0.02).to(torch.float16)
+    base = np.sort((np.random.default_rng(2).standard_normal(ncent) * 0.02).astype(np.float16))
+    while len(np.unique(base)) < ncent:
+        base = np.sort((np.random.default_rng(int(base.view(np.uint16).sum())).standard_normal(ncent) * 0.02).astype(np.float16))
+    cb = torch.from_numpy(np.tile(base[None, :], (N, 1))).cuda()
+    idx = lcd.lcd_assign_indices(w, cb, ncent, bits)
+    counts = lcd.lcd_cluster_counts(idx, bits)
+    packed = lcd.lcd_pack_indices(idx, bits)
+    stream = torch.cuda.current_stream()
+    weights = N * K
+
+    def timed(fn):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(steps):
+            fn()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / steps   # us
+
+    idx_out = torch.empty_like(idx)
+    rows = {
+        "assign_kernel": (timed(lambda: lcd.lcd_assign_indices(w, cb, ncent, bits)), 3 * weights),
+        "counts_kernel": (timed(lambda: lcd.lcd_cluster_counts(idx, bits)), weights),
+        "merge_kernel+remap_kernel": (timed(lambda: lcd.lcd_merge_closest(cb, counts, idx, ncent, bits, idx_out=idx_out)), 2 * weights),
+        "pack_kernel": (timed(lambda: lcd.lcd_pack_indices(idx, bits, out=packed)), weights + weights * bits // 8),
+        "build_lut_kernel": (timed(lambda: lcd.lcd_build_lut(cb, bits)), N * ncent * 2 + lcd.lcd_lut_bytes(N, bits)),
+    }
+    out = {"metric": "offline_kernel_bandwidth_algorithmic_bytes", "unit": "GB/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+           "data": "synthetic", "config": {"workload": f"offline kernels on {N}x{K}, {bits}-bit ({cfg.label})"},
+           "kernels": {k: {"us": round(t, 2), "bytes": b, "GB/s": round(b / t / 1e3, 1), "frac_of_hbm_peak": round(b / t / 1e3 / HBM_PEAK_GBS, 3)}
+                       for k, (t, b) in rows.items()}}
+    print(json.dumps(out))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -225,6 +275,9 @@ def main():
     torch.cuda.set_device(0)
     cfg = resolve_config(args.config, args.bits)
     M = args.m if args.m is not None else cfg.Ms[0]
+    if args.offline:
+        bench_offline(cfg, min(args.steps, 50), min(args.warmup, 5))
+        return
     replicas = args.replicas or max(2, -(-600_000_000 // cfg.index_bytes()))
     if args.act_int8 and (M > 16 or args.per_layer):
         sys.exit("--act-int8 applies to the grouped decode path (M <= 16)")

@@ -197,6 +197,36 @@ lcd_status lcd_lut_gemv_grouped_mixed(const lcd_gemv_problem *problems /*HOST*/,
 lcd_status lcd_lut_gemv_q8_grouped(const lcd_gemv_problem *problems /*HOST*/, const float *s_q /*HOST*/, int count,
                                    int M, int bits, void *workspace, size_t workspace_bytes, void *stream);
 
+/* ---- clustering-side steps that need no calibration data (offline) ------------------------ *
+ *
+ * Codebooks here are per output row, fp16 [N][2^bits], of which the first `ncent` entries are in
+ * use and STRICTLY ASCENDING (the paper sorts the centroids, Sec. 3.3); the rest is ignored.
+ *
+ * lcd_assign_indices: idx[n][k] = the centroid of row n nearest to w[n][k] (w: DEVICE fp16 [N][K],
+ *   e.g. the smoothed weights).  This is the state the reclassification rule of Sec. 3.3 (Eq. 6)
+ *   maintains: a weight leaves its cluster once it crosses half the gap to a neighbouring
+ *   centroid.  A weight exactly half way stays with the lower centroid; NaN goes to centroid 0.
+ *   The decision is exact (no rounding anywhere).  Output as lcd_pack_indices takes it.
+ * lcd_cluster_counts: counts[n][i] = number of k with idx[n][k] == i, for i < 2^bits
+ *   (DEVICE uint32 [N][2^bits]; the cluster sizes of Sec. 3.5).  idx must be < 16.
+ * lcd_merge_closest: Sec. 3.5, Eq. 8, per row: the two closest centroids a, a+1 (smallest gap,
+ *   the lowest pair on equal gaps) are replaced by their mean weighted by their cluster sizes --
+ *   each centroid by its OWN count, as the text defines it (the printed formula has the counts
+ *   crossed), the plain mean if both clusters are empty -- computed in fp64 and rounded to fp16
+ *   (at most one fp16 step from the correctly rounded value).  codebook_out gets ncent-1 ascending
+ *   entries followed by zeros, merged[n] = a (DEVICE uint8 [N]), idx_out the re-numbered indices
+ *   (idx - 1 above a; idx_out may be idx itself; codebook_out must not be codebook).
+ * Errors: as above; ncent outside 1..2^bits (2..2^bits for the merge) is LCD_ERR_SIZE.
+ */
+lcd_status lcd_assign_indices(const uint16_t *w /*DEVICE*/, const uint16_t *codebook /*DEVICE*/, int ncent,
+                              int N, int K, int bits, uint8_t *idx /*DEVICE [N][K]*/, void *stream);
+lcd_status lcd_cluster_counts(const uint8_t *idx /*DEVICE*/, int N, int K, int bits,
+                              uint32_t *counts /*DEVICE [N][2^bits]*/, void *stream);
+lcd_status lcd_merge_closest(const uint16_t *codebook /*DEVICE*/, const uint32_t *counts /*DEVICE*/,
+                             const uint8_t *idx /*DEVICE*/, int ncent, int N, int K, int bits,
+                             uint16_t *codebook_out /*DEVICE*/, uint8_t *idx_out /*DEVICE*/,
+                             uint8_t *merged /*DEVICE [N]*/, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

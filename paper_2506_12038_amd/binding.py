@@ -21,6 +21,7 @@ EXPORTS = (
     "lcd_pack_indices", "lcd_unpack_indices", "lcd_pack_indices_host", "lcd_unpack_indices_host",
     "lcd_build_lut", "lcd_lut_gemv", "lcd_lut_gemm", "lcd_lut_gemv_q8",
     "lcd_workspace_bytes_grouped", "lcd_lut_gemv_grouped", "lcd_lut_gemv_q8_grouped", "lcd_lut_gemv_grouped_mixed",
+    "lcd_assign_indices", "lcd_cluster_counts", "lcd_merge_closest",
 )
 
 
@@ -82,6 +83,12 @@ def load_library():
     lib.lcd_lut_gemv_q8_grouped.argtypes = [ctypes.POINTER(_Problem), ctypes.POINTER(ctypes.c_float), ci, ci, ci, vp, sz, vp]
     lib.lcd_lut_gemv_grouped_mixed.restype = ci
     lib.lcd_lut_gemv_grouped_mixed.argtypes = [ctypes.POINTER(_Problem), ctypes.POINTER(ci), ci, ci, vp, sz, vp]
+    lib.lcd_assign_indices.restype = ci
+    lib.lcd_assign_indices.argtypes = [vp, vp, ci, ci, ci, ci, vp, vp]
+    lib.lcd_cluster_counts.restype = ci
+    lib.lcd_cluster_counts.argtypes = [vp, ci, ci, ci, vp, vp]
+    lib.lcd_merge_closest.restype = ci
+    lib.lcd_merge_closest.argtypes = [vp, vp, vp, ci, ci, ci, ci, vp, vp, vp, vp]
     _lib = lib
     return lib
 
@@ -293,3 +300,40 @@ def lcd_workspace_bytes_grouped(problems, bits: int) -> int:
 def lcd_lut_gemv_grouped(problems, bits: int, workspace=None, stream=None):
     """One launch for several layers: problems = [(packed, lut, x, s, y, N), ...]; writes every y."""
     GemvGroup(problems, bits, workspace)(stream)
+
+
+def lcd_assign_indices(w, codebook, ncent: int, bits: int, stream=None):
+    """w: CUDA float16 [N, K], codebook: CUDA float16 [N, 2**bits] -> CUDA uint8 [N, K] nearest-centroid indices."""
+    import torch
+    N, K = w.shape
+    if tuple(codebook.shape) != (N, 1 << bits):
+        raise ValueError("codebook must be [N, 2**bits]")
+    idx = torch.empty((N, K), dtype=torch.uint8, device=w.device)
+    _check(load_library().lcd_assign_indices(_dev(w, torch.float16, "w"), _dev(codebook, torch.float16, "codebook"), ncent,
+                                             N, K, bits, _dev(idx, torch.uint8, "idx"), _stream(stream)))
+    return idx
+
+
+def lcd_cluster_counts(idx, bits: int, stream=None):
+    """idx: CUDA uint8 [N, K] -> CUDA int32 [N, 2**bits] cluster sizes (the bit patterns are uint32)."""
+    import torch
+    N, K = idx.shape
+    counts = torch.empty((N, 1 << bits), dtype=torch.int32, device=idx.device)
+    _check(load_library().lcd_cluster_counts(_dev(idx, torch.uint8, "idx"), N, K, bits, _dev(counts, torch.int32, "counts"),
+                                             _stream(stream)))
+    return counts
+
+
+def lcd_merge_closest(codebook, counts, idx, ncent: int, bits: int, idx_out=None, stream=None):
+    """Merge the two closest centroids of every row; returns (codebook_out, idx_out, merged)."""
+    import torch
+    N, K = idx.shape
+    cb_out = torch.empty_like(codebook)
+    if idx_out is None:
+        idx_out = torch.empty_like(idx)
+    merged = torch.empty((N,), dtype=torch.uint8, device=idx.device)
+    _check(load_library().lcd_merge_closest(_dev(codebook, torch.float16, "codebook"), _dev(counts, torch.int32, "counts"),
+                                            _dev(idx, torch.uint8, "idx"), ncent, N, K, bits,
+                                            _dev(cb_out, torch.float16, "codebook_out"), _dev(idx_out, torch.uint8, "idx_out"),
+                                            _dev(merged, torch.uint8, "merged"), _stream(stream)))
+    return cb_out, idx_out, merged

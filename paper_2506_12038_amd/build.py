@@ -12,7 +12,7 @@ CSRC = PKG / "csrc"
 LIB = PKG / "liblcd.so"
 BUILD = ROOT / "_build"
 
-SOURCES = ["lcd_host.cpp", "lcd_pack.hip", "lcd_gemv.hip", "lcd_gemm.hip"]
+SOURCES = ["lcd_host.cpp", "lcd_pack.hip", "lcd_gemv.hip", "lcd_gemm.hip", "lcd_cluster.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

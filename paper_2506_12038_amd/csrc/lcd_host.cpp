@@ -329,4 +329,48 @@ lcd_status lcd_lut_gemm(const void *packed, const void *lut, const uint16_t *x, 
     return LCD_OK;
 }
 
+static lcd_status check_ncent(int ncent, int bits, int least)
+{
+    if (ncent < least || ncent > (1 << bits))
+        return fail(LCD_ERR_SIZE, "ncent=%d must be in %d..%d for bits=%d", ncent, least, 1 << bits, bits);
+    return LCD_OK;
+}
+
+lcd_status lcd_assign_indices(const uint16_t *w, const uint16_t *codebook, int ncent, int N, int K, int bits, uint8_t *idx, void *stream)
+{
+    if (lcd_status st = check_shape(N, K, bits)) return st;
+    if (lcd_status st = check_ncent(ncent, bits, 1)) return st;
+    if (lcd_status st = check_aligned(w, "w")) return st;
+    if (lcd_status st = check_aligned(codebook, "codebook")) return st;
+    if (lcd_status st = check_aligned(idx, "idx")) return st;
+    if (int e = launch_assign(w, codebook, ncent, N, K, bits, idx, stream)) return fail(LCD_ERR_HIP, "assign launch: %s", hip_error_name(e));
+    return LCD_OK;
+}
+
+lcd_status lcd_cluster_counts(const uint8_t *idx, int N, int K, int bits, uint32_t *counts, void *stream)
+{
+    if (lcd_status st = check_shape(N, K, bits)) return st;
+    if (lcd_status st = check_aligned(idx, "idx")) return st;
+    if (lcd_status st = check_aligned(counts, "counts")) return st;
+    if (int e = launch_counts(idx, N, K, bits, counts, stream)) return fail(LCD_ERR_HIP, "counts launch: %s", hip_error_name(e));
+    return LCD_OK;
+}
+
+lcd_status lcd_merge_closest(const uint16_t *codebook, const uint32_t *counts, const uint8_t *idx, int ncent, int N, int K, int bits,
+                             uint16_t *codebook_out, uint8_t *idx_out, uint8_t *merged, void *stream)
+{
+    if (lcd_status st = check_shape(N, K, bits)) return st;
+    if (lcd_status st = check_ncent(ncent, bits, 2)) return st;
+    if (lcd_status st = check_aligned(codebook, "codebook")) return st;
+    if (lcd_status st = check_aligned(counts, "counts")) return st;
+    if (lcd_status st = check_aligned(idx, "idx")) return st;
+    if (lcd_status st = check_aligned(codebook_out, "codebook_out")) return st;
+    if (lcd_status st = check_aligned(idx_out, "idx_out")) return st;
+    if (lcd_status st = check_aligned(merged, "merged")) return st;
+    if (codebook_out == codebook) return fail(LCD_ERR_SIZE, "codebook_out must not be the input codebook");
+    if (int e = launch_merge(codebook, counts, idx, ncent, N, K, bits, codebook_out, idx_out, merged, stream))
+        return fail(LCD_ERR_HIP, "merge launch: %s", hip_error_name(e));
+    return LCD_OK;
+}
+
 }  // extern "C"

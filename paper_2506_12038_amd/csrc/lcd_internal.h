@@ -42,6 +42,10 @@ int launch_gemv(const void *packed, const void *lut, const uint16_t *x, const fl
                 int M, int N, int K, int bits, float act_scale, void *workspace, void *stream);
 int launch_gemm(const void *packed, const void *lut, const uint16_t *x, const float *s, uint16_t *y,
                 int M, int N, int K, int bits, void *workspace, const GemmPlan &plan, void *stream);
+int launch_assign(const uint16_t *w, const uint16_t *codebook, int ncent, int N, int K, int bits, uint8_t *idx, void *stream);
+int launch_counts(const uint8_t *idx, int N, int K, int bits, uint32_t *counts, void *stream);
+int launch_merge(const uint16_t *cb_in, const uint32_t *counts, const uint8_t *idx_in, int ncent, int N, int K, int bits,
+                 uint16_t *cb_out, uint8_t *idx_out, uint8_t *merged, void *stream);
 const char *hip_error_name(int err);
 int launch_smooth(const uint16_t *x, const float *s, void *xs, int M, int Mpad, int K, void *stream);
 

@@ -180,3 +180,22 @@ def test_grouped_entry_point_validates_on_host():
     assert st(lib.lcd_lut_gemv_grouped_mixed(arr, widths, 2, 1, ctypes.c_void_p(a), big, None)) == b"LCD_ERR_BAD_SHAPE"
     arr[0].K = 256
     assert st(lib.lcd_lut_gemv_grouped_mixed(arr, widths, 2, 4, ctypes.c_void_p(a), 256, None)) == b"LCD_ERR_SIZE"
+
+
+def test_clustering_entry_points_validate_on_host():
+    lib = lcd.load_library()
+    a = ctypes.c_void_p(0x1000)
+    odd = ctypes.c_void_p(0x1008)
+    st = lambda code: lib.lcd_status_string(code)
+    assert st(lib.lcd_assign_indices(None, a, 4, 16, 256, 2, a, None)) == b"LCD_ERR_NULL"
+    assert st(lib.lcd_assign_indices(a, odd, 4, 16, 256, 2, a, None)) == b"LCD_ERR_ALIGN"
+    assert st(lib.lcd_assign_indices(a, a, 5, 16, 256, 2, a, None)) == b"LCD_ERR_SIZE"
+    assert st(lib.lcd_assign_indices(a, a, 0, 16, 256, 2, a, None)) == b"LCD_ERR_SIZE"
+    assert st(lib.lcd_assign_indices(a, a, 4, 16, 200, 2, a, None)) == b"LCD_ERR_BAD_SHAPE"
+    assert st(lib.lcd_assign_indices(a, a, 4, 16, 256, 6, a, None)) == b"LCD_ERR_BAD_BITS"
+    assert st(lib.lcd_cluster_counts(a, 16, 256, 3, None, None)) == b"LCD_ERR_NULL"
+    assert st(lib.lcd_cluster_counts(a, 17, 256, 3, a, None)) == b"LCD_ERR_BAD_SHAPE"
+    assert st(lib.lcd_merge_closest(a, a, a, 1, 16, 256, 3, ctypes.c_void_p(0x2000), a, a, None)) == b"LCD_ERR_SIZE"
+    assert st(lib.lcd_merge_closest(a, a, a, 9, 16, 256, 3, ctypes.c_void_p(0x2000), a, a, None)) == b"LCD_ERR_SIZE"
+    assert st(lib.lcd_merge_closest(a, a, a, 8, 16, 256, 3, a, a, a, None)) == b"LCD_ERR_SIZE"      # output over the input codebook
+    assert st(lib.lcd_merge_closest(a, a, a, 8, 16, 256, 3, ctypes.c_void_p(0x2000), a, None, None)) == b"LCD_ERR_NULL"
