@@ -1,5 +1,5 @@
-// Offline kernels: index packing / unpacking, table build, and the small helper kernels
-// (activation smoothing, split-K reduction).  Layout: see include/lcd.h.
+// Offline kernels: index packing / unpacking and table build, and the activation smoothing
+// kernel of the prefill path.  Layout: see include/lcd.h.
 #include <hip/hip_runtime.h>
 #include "lcd_internal.h"
 #include "lcd_device.h"
