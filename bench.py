@@ -287,6 +287,8 @@ def main():
     decode = M <= 16
     n_launch = 1 if (decode and not args.per_layer) else len(ls.mats)
     decode_kernel = "gemv_bucket_kernel" if (M == 1 and cfg.bits < 4) else "gemv_tokens_kernel"
+    # the tokens kernel is preceded by a small activation-transform kernel for INT8 codes and for wide layers
+    prepass = decode_kernel == "gemv_tokens_kernel" and not args.per_layer and (args.act_int8 or max(s.K for _, s in cfg.matrices()) >= 16384)
     if decode:
         metric, unit = "lut_gemv_effective_bandwidth_packed_index_bytes", "GB/s"
         value = ls.index_bytes / (wall_ms * 1e-3) / 1e9
@@ -295,7 +297,7 @@ def main():
             "frac": ls.index_bytes / (event_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
             "traffic": measured_traffic(decode_kernel, args.config) if (n_launch == 1 and args.bits is None and not args.act_int8) else None,
             "kernel": decode_kernel,
-            "launches_per_step": n_launch, "algorithmic_bytes_per_step": ls.index_bytes,
+            "launches_per_step": n_launch, "kernels_per_launch": 2 if prepass else 1, "algorithmic_bytes_per_step": ls.index_bytes,
             "avg_launch_us": event_ms * 1e3 / n_launch,
         }
     else:

@@ -64,9 +64,10 @@ const char *lcd_status_string(lcd_status st);
 size_t lcd_packed_bytes(int N, int K, int bits);
 /* Bytes of the per-layer table lcd_build_lut writes (24*N for 2 bits, 48*N for 3, 32*N for 4). */
 size_t lcd_lut_bytes(int N, int bits);
-/* Bytes of scratch the product entry points accept for this problem (a multiple of 256).  Only
- * lcd_lut_gemm uses it (smoothed activations in matrix-operand order, about 2*K bytes per token);
- * the decode entry points take the argument so that one buffer serves all of them. */
+/* Bytes of scratch the product entry points need for this problem (a multiple of 256): the
+ * transformed activations (lcd_lut_gemm: smoothed, in matrix-operand order, about 2*K bytes per
+ * token with the tokens padded to 128; the decode entry points with M >= 2, or 4 bits: at most
+ * M*K fp16 numbers).  One buffer of this size serves every entry point for the problem. */
 size_t lcd_workspace_bytes(int M, int N, int K, int bits);
 
 /* ---- index packing (offline, once per layer; Sec. 4.1 "constructed ahead of time") ------- *
