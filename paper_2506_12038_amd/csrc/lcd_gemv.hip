@@ -734,7 +734,6 @@ int launch_decode_group(const GroupItem *items, int count, int M, int bits, void
 {
     hipStream_t stream = (hipStream_t)stream_;
     BucketBatch batch{};
-    long long cost[kMaxGroup], total = 0;
     int tiles = 0;
     const bool tokens_path = M > 1 || bits == 4;   // 4 bits: the register dequantiser serves one token too
     // several tokens: quantised activations are made once, ahead of the product, and so are smoothed
@@ -767,15 +766,12 @@ int launch_decode_group(const GroupItem *items, int count, int M, int bits, void
         p.nt = items[i].N / kTileRows; p.kc = items[i].K / kTileCols;
         p.act_scale = items[i].act_scale;
         p.x_ready = codes[i] != nullptr;
-        cost[i] = (long long)p.nt * p.kc;
-        total += cost[i];
         tiles += p.nt;
     }
     // Workgroups per layer.  A layer's time is that of its slowest workgroup, in units of two-chunk
     // steps: a fixed start-up, then for each K segment one pass over its row tiles plus the cost of
     // switching to the segment's activations.  A wave takes `ch` chunks of a full segment; a short
-    // last segment gives every wave ceil(rest / 8).  Start from 7/8 of the proportional share, then
-    // hand out the rest one by one to the layer that is slowest at that moment.
+    // last segment gives every wave ceil(rest / 8).  The split minimises the time of the slowest layer.
     int grid = num_cus();
     if (grid > tiles) grid = tiles;
     if (grid < count) grid = count;
@@ -791,15 +787,44 @@ int launch_decode_group(const GroupItem *items, int count, int M, int bits, void
             const int t = (batch.p[i].nt + n - 1) / n, visits = (t + kVisitTiles - 1) / kVisitTiles;
             return startup_steps + steps_per_tile * t + segs * visits * segment_steps;
         };
-        int used = 0;
+        // smallest number of workgroups with which layer i takes at most T (0: not even one per tile does)
+        auto need = [&](int i, double T) {
+            const int nt = batch.p[i].nt;
+            if (layer_time(i, nt) > T) return 0;
+            int lo = 1, hi = nt;               // layer_time never grows with n
+            while (lo < hi) {
+                const int mid = (lo + hi) / 2;
+                if (layer_time(i, mid) <= T) hi = mid; else lo = mid + 1;
+            }
+            return lo;
+        };
+        auto fits = [&](double T, int *out) {
+            int sum = 0;
+            for (int i = 0; i < count; ++i) {
+                const int n = need(i, T);
+                if (n == 0) return false;
+                out[i] = n;
+                sum += n;
+            }
+            return sum <= grid;
+        };
+        // the smallest common finish time the grid can reach: bisection over T between "one workgroup per
+        // tile everywhere" and "one workgroup per layer" (the host guarantees grid >= count)
+        double t_lo = 0.0, t_hi = 0.0;
         for (int i = 0; i < count; ++i) {
-            long long n = cost[i] * grid * 7 / (total * 8);
-            if (n < 1) n = 1;
-            if (n > batch.p[i].nt) n = batch.p[i].nt;
-            nwg[i] = (int)n;
-            used += nwg[i];
+            t_lo = std::max(t_lo, layer_time(i, batch.p[i].nt));
+            t_hi = std::max(t_hi, layer_time(i, 1));
         }
-        while (used < grid) {
+        int trial[kMaxGroup];
+        if (fits(t_lo, trial)) t_hi = t_lo;
+        for (int it = 0; it < 24 && t_hi - t_lo > 0.02; ++it) {
+            const double mid = 0.5 * (t_lo + t_hi);
+            if (fits(mid, trial)) t_hi = mid; else t_lo = mid;
+        }
+        fits(t_hi, nwg);
+        int used = 0;
+        for (int i = 0; i < count; ++i) used += nwg[i];
+        while (used < grid) {                  // spare workgroups: one by one to the layer that is slowest then
             int best = -1;
             double best_time = 0.0;
             for (int i = 0; i < count; ++i) {
@@ -812,8 +837,19 @@ int launch_decode_group(const GroupItem *items, int count, int M, int bits, void
             ++used;
         }
     };
+    // the split depends on the shapes only: the last one is kept (serving loops repeat a few groups)
+    struct SplitMemo { int count, M, bits, grid, nt[kMaxGroup], kc[kMaxGroup], nwg[kMaxGroup]; };
+    static thread_local SplitMemo memo = {};
+    bool known = memo.count == count && memo.M == M && memo.bits == bits && memo.grid == grid;
+    for (int i = 0; known && i < count; ++i) known = memo.nt[i] == batch.p[i].nt && memo.kc[i] == batch.p[i].kc;
     int nwg[kMaxGroup];
-    split(kBCH, nwg);
+    if (known) {
+        for (int i = 0; i < count; ++i) nwg[i] = memo.nwg[i];
+    } else {
+        split(kBCH, nwg);
+        memo.count = count; memo.M = M; memo.bits = bits; memo.grid = grid;
+        for (int i = 0; i < count; ++i) { memo.nt[i] = batch.p[i].nt; memo.kc[i] = batch.p[i].kc; memo.nwg[i] = nwg[i]; }
+    }
     grid = 0;
     for (int i = 0; i < count; ++i) grid += nwg[i];
     int acc = 0;
