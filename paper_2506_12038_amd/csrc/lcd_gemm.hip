@@ -421,6 +421,9 @@ gemm_kernel(const uint8_t *__restrict__ packed_, const uint8_t *__restrict__ lut
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: keeps addresses scalar
     const int kc = K / kTileCols, nt = N / kTileRows;
+#ifdef LCD_TRACE
+    if (threadIdx.x == 0 && g_gemm_trace && blockIdx.x < 1024) g_gemm_trace[3072 + blockIdx.x] = __builtin_amdgcn_s_memrealtime();
+#endif
     // XCD-aware tile order.  Workgroup ids go round-robin over the 8 XCDs, each with its own L2.
     // Output tiles are numbered token-block-major and cut into 8 contiguous runs, one per XCD, so
     // the workgroups that are resident on an XCD at the same time share one or two 128-token
@@ -476,6 +479,7 @@ gemm_kernel(const uint8_t *__restrict__ packed_, const uint8_t *__restrict__ lut
 
 #ifdef LCD_TRACE
     if (lane == 0 && blockIdx.x == 0 && g_gemm_trace) { g_gemm_trace[wave * 128 + 120] = __builtin_amdgcn_s_memtime(); g_gemm_trace[wave * 128 + 121] = __builtin_amdgcn_s_memrealtime(); }
+    if (threadIdx.x == 0 && g_gemm_trace && blockIdx.x < 2048) g_gemm_trace[1024 + blockIdx.x * 2] = __builtin_amdgcn_s_memrealtime();
 #endif
     BWindow bw;
     WordOps wa, wb;          // operands of the current / next word, swapping roles word by word
@@ -537,6 +541,7 @@ gemm_kernel(const uint8_t *__restrict__ packed_, const uint8_t *__restrict__ lut
 
 #ifdef LCD_TRACE
     if (lane == 0 && blockIdx.x == 0 && g_gemm_trace) { g_gemm_trace[wave * 128 + 122] = __builtin_amdgcn_s_memtime(); g_gemm_trace[wave * 128 + 123] = __builtin_amdgcn_s_memrealtime(); }
+    if (threadIdx.x == 0 && g_gemm_trace && blockIdx.x < 2048) g_gemm_trace[1024 + blockIdx.x * 2 + 1] = __builtin_amdgcn_s_memrealtime();
 #endif
     // The wave that owns the second half of the chunks hands its accumulators to its partner
     // through LDS (the stages are free now): [row group][accumulator 8][register quad 4][lane] float4.
@@ -552,26 +557,54 @@ gemm_kernel(const uint8_t *__restrict__ packed_, const uint8_t *__restrict__ lut
     __syncthreads();
     if (khalf == 1) return;
 
-    // store: accumulator register r of lane l is row 8*(r/4) + 4*(l/32) + r%4 of the pair, token l%32
+    // Sum of the two halves, rounded once to fp16.  Accumulator register r of lane l is row
+    // 8*(r/4) + 4*(l/32) + r%4 of the pair, token l%32: four consecutive rows of one token per
+    // register quad, i.e. 8-byte pieces of 32 different output rows per store instruction.  Stored
+    // like that, every 128-byte line of y is written in 16 pieces and the end of the kernel waits
+    // on the L2's request rate; so the wave first turns its 64 rows x 128 tokens into
+    // [token][row] order through its own (now free) part of the exchange buffer and then writes
+    // whole lines: 8 lanes x 16 bytes per token.
     const int tok = lane & 31, lh = lane >> 5;
-    auto store_acc = [&](const float16v &own, int p, int b) {
-        const int m = (tb0 + b) * 32 + tok;
+    typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+    constexpr int kOutStride = 64 * 2 + 16;   // bytes per token row of the tile (16-byte aligned, spreads the banks)
+    uint8_t *tile_out = reinterpret_cast<uint8_t *>(xchg);   // 32 KiB, touched by this wave only from here on
+    uint2v outv[8][4];
+    auto sum_acc = [&](const float16v &own, int idx) {
 #pragma unroll
         for (int rg = 0; rg < 4; ++rg) {
-            const float4v other = xchg[((p * 4 + b) * 4 + rg) * 64 + lane];
-            const int row_in_pair = 8 * rg + 4 * lh;
-            const int tile = t0 + 2 * p + (row_in_pair >> 4);
-            if (m < M && tile < nt) {
-                typedef _Float16 half4 __attribute__((ext_vector_type(4)));
-                half4 o;
+            const float4v other = xchg[(idx * 4 + rg) * 64 + lane];
+            half4 o;
 #pragma unroll
-                for (int u = 0; u < 4; ++u) o[u] = (_Float16)(own[4 * rg + u] + other[u]);
-                *reinterpret_cast<half4 *>(y + (size_t)m * N + (size_t)(t0 + 2 * p) * kTileRows + row_in_pair) = o;
-            }
+            for (int u = 0; u < 4; ++u) o[u] = (_Float16)(own[4 * rg + u] + other[u]);
+            outv[idx][rg] = __builtin_bit_cast(uint2v, o);
         }
     };
-    store_acc(read_acc<0>(), 0, 0); store_acc(read_acc<1>(), 0, 1); store_acc(read_acc<2>(), 0, 2); store_acc(read_acc<3>(), 0, 3);
-    store_acc(read_acc<4>(), 1, 0); store_acc(read_acc<5>(), 1, 1); store_acc(read_acc<6>(), 1, 2); store_acc(read_acc<7>(), 1, 3);
+    sum_acc(read_acc<0>(), 0); sum_acc(read_acc<1>(), 1); sum_acc(read_acc<2>(), 2); sum_acc(read_acc<3>(), 3);
+    sum_acc(read_acc<4>(), 4); sum_acc(read_acc<5>(), 5); sum_acc(read_acc<6>(), 6); sum_acc(read_acc<7>(), 7);
+    // every read above must precede the writes below, which reuse the same bytes: the wait orders
+    // them for the compiler too (the two sides use different vector types)
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+    for (int idx = 0; idx < 8; ++idx) {
+        const int pr = idx >> 2, blk = idx & 3;
+#pragma unroll
+        for (int rg = 0; rg < 4; ++rg)
+            *reinterpret_cast<uint2v *>(tile_out + (blk * 32 + tok) * kOutStride + (pr * 32 + 8 * rg + 4 * lh) * 2) = outv[idx][rg];
+    }
+    asm volatile("" ::: "memory");               // LDS operations of one wave complete in order; keep the compiler's order too
+    const int r8 = lane & 7;                       // which 8 rows of the wave's 64
+    const bool rows_ok = t0 + (r8 >> 1) < nt;      // N is a multiple of 16: 8 rows are all inside or all outside
+#pragma unroll
+    for (int it = 0; it < kGemmTokens / 8; ++it) {
+        const int tk = it * 8 + (lane >> 3);
+        const uint4v v = *reinterpret_cast<const uint4v *>(tile_out + tk * kOutStride + r8 * 16);
+        const int m = tb0 * 32 + tk;
+        if (m < M && rows_ok) *reinterpret_cast<uint4v *>(y + (size_t)m * N + (size_t)t0 * kTileRows + r8 * 8) = v;
+    }
+#ifdef LCD_TRACE
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if (threadIdx.x == 0 && g_gemm_trace && blockIdx.x < 1024) g_gemm_trace[2048 + blockIdx.x] = __builtin_amdgcn_s_memrealtime();
+#endif
 }
 
 int launch_gemm(const void *packed, const void *lut, const uint16_t *x, const float *s, uint16_t *y,
