@@ -30,13 +30,34 @@ __device__ __forceinline__ uint32_t bfi(uint32_t mask, uint32_t a, uint32_t b) {
 __device__ __forceinline__ half8 as_half8(uint4v v) { return __builtin_bit_cast(half8, v); }
 __device__ __forceinline__ uint4v as_uint4(half8 v) { return __builtin_bit_cast(uint4v, v); }
 
-// Smoothing of one activation: x * (1/s) in fp32 (the reciprocal is accurate to 1 ulp; paper
-// Sec. 4.1 folds the division into one multiplication by a stored reciprocal), rounded once
-// more to fp16 (round to nearest even).  Exact when s is a power of two.
+// Smoothing of one activation: x * (1/s), the reciprocal in fp32 and accurate to 1 ulp (paper
+// Sec. 4.1 folds the division into one multiplication by a stored reciprocal), the product
+// rounded to fp16 by v_fma_mixlo_f16, which takes the fp16 operand as it is: one instruction
+// instead of convert, multiply, convert.  Its last bit differs from that sequence on a few
+// inputs, so EVERY smoothing in the library goes through this instruction: the fused and the
+// ahead-of-time routes then agree bit for bit.  Exact when s is a power of two.
 __device__ __forceinline__ _Float16 smooth_one(uint16_t xbits, float s)
 {
-    const float xf = (float)__builtin_bit_cast(_Float16, xbits);
-    return (_Float16)(xf * __builtin_amdgcn_rcpf(s));
+    const uint32_t a = xbits;
+    const float r = __builtin_amdgcn_rcpf(s);
+    uint32_t d;
+    asm("v_fma_mixlo_f16 %0, %1, %2, 0 op_sel:[0,0,0] op_sel_hi:[1,0,0]" : "=v"(d) : "v"(a), "v"(r));
+    return __builtin_bit_cast(_Float16, (uint16_t)d);
+}
+
+// Two smoothed activations into one register in a single instruction each: v_fma_mix{lo,hi}_f16
+// reads its first operand as the low or high fp16 half of a register, multiplies it by an fp32
+// reciprocal and writes the fp32 product rounded to fp16 into the low / high half of the result --
+// the arithmetic of smooth_one, two results per register.  LO_HALF / HI_HALF: which half of `a` / `b` holds the activation.
+template <int LO_HALF, int HI_HALF>
+__device__ __forceinline__ uint32_t smooth_pair(uint32_t a, float ra, uint32_t b, float rb)
+{
+    uint32_t d;
+    if (LO_HALF == 0) asm("v_fma_mixlo_f16 %0, %1, %2, 0 op_sel:[0,0,0] op_sel_hi:[1,0,0]" : "=v"(d) : "v"(a), "v"(ra));
+    else asm("v_fma_mixlo_f16 %0, %1, %2, 0 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(d) : "v"(a), "v"(ra));
+    if (HI_HALF == 0) asm("v_fma_mixhi_f16 %0, %1, %2, 0 op_sel:[0,0,0] op_sel_hi:[1,0,0]" : "+v"(d) : "v"(b), "v"(rb));
+    else asm("v_fma_mixhi_f16 %0, %1, %2, 0 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "+v"(d) : "v"(b), "v"(rb));
+    return d;
 }
 
 // Input transformation of paper Sec. 4.1 (Eq. 10-11, b = 8), the smoothing and the quantisation

@@ -527,13 +527,13 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_tokens_kernel(const BucketBa
                 for (int e = 0; e < 8; ++e) rs[e] = cv ? __builtin_amdgcn_rcpf(e < 4 ? sa[ch][e] : sb[ch][e - 4]) : 0.0f;
 #pragma unroll
                 for (int mm = 0; mm < 8; ++mm) {
-                    half8 o;
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const uint16_t xb = (uint16_t)(xr[ch][mm][e >> 1] >> (16 * (e & 1)));
-                        o[(e & 3) * 2 + (e >> 2)] = (_Float16)((float)__builtin_bit_cast(_Float16, xb) * rs[e]);
-                    }
-                    *reinterpret_cast<half8 *>(&my_stage[(th * 8 + mm) * kStageStride + 8 * kg]) = o;
+                    const uint4v v = xr[ch][mm];   // register i: columns 2i, 2i+1; result register j: columns j, 4+j
+                    uint4v o;
+                    o[0] = smooth_pair<0, 0>(v[0], rs[0], v[2], rs[4]);
+                    o[1] = smooth_pair<1, 1>(v[0], rs[1], v[2], rs[5]);
+                    o[2] = smooth_pair<0, 0>(v[1], rs[2], v[3], rs[6]);
+                    o[3] = smooth_pair<1, 1>(v[1], rs[3], v[3], rs[7]);
+                    *reinterpret_cast<uint4v *>(&my_stage[(th * 8 + mm) * kStageStride + 8 * kg]) = o;
                 }
             } else {   // wave-uniform branch: x already holds the operands, only the slot order is left
 #pragma unroll
