@@ -543,63 +543,64 @@ gemm_kernel(const uint8_t *__restrict__ packed_, const uint8_t *__restrict__ lut
     if (lane == 0 && blockIdx.x == 0 && g_gemm_trace) { g_gemm_trace[wave * 128 + 122] = __builtin_amdgcn_s_memtime(); g_gemm_trace[wave * 128 + 123] = __builtin_amdgcn_s_memrealtime(); }
     if (threadIdx.x == 0 && g_gemm_trace && blockIdx.x < 2048) g_gemm_trace[1024 + blockIdx.x * 2 + 1] = __builtin_amdgcn_s_memrealtime();
 #endif
-    // The wave that owns the second half of the chunks hands its accumulators to its partner
-    // through LDS (the stages are free now): [row group][accumulator 8][register quad 4][lane] float4.
-    float4v *xchg = reinterpret_cast<float4v *>(lds) + (size_t)rgrp * (8 * 4 * 64);
-    auto put_acc = [&](const float16v &v, int idx) {
+    // The two waves of a row group hold partial sums over the two halves of every chunk.  Each keeps
+    // one 32-row pair and hands the other pair's four accumulators to its partner through LDS (the
+    // stages are free now): per row group two 16 KiB areas, area h read by the wave with khalf == h,
+    // [accumulator 4][register quad 4][lane] float4.
+    float4v *area_in = reinterpret_cast<float4v *>(lds) + (size_t)(rgrp * 2 + khalf) * (4 * 4 * 64);
+    float4v *area_out = reinterpret_cast<float4v *>(lds) + (size_t)(rgrp * 2 + (khalf ^ 1)) * (4 * 4 * 64);
+    auto put_acc = [&](const float16v &v, int slot) {
 #pragma unroll
-        for (int rg = 0; rg < 4; ++rg) xchg[(idx * 4 + rg) * 64 + lane] = float4v{v[4 * rg], v[4 * rg + 1], v[4 * rg + 2], v[4 * rg + 3]};
+        for (int rg = 0; rg < 4; ++rg) area_out[(slot * 4 + rg) * 64 + lane] = float4v{v[4 * rg], v[4 * rg + 1], v[4 * rg + 2], v[4 * rg + 3]};
     };
-    if (khalf == 1) {
-        put_acc(read_acc<0>(), 0); put_acc(read_acc<1>(), 1); put_acc(read_acc<2>(), 2); put_acc(read_acc<3>(), 3);
-        put_acc(read_acc<4>(), 4); put_acc(read_acc<5>(), 5); put_acc(read_acc<6>(), 6); put_acc(read_acc<7>(), 7);
-    }
+    if (khalf == 0) { put_acc(read_acc<4>(), 0); put_acc(read_acc<5>(), 1); put_acc(read_acc<6>(), 2); put_acc(read_acc<7>(), 3); }
+    else            { put_acc(read_acc<0>(), 0); put_acc(read_acc<1>(), 1); put_acc(read_acc<2>(), 2); put_acc(read_acc<3>(), 3); }
     __syncthreads();
-    if (khalf == 1) return;
 
     // Sum of the two halves, rounded once to fp16.  Accumulator register r of lane l is row
     // 8*(r/4) + 4*(l/32) + r%4 of the pair, token l%32: four consecutive rows of one token per
     // register quad, i.e. 8-byte pieces of 32 different output rows per store instruction.  Stored
     // like that, every 128-byte line of y is written in 16 pieces and the end of the kernel waits
-    // on the L2's request rate; so the wave first turns its 64 rows x 128 tokens into
-    // [token][row] order through its own (now free) part of the exchange buffer and then writes
-    // whole lines: 8 lanes x 16 bytes per token.
+    // on the L2's request rate; so the wave first turns its 32 rows x 128 tokens into
+    // [token][row] order through the area it has just read (nobody else touches it any more) and
+    // then writes 64 contiguous bytes per token: 4 lanes x 16 bytes, the other half of the line
+    // coming from its partner.
     const int tok = lane & 31, lh = lane >> 5;
     typedef _Float16 half4 __attribute__((ext_vector_type(4)));
-    constexpr int kOutStride = 64 * 2 + 16;   // bytes per token row of the tile (16-byte aligned, spreads the banks)
-    uint8_t *tile_out = reinterpret_cast<uint8_t *>(xchg);   // 32 KiB, touched by this wave only from here on
-    uint2v outv[8][4];
-    auto sum_acc = [&](const float16v &own, int idx) {
+    constexpr int kOutStride = 32 * 2 + 16;   // bytes per token row of the tile (16-byte aligned, spreads the banks)
+    uint8_t *tile_out = reinterpret_cast<uint8_t *>(area_in);
+    uint2v outv[4][4];
+    auto sum_acc = [&](const float16v &own, int slot) {
 #pragma unroll
         for (int rg = 0; rg < 4; ++rg) {
-            const float4v other = xchg[(idx * 4 + rg) * 64 + lane];
+            const float4v other = area_in[(slot * 4 + rg) * 64 + lane];
             half4 o;
 #pragma unroll
             for (int u = 0; u < 4; ++u) o[u] = (_Float16)(own[4 * rg + u] + other[u]);
-            outv[idx][rg] = __builtin_bit_cast(uint2v, o);
+            outv[slot][rg] = __builtin_bit_cast(uint2v, o);
         }
     };
-    sum_acc(read_acc<0>(), 0); sum_acc(read_acc<1>(), 1); sum_acc(read_acc<2>(), 2); sum_acc(read_acc<3>(), 3);
-    sum_acc(read_acc<4>(), 4); sum_acc(read_acc<5>(), 5); sum_acc(read_acc<6>(), 6); sum_acc(read_acc<7>(), 7);
+    if (khalf == 0) { sum_acc(read_acc<0>(), 0); sum_acc(read_acc<1>(), 1); sum_acc(read_acc<2>(), 2); sum_acc(read_acc<3>(), 3); }
+    else            { sum_acc(read_acc<4>(), 0); sum_acc(read_acc<5>(), 1); sum_acc(read_acc<6>(), 2); sum_acc(read_acc<7>(), 3); }
     // every read above must precede the writes below, which reuse the same bytes: the wait orders
     // them for the compiler too (the two sides use different vector types)
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
-    for (int idx = 0; idx < 8; ++idx) {
-        const int pr = idx >> 2, blk = idx & 3;
+    for (int blk = 0; blk < 4; ++blk) {
 #pragma unroll
         for (int rg = 0; rg < 4; ++rg)
-            *reinterpret_cast<uint2v *>(tile_out + (blk * 32 + tok) * kOutStride + (pr * 32 + 8 * rg + 4 * lh) * 2) = outv[idx][rg];
+            *reinterpret_cast<uint2v *>(tile_out + (blk * 32 + tok) * kOutStride + (8 * rg + 4 * lh) * 2) = outv[blk][rg];
     }
     asm volatile("" ::: "memory");               // LDS operations of one wave complete in order; keep the compiler's order too
-    const int r8 = lane & 7;                       // which 8 rows of the wave's 64
-    const bool rows_ok = t0 + (r8 >> 1) < nt;      // N is a multiple of 16: 8 rows are all inside or all outside
+    const int r4 = lane & 3;                       // which 8 rows of the pair's 32
+    const int tile_first = t0 + 2 * khalf;         // first 16-row tile of this wave's pair
+    const bool rows_ok = tile_first + (r4 >> 1) < nt;   // N is a multiple of 16: 8 rows are all inside or all outside
 #pragma unroll
-    for (int it = 0; it < kGemmTokens / 8; ++it) {
-        const int tk = it * 8 + (lane >> 3);
-        const uint4v v = *reinterpret_cast<const uint4v *>(tile_out + tk * kOutStride + r8 * 16);
+    for (int it = 0; it < kGemmTokens / 16; ++it) {
+        const int tk = it * 16 + (lane >> 2);
+        const uint4v v = *reinterpret_cast<const uint4v *>(tile_out + tk * kOutStride + r4 * 16);
         const int m = tb0 * 32 + tk;
-        if (m < M && rows_ok) *reinterpret_cast<uint4v *>(y + (size_t)m * N + (size_t)t0 * kTileRows + r8 * 8) = v;
+        if (m < M && rows_ok) *reinterpret_cast<uint4v *>(y + (size_t)m * N + (size_t)tile_first * kTileRows + r4 * 8) = v;
     }
 #ifdef LCD_TRACE
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
