@@ -36,14 +36,14 @@ __device__ __forceinline__ uint4v as_uint4(half8 v) { return __builtin_bit_cast(
 // instead of convert, multiply, convert.  Its last bit differs from that sequence on a few
 // inputs, so EVERY smoothing in the library goes through this instruction: the fused and the
 // ahead-of-time routes then agree bit for bit.  Exact when s is a power of two.
-__device__ __forceinline__ _Float16 smooth_one(uint16_t xbits, float s)
+__device__ __forceinline__ _Float16 smooth_with(uint16_t xbits, float r)   // r = v_rcp_f32(s), shared by the caller
 {
     const uint32_t a = xbits;
-    const float r = __builtin_amdgcn_rcpf(s);
     uint32_t d;
     asm("v_fma_mixlo_f16 %0, %1, %2, 0 op_sel:[0,0,0] op_sel_hi:[1,0,0]" : "=v"(d) : "v"(a), "v"(r));
     return __builtin_bit_cast(_Float16, (uint16_t)d);
 }
+__device__ __forceinline__ _Float16 smooth_one(uint16_t xbits, float s) { return smooth_with(xbits, __builtin_amdgcn_rcpf(s)); }
 
 // Two smoothed activations into one register in a single instruction each: v_fma_mix{lo,hi}_f16
 // reads its first operand as the low or high fp16 half of a register, multiplies it by an fp32

@@ -177,21 +177,35 @@ __global__ void __launch_bounds__(256) smooth_kernel(const uint16_t *__restrict_
 {
     __shared__ __attribute__((aligned(16))) uint8_t tile[32 * kSmoothRowBytes];
     const int c = blockIdx.x, mb = blockIdx.y, t = threadIdx.x;
+    // a thread's four groups are the same 8 columns of four token rows: one set of reciprocals
+    const int kg = t & 31, k = c * kTileCols + 8 * kg;
+    float r[8];
+    {
+        const float4v s0 = *reinterpret_cast<const float4v *>(s + k);
+        const float4v s1 = *reinterpret_cast<const float4v *>(s + k + 4);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) r[e] = __builtin_amdgcn_rcpf(e < 4 ? s0[e] : s1[e - 4]);
+    }
+    uint4v xin[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {               // all four loads in flight together
+        const int m = mb * 32 + ((t + 256 * u) >> 5);
+        xin[u] = uint4v{0u, 0u, 0u, 0u};
+        if (m < M) xin[u] = *reinterpret_cast<const uint4v *>(x + (size_t)m * K + k);
+    }
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
         const int grp = t + 256 * u;            // input order: 32 groups of 8 columns per token row
-        const int ml = grp >> 5, kg = grp & 31;
-        const int m = mb * 32 + ml, k = c * kTileCols + 8 * kg;
+        const int ml = grp >> 5;
+        const int m = mb * 32 + ml;
         half8 o;
         if (m < M) {
-            const uint4v xv = *reinterpret_cast<const uint4v *>(x + (size_t)m * K + k);
-            const float4v s0 = *reinterpret_cast<const float4v *>(s + k);
-            const float4v s1 = *reinterpret_cast<const float4v *>(s + k + 4);
+            const uint4v xv = xin[u];
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const uint16_t xb = (uint16_t)(xv[e >> 1] >> (16 * (e & 1)));
                 const int slot = e < 4 ? 2 * e : 2 * (e - 4) + 1;
-                o[slot] = smooth_one(xb, e < 4 ? s0[e] : s1[e - 4]);
+                o[slot] = smooth_with(xb, r[e]);
             }
         } else {
 #pragma unroll
