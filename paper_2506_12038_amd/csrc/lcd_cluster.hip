@@ -58,7 +58,7 @@ __global__ void __launch_bounds__(kAssignThreads) assign_kernel(const uint16_t *
     __syncthreads();
     // the workgroup walks its row: the boundaries are found once per row
     for (int k0 = (int)threadIdx.x * 8; k0 < K; k0 += kAssignCols) {   // K is a multiple of 256: 8 columns are all inside or all outside
-        const uint4v v = *reinterpret_cast<const uint4v *>(w + (size_t)n * K + k0);
+        const uint4v v = stream_load(reinterpret_cast<const uint4v *>(w + (size_t)n * K + k0));
         float wf[8];
         uint32_t cnt[8];
 #pragma unroll
@@ -76,7 +76,7 @@ __global__ void __launch_bounds__(kAssignThreads) assign_kernel(const uint16_t *
         uint2v o;
         o[0] = cnt[0] | (cnt[1] << 8) | (cnt[2] << 16) | (cnt[3] << 24);
         o[1] = cnt[4] | (cnt[5] << 8) | (cnt[6] << 16) | (cnt[7] << 24);
-        *reinterpret_cast<uint2v *>(idx + (size_t)n * K + k0) = o;
+        stream_store(reinterpret_cast<uint2v *>(idx + (size_t)n * K + k0), o);
     }
 }
 
@@ -143,11 +143,11 @@ __global__ void __launch_bounds__(256) remap_kernel(const uint8_t *__restrict__ 
     const int k0 = ((int)blockIdx.y * 256 + (int)threadIdx.x) * 16;
     if (k0 >= K) return;
     const uint32_t bias = (127u - merged[n]) * 0x01010101u;     // byte + bias has bit 7 set iff byte > a (bytes < 16)
-    const uint4v v = *reinterpret_cast<const uint4v *>(idx + (size_t)n * K + k0);
+    const uint4v v = stream_load(reinterpret_cast<const uint4v *>(idx + (size_t)n * K + k0));
     uint4v o;
 #pragma unroll
     for (int d = 0; d < 4; ++d) o[d] = v[d] - (((v[d] + bias) >> 7) & 0x01010101u);
-    *reinterpret_cast<uint4v *>(out + (size_t)n * K + k0) = o;
+    stream_store(reinterpret_cast<uint4v *>(out + (size_t)n * K + k0), o);
 }
 
 int launch_assign(const uint16_t *w, const uint16_t *codebook, int ncent, int N, int K, int bits, uint8_t *idx, void *stream)

@@ -27,6 +27,11 @@ __device__ __forceinline__ float dpp_f32(float v)
 // (mask & a) | (~mask & b): one v_bfi_b32.
 __device__ __forceinline__ uint32_t bfi(uint32_t mask, uint32_t a, uint32_t b) { return (mask & a) | (~mask & b); }
 
+// Loads and stores of data that is touched once per kernel: the non-temporal hint keeps it from
+// displacing what is reused.
+template <class T> __device__ __forceinline__ T stream_load(const T *p) { return __builtin_nontemporal_load(p); }
+template <class T> __device__ __forceinline__ void stream_store(T *p, T v) { __builtin_nontemporal_store(v, p); }
+
 __device__ __forceinline__ half8 as_half8(uint4v v) { return __builtin_bit_cast(half8, v); }
 __device__ __forceinline__ uint4v as_uint4(half8 v) { return __builtin_bit_cast(uint4v, v); }
 
