@@ -24,6 +24,9 @@
 
 namespace lcd {
 
+// packed weights are read by every token block of the layer: default cache policy (the non-temporal
+// hint of the decode kernels costs 2 % here)
+constexpr int kGemmWeightPolicy = 0;
 constexpr int kXcds = 8;             // accelerator complex dies of the MI355X, each with its own L2
 constexpr int kGemmRowGroups = 4;   // 64-row groups per workgroup
 constexpr int kGemmWaves = 2 * kGemmRowGroups;   // x the two halves of a chunk
@@ -295,9 +298,9 @@ __device__ __forceinline__ void load_gemm_tiles(GemmTileRegs<BITS> &r, __amdgpu_
         const uint32_t base = ((uint32_t)tile * (uint32_t)kc + (uint32_t)c) * TB;
         const int slot = 16 * (2 * h + kh) + i;          // lane slot inside the 16 x 256 tile
         const bool v = tile < nt;
-        r.lo[p] = __builtin_amdgcn_raw_buffer_load_b128(packed, v ? base + 16 * slot : 0xFFFFFFF0u, 0, 0);
-        if (BITS == 3) r.hi[p] = __builtin_amdgcn_raw_buffer_load_b64(packed, v ? base + 1024 + 8 * slot : 0xFFFFFFF0u, 0, 0);
-        if (BITS == 4) r.hi4[p] = __builtin_amdgcn_raw_buffer_load_b128(packed, v ? base + 1024 + 16 * slot : 0xFFFFFFF0u, 0, 0);
+        r.lo[p] = __builtin_amdgcn_raw_buffer_load_b128(packed, v ? base + 16 * slot : 0xFFFFFFF0u, 0, kGemmWeightPolicy);
+        if (BITS == 3) r.hi[p] = __builtin_amdgcn_raw_buffer_load_b64(packed, v ? base + 1024 + 8 * slot : 0xFFFFFFF0u, 0, kGemmWeightPolicy);
+        if (BITS == 4) r.hi4[p] = __builtin_amdgcn_raw_buffer_load_b128(packed, v ? base + 1024 + 16 * slot : 0xFFFFFFF0u, 0, kGemmWeightPolicy);
     }
 }
 

@@ -191,7 +191,7 @@ __global__ void __launch_bounds__(256) smooth_kernel(const uint16_t *__restrict_
     for (int u = 0; u < 4; ++u) {               // all four loads in flight together
         const int m = mb * 32 + ((t + 256 * u) >> 5);
         xin[u] = uint4v{0u, 0u, 0u, 0u};
-        if (m < M) xin[u] = *reinterpret_cast<const uint4v *>(x + (size_t)m * K + k);
+        if (m < M) xin[u] = stream_load(reinterpret_cast<const uint4v *>(x + (size_t)m * K + k));   // read once
     }
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
