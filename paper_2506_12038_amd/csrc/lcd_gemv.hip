@@ -671,7 +671,7 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_tokens_kernel(const BucketBa
 }
 
 // ---- activation transformation ahead of the tokens kernel (Sec. 4.1) -----------------------------
-// For 2..16 tokens every workgroup of a layer stages the whole activation matrix, so whatever is
+// On the tokens kernel's route (2..16 tokens, and 4 bits) every workgroup of a layer stages the whole activation matrix, so whatever is
 // done to an activation is repeated by each of them.  This small kernel does it once per layer
 // and leaves the result, as fp16 numbers in the layout of x, in the workspace: the INT8 codes of
 // Eq. 10 (always: the divisions are expensive), or the smoothed activations x/s when K is large
