@@ -101,14 +101,14 @@ def test_grouped_config1_full_size_sampled():
         assert err["max_rel_floored"] <= TOL, err
 
 
-@pytest.mark.parametrize("bits,M", [(3, 1), (2, 16)])
-def test_grouped_launch_replayed_from_a_hip_graph(bits, M):
+@pytest.mark.parametrize("bits,M,quantised", [(3, 1, False), (2, 16, False), (2, 16, True), (4, 3, True), (3, 1, True)])
+def test_grouped_launch_replayed_from_a_hip_graph(bits, M, quantised):
     # the launch configuration bench.py times: the grouped call captured once, replayed several times
     # with eager work and synchronisations in between; every replay must reproduce the eager result
     import torch
     from paper_2506_12038_amd.binding import GemvGroup
     shapes = [(256, 4096), (176, 2816), (64, 11008)]
-    problems, eager = [], []
+    problems, eager, steps = [], [], []
     for i, (N, K) in enumerate(shapes):
         layer = synth.make_layer(1, i, N, K, bits, M, seed_offset=17 * i + bits + M)
         packed = lcd.lcd_pack_indices(to_dev(layer["idx"]), bits)
@@ -116,11 +116,18 @@ def test_grouped_launch_replayed_from_a_hip_graph(bits, M):
         x, s = to_dev(layer["x"]), to_dev(layer["s"])
         y = torch.zeros((M, N), dtype=torch.float16, device="cuda")
         problems.append((packed, lut, x, s, y, N))
-        Y = oracle.lut_matmul(layer["codebook"], layer["idx"], layer["x"], layer["s"], bits)
-        ref = lcd.lcd_lut_gemv(packed, lut, x, s, N, bits)
-        assert oracle.parity_errors(ref.cpu().numpy(), Y)["max_rel_floored"] <= TOL
+        if quantised:   # two kernels per call for several tokens: the activation pre-pass, then the product
+            s_q = float(np.float32(np.quantile(np.abs(layer["x"].astype(np.float64) / layer["s"]), 0.99) / 127.0))
+            steps.append(s_q)
+            Y = oracle.quantised_lut_matmul(layer["codebook"], layer["idx"], layer["x"], layer["s"], s_q, bits)
+            ref = lcd.lcd_lut_gemv_q8(packed, lut, x, s, s_q, N, bits)
+            assert oracle.parity_errors(ref.cpu().numpy(), Y)["max_rel_floored"] <= 1e-3
+        else:
+            Y = oracle.lut_matmul(layer["codebook"], layer["idx"], layer["x"], layer["s"], bits)
+            ref = lcd.lcd_lut_gemv(packed, lut, x, s, N, bits)
+            assert oracle.parity_errors(ref.cpu().numpy(), Y)["max_rel_floored"] <= TOL
         eager.append(ref)
-    group = GemvGroup(problems, bits)
+    group = GemvGroup(problems, bits, s_q=steps if quantised else None)
     stream = torch.cuda.Stream()
     with torch.cuda.stream(stream):
         group(stream)                      # first call outside capture (lazy module load)
