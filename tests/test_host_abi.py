@@ -199,3 +199,28 @@ def test_clustering_entry_points_validate_on_host():
     assert st(lib.lcd_merge_closest(a, a, a, 9, 16, 256, 3, ctypes.c_void_p(0x2000), a, a, None)) == b"LCD_ERR_SIZE"
     assert st(lib.lcd_merge_closest(a, a, a, 8, 16, 256, 3, a, a, a, None)) == b"LCD_ERR_SIZE"      # output over the input codebook
     assert st(lib.lcd_merge_closest(a, a, a, 8, 16, 256, 3, ctypes.c_void_p(0x2000), a, None, None)) == b"LCD_ERR_NULL"
+
+
+def test_header_is_plain_c_and_links_from_c(tmp_path):
+    # the boundary is a C ABI: the header must compile as C99 and a C program must link and run
+    import shutil
+    import subprocess
+    from pathlib import Path
+    root = Path(__file__).resolve().parent.parent
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    src = tmp_path / "use_lcd.c"
+    src.write_text(
+        '#include <stdio.h>\n#include "lcd.h"\n'
+        "int main(void) {\n"
+        "    if (lcd_packed_bytes(16, 256, 3) != 1536 || lcd_lut_bytes(16, 4) != 512) return 1;\n"
+        "    if (lcd_pack_indices_host(NULL, 16, 256, 2, NULL, 0) != LCD_ERR_NULL) return 2;\n"
+        '    printf("%s %d\\n", lcd_status_string(LCD_ERR_BAD_BITS), lcd_layout_revision());\n'
+        "    return 0;\n}\n")
+    exe = tmp_path / "use_lcd"
+    libdir = root / "paper_2506_12038_amd"
+    subprocess.check_call(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", f"-I{root / 'include'}", str(src), "-o", str(exe),
+                           f"-L{libdir}", "-llcd", f"-Wl,-rpath,{libdir}"])
+    out = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert out.returncode == 0, out
+    assert out.stdout.split() == ["LCD_ERR_BAD_BITS", "1"]
