@@ -262,3 +262,29 @@ def test_grouped_layers_of_mixed_index_widths(M):
         Y = oracle.lut_matmul(layer["codebook"], layer["idx"], layer["x"], layer["s"], bits)
         assert oracle.parity_errors(y.cpu().numpy(), Y)["max_rel_floored"] <= TOL
         assert torch.equal(y, lcd.lcd_lut_gemv(packed, lut, x, s, N, bits))
+
+
+def test_gemv_q8_decides_hard_cases_like_the_binary32_oracle():
+    # inputs on which the order of roundings decides the code (a double-precision quotient, or a
+    # product with a rounded reciprocal, gives the neighbouring integer): the kernel's split division
+    # must land on the correctly rounded binary32 quotient
+    import torch
+    cases = [(49119, 2.232786178588867, 0.028895359486341476), (51926, 1.3333886861801147, 0.08302413672208786),
+             (52416, 2.515049934387207, 0.0709344744682312), (18075, 2.6308062076568604, 0.05176938697695732),
+             (51858, 2.7504186630249023, 0.048504382371902466), (49771, 0.9853012561798096, 0.038542672991752625),
+             (51873, 1.5403376817703247, 0.0839715301990509), (52298, 1.627970814704895, 0.0839715301990509),
+             (50758, 1.0950627326965332, 0.04875607416033745), (17859, 2.0101850032806396, 0.0320252850651741)]
+    bits, N, K = 2, 256, 256
+    codebook = np.zeros((N, 4), dtype=np.float16); codebook[:, 0] = 1.0
+    idx = np.ones((N, K), dtype=np.uint8); idx[np.arange(N), np.arange(K)] = 0     # row n reads column n
+    packed = lcd.lcd_pack_indices(to_dev(idx), bits)
+    lut = lcd.lcd_build_lut(to_dev(codebook), bits)
+    for M in (1, 3):
+        for bits16, s0, s_q in cases:
+            x = np.zeros((M, K), dtype=np.float16)
+            x[:, 0] = np.array([bits16], dtype=np.uint16).view(np.float16)[0]
+            s = np.ones(K, dtype=np.float32); s[0] = s0
+            expect = oracle.input_transform(x, s, s_q, 8, single_precision=True)
+            y = lcd.lcd_lut_gemv_q8(packed, lut, to_dev(x), to_dev(s), s_q, N, bits).cpu().numpy()
+            got = np.rint(y.astype(np.float64) / s_q).astype(np.int32)      # y = fp16(s_q * q): q is recoverable
+            assert np.array_equal(got, expect), (M, bits16, s0, s_q, got[:, 0], expect[:, 0])

@@ -58,6 +58,18 @@ MUTATIONS = [
     ("input transformation clips to the printed range",
      "double lo = -ldexp(1.0, b - 1), hi = ldexp(1.0, b - 1) - 1.0;",
      "double lo = -ldexp(1.0, b), hi = ldexp(1.0, b) - 1.0;"),
+    ("binary32 quantiser divides in double precision",
+     "volatile float v = xf / d;",
+     "volatile float v = (float)((double)xf / ((double)s_m[k] * (double)s_q));"),
+    ("binary32 quantiser multiplies by a rounded reciprocal",
+     "volatile float v = xf / d;",
+     "volatile float rcp = 1.0f / d; volatile float v = xf * rcp;"),
+    ("binary32 quantiser rounds half away from zero",
+     "float r = nearbyintf(v);",
+     "float r = roundf(v);"),
+    ("binary32 quantiser clips symmetrically",
+     "float lo = -ldexpf(1.0f, b - 1), hi = ldexpf(1.0f, b - 1) - 1.0f;",
+     "float lo = -ldexpf(1.0f, b - 1) + 1.0f, hi = ldexpf(1.0f, b - 1) - 1.0f;"),
     ("dequantised weight of the wrong centroid",
      "What[(size_t)n * K + k] = oracle_half_to_double(codebook[(size_t)n * ncent + c]);",
      "What[(size_t)n * K + k] = oracle_half_to_double(codebook[(size_t)n * ncent + (c ^ 1)]);"),

@@ -261,6 +261,59 @@ def test_input_transform_single_precision():
     assert oracle.input_transform(x1, s1, 1.0, 8, single_precision=True).tolist() == [[0]]
 
 
+def _rne_binary32(v: Fraction) -> Fraction:
+    """Round a rational to the nearest binary32 number (ties to even), normal range, exact integer arithmetic."""
+    if v == 0:
+        return v
+    sign, a = (-1 if v < 0 else 1), abs(v)
+    e = 0
+    while Fraction(2) ** (e + 1) <= a:
+        e += 1
+    while Fraction(2) ** e > a:
+        e -= 1
+    ulp = Fraction(2) ** (e - 23)
+    n, rem = divmod(a, ulp)
+    n = int(n)
+    if rem * 2 > ulp or (rem * 2 == ulp and n % 2 == 1):
+        n += 1
+    return sign * n * ulp
+
+
+def test_input_transform_single_precision_step_by_step_in_exact_arithmetic():
+    # Inputs found by a search for cases where the order of roundings decides the code: the product
+    # s*s_q rounded to binary32, the quotient rounded to binary32, then round half to even.  Every step
+    # is redone here with rationals and an explicit rounding function (no floating-point hardware
+    # involved); dividing in double precision and rounding the quotient to binary32 afterwards gives
+    # a different code for every one of them.
+    cases = [(49119, 2.232786178588867, 0.028895359486341476),
+             (51926, 1.3333886861801147, 0.08302413672208786),
+             (52416, 2.515049934387207, 0.0709344744682312),
+             (18075, 2.6308062076568604, 0.05176938697695732),
+             (51858, 2.7504186630249023, 0.048504382371902466),
+             (49771, 0.9853012561798096, 0.038542672991752625),
+             # ... and cases where multiplying by the rounded reciprocal of s*s_q decides differently
+             (51873, 1.5403376817703247, 0.0839715301990509),
+             (52298, 1.627970814704895, 0.0839715301990509),
+             (50758, 1.0950627326965332, 0.04875607416033745),
+             (17859, 2.0101850032806396, 0.0320252850651741)]
+    differs = 0
+    for bits16, s, s_q in cases:
+        assert float(np.float32(s)) == s and float(np.float32(s_q)) == s_q          # binary32 values, written exactly
+        xh = np.array([[bits16]], dtype=np.uint16).view(np.float16)
+        x = Fraction(float(xh[0, 0]))
+        d = _rne_binary32(Fraction(s) * Fraction(s_q))
+        v = _rne_binary32(x / d)
+        lo = v.numerator // v.denominator                     # floor
+        frac = v - lo
+        code = lo + (1 if frac > Fraction(1, 2) or (frac == Fraction(1, 2) and lo % 2 == 1) else 0)
+        code = max(-128, min(127, code))
+        got = oracle.input_transform(xh, np.array([s], dtype=np.float32), s_q, 8, single_precision=True)
+        assert got.tolist() == [[code]], (bits16, s, s_q)
+        in_double = oracle.input_transform(xh, np.array([s], dtype=np.float32), s_q, 8)
+        differs += in_double.tolist() != [[code]]
+    assert differs >= 3        # the fp64 evaluation of Eq. 10 decides several of them the other way
+
+
 def test_quantised_product_definition():
     # Y = s_q * sum_k q_k * C[n][idx]: exact small case by hand
     codebook = np.array([[-0.5, -0.25, 0.25, 0.5]], dtype=np.float16)
