@@ -44,6 +44,7 @@ def parse_args():
     ap.add_argument("--act-int8", action="store_true", help="decode configs: INT8 activation codes (input transformation of Sec. 4.1) instead of fp16 x/s")
     ap.add_argument("--offline", action="store_true", help="time the offline kernels (assign, counts, merge, pack, table build) on the config's largest matrix instead of the hot path")
     ap.add_argument("--eager", action="store_true", help="launch every step from Python instead of replaying a HIP graph")
+    ap.add_argument("--library-gemm", action="store_true", help="prefill configs: also time the vendor library's dense fp16 GEMM (torch.matmul) on the same shapes, as context for the roofline fraction")
     return ap.parse_args()
 
 
@@ -212,6 +213,34 @@ def measured_traffic(kernel, cfg_index):
     return None
 
 
+def library_dense_gemm(cfg, M, steps, warmup):
+    """Context only: the vendor library's dense fp16 GEMM (torch.matmul -> hipBLASLt) on fp16 weights of the
+    config's shapes, same token count, same box.  It reads 16-bit weights and does no lookup; what it shows is
+    the rate the chip sustains on this contraction size at the clock its power management allows."""
+    import torch
+    g = torch.Generator(device="cuda"); g.manual_seed(7)
+    mats = []
+    for _, spec in cfg.matrices():
+        x = torch.randn((M, spec.K), device="cuda", generator=g).to(torch.float16)
+        w = (torch.randn((spec.N, spec.K), device="cuda", generator=g) * 0.02).to(torch.float16)
+        mats.append((x, w.t()))
+    for _ in range(warmup):
+        for x, wt in mats:
+            torch.matmul(x, wt)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        for x, wt in mats:
+            torch.matmul(x, wt)
+    e1.record()
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / steps
+    flops = sum(2.0 * M * spec.N * spec.K for _, spec in cfg.matrices())
+    return {"value": flops / us / 1e6, "unit": "TFLOP/s", "us_per_step": us,
+            "what": "torch.matmul (vendor library) on dense fp16 weights of the same shapes and token count, eager launches"}
+
+
 def bench_offline(cfg, steps, warmup):
     """Offline kernels on the largest matrix of the config: HIP-event time per call and the rate in
     algorithmic bytes (what the kernel must read and write once).  One JSON line."""
@@ -322,6 +351,8 @@ def main():
     }
     del ls
     torch.cuda.empty_cache()
+    if args.library_gemm and not decode:
+        out["roofline"]["library_dense_fp16"] = library_dense_gemm(cfg, M, args.steps, args.warmup)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.config, M, bits=args.bits)
     print(json.dumps(out))

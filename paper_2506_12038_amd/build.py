@@ -24,7 +24,10 @@ FLAGS = [
 
 # lcd_gemm.hip keeps its accumulators in fixed AGPRs through inline assembly: the compiler must not
 # use AGPRs as spill space there.
-EXTRA = {"lcd_gemm.hip": ["-mllvm", "-amdgpu-spill-vgpr-to-agpr=0"]}
+# lcd_gemv.hip: the decode kernels' eight leading scalar arguments (the table of first workgroups) are
+# preloaded into scalar registers at wave start instead of being read from the argument segment.
+EXTRA = {"lcd_gemm.hip": ["-mllvm", "-amdgpu-spill-vgpr-to-agpr=0"],
+         "lcd_gemv.hip": ["-mllvm", "-amdgpu-kernarg-preload-count=8"]}
 
 
 def _compile(src: str, keep_asm: bool) -> Path:

@@ -80,10 +80,26 @@ struct BucketProblem {
     int tiles_base, tiles_extra;  // workgroup i of this layer owns tiles_base (+1 if i < tiles_extra) row tiles
     float act_scale;              // 0: fp16 activations x/s; s_q > 0: INT8 codes of Sec. 4.1, output scaled by s_q
     int x_ready;                  // tokens kernel: x already holds the smoothed activations / the codes (transform_kernel)
+    int wg_first;                 // first workgroup of this layer
 };
+// The table of first workgroups (wg_begin[1..16], 16 bits each) also travels as eight leading scalar
+// kernel arguments: those are preloaded into scalar registers when a wave starts, so a workgroup
+// knows its layer without a load and the problem record is the only load between the kernel's
+// entry and its first index loads.  Number of table entries <= b, for b < 2^15 - 1:
+struct WgTable { uint32_t t[kMaxGroup / 2]; };
+__device__ __forceinline__ int layer_of_workgroup(uint32_t b, uint32_t t0, uint32_t t1, uint32_t t2, uint32_t t3,
+                                                  uint32_t t4, uint32_t t5, uint32_t t6, uint32_t t7)
+{
+    // per 16-bit field f: bit 15 of (0x8000 + f) - (b + 1) is clear exactly when f <= b (no borrow crosses a field)
+    const uint32_t bb = (b + 1u) * 0x00010001u, top = 0x80008000u;
+    const uint32_t t[8] = {t0, t1, t2, t3, t4, t5, t6, t7};
+    int n = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) n += __builtin_popcount(~((t[i] | top) - bb) & top);
+    return n;
+}
 struct BucketBatch {
     BucketProblem p[kMaxGroup];
-    int wg_begin[kMaxGroup + 1];  // first workgroup of every layer
     int count;
 #ifdef LCD_TRACE
     unsigned long long *trace;   // debug builds only: 16 timestamps per workgroup
@@ -166,7 +182,9 @@ __device__ __forceinline__ void issue_step_loads(StepRegs<BITS> &r, const Cursor
 }
 
 template <int BITS>
-__global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const BucketBatch batch)
+__global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t t0, const uint32_t t1, const uint32_t t2, const uint32_t t3,
+                                                                   const uint32_t t4, const uint32_t t5, const uint32_t t6, const uint32_t t7,
+                                                                   const BucketBatch batch)
 {
     constexpr int NC = BITS == 2 ? 4 : 8;        // accumulator columns one row tile uses
     constexpr int TG = 16 / NC;                  // row tiles that share one reduction (4 or 2)
@@ -186,11 +204,8 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const BucketBa
     LCD_STAMP(0);
 
     // which layer, which row tiles
-    // (entries past the last layer hold the total, so they never count: no loop over `count`, and
-    // the whole table comes in one scalar load)
-    int pi = 0;
-#pragma unroll
-    for (int i = 1; i < kMaxGroup; ++i) pi += (int)((uint32_t)(batch.wg_begin[i] - 1 - (int)blockIdx.x) >> 31);   // += (blockIdx.x >= wg_begin[i])
+    // (entries past the last layer hold the total, so they never count: no loop over `count`)
+    const int pi = layer_of_workgroup(blockIdx.x, t0, t1, t2, t3, t4, t5, t6, t7);
 #ifdef LCD_TRACE
     asm volatile("" :: "s"(pi));
     const unsigned long long tt1 = __builtin_amdgcn_s_memrealtime();
@@ -200,7 +215,7 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const BucketBa
     asm volatile("" :: "s"(pb.kc), "s"(pb.nt));
     const unsigned long long tt2 = __builtin_amdgcn_s_memrealtime();
 #endif
-    const int li = (int)blockIdx.x - batch.wg_begin[pi];
+    const int li = (int)blockIdx.x - pb.wg_first;
     const int ta = li * pb.tiles_base + min(li, pb.tiles_extra);
     const int tb = ta + pb.tiles_base + (li < pb.tiles_extra ? 1 : 0);
     const int kc = pb.kc, nseg = (kc + kBSeg - 1) / kBSeg;
@@ -462,7 +477,9 @@ __device__ __forceinline__ void issue_tok_loads(TokStepRegs<BITS, CH> &r, const 
 }
 
 template <int BITS, int CH>
-__global__ void __launch_bounds__(kBW * 64, 1) gemv_tokens_kernel(const BucketBatch batch, const int M)
+__global__ void __launch_bounds__(kBW * 64, 1) gemv_tokens_kernel(const uint32_t t0, const uint32_t t1, const uint32_t t2, const uint32_t t3,
+                                                                   const uint32_t t4, const uint32_t t5, const uint32_t t6, const uint32_t t7,
+                                                                   const BucketBatch batch, const int M)
 {
     constexpr int NC = BITS == 2 ? 4 : 8;
     constexpr uint32_t TB = kTileRows * kTileCols * BITS / 8;
@@ -476,11 +493,9 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_tokens_kernel(const BucketBa
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int q = lane >> 4, j = lane & 15, bq = lane >> 4;
 
-    int pi = 0;
-#pragma unroll
-    for (int i = 1; i < kMaxGroup; ++i) pi += (int)((uint32_t)(batch.wg_begin[i] - 1 - (int)blockIdx.x) >> 31);   // += (blockIdx.x >= wg_begin[i])
+    const int pi = layer_of_workgroup(blockIdx.x, t0, t1, t2, t3, t4, t5, t6, t7);
     const BucketProblem pb = batch.p[pi];
-    const int li = (int)blockIdx.x - batch.wg_begin[pi];
+    const int li = (int)blockIdx.x - pb.wg_first;
     const int ta = li * pb.tiles_base + min(li, pb.tiles_extra);
     const int tb_end = ta + pb.tiles_base + (li < pb.tiles_extra ? 1 : 0);
     const int kc = pb.kc, nseg = (kc + kBW * CH - 1) / (kBW * CH), K = kc * kTileCols, N = pb.nt * kTileRows;
@@ -861,14 +876,20 @@ int launch_decode_group(const GroupItem *items, int count, int M, int bits, void
     grid = 0;
     for (int i = 0; i < count; ++i) grid += nwg[i];
     int acc = 0;
+    int wg_begin[kMaxGroup + 1];   // first workgroup of every layer; entries past the last layer hold the total
     for (int i = 0; i < count; ++i) {
-        batch.wg_begin[i] = acc;
+        wg_begin[i] = acc;
         acc += nwg[i];
         batch.p[i].tiles_base = batch.p[i].nt / nwg[i];
         batch.p[i].tiles_extra = batch.p[i].nt % nwg[i];
     }
-    for (int i = count; i <= kMaxGroup; ++i) batch.wg_begin[i] = acc;
+    for (int i = count; i <= kMaxGroup; ++i) wg_begin[i] = acc;
     batch.count = count;
+    static_assert(kMaxGroup == 16, "eight leading kernel arguments hold wg_begin[1..16]");
+    if (acc >= 0x7fff) return (int)hipErrorInvalidConfiguration;   // 16-bit table fields (acc <= max(CUs, count))
+    WgTable table;
+    for (int i = 0; i < kMaxGroup / 2; ++i) table.t[i] = (uint32_t)wg_begin[2 * i + 1] | (uint32_t)wg_begin[2 * i + 2] << 16;
+    for (int i = 0; i < count; ++i) batch.p[i].wg_first = wg_begin[i];
 #ifdef LCD_TRACE
     batch.trace = g_trace;
 #endif
@@ -889,7 +910,8 @@ int launch_decode_group(const GroupItem *items, int count, int M, int bits, void
         if (hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)) return (int)e;
         lds_set[variant][bits - 2] = true;
     }
-    void *args[] = {&batch, const_cast<int *>(&M)};
+    void *args[] = {&table.t[0], &table.t[1], &table.t[2], &table.t[3], &table.t[4], &table.t[5], &table.t[6], &table.t[7],
+                    &batch, const_cast<int *>(&M)};   // the bucket kernel takes no M
     if (hipError_t e = hipLaunchKernel(fn, dim3(grid), dim3(kBW * 64), args, lds, stream)) return (int)e;
     return (int)hipGetLastError();
 }
