@@ -20,6 +20,7 @@
 // contiguous K range; their partial outputs meet in LDS (fixed order).  If K needs more than
 // one workgroup, fp32 partials go to the workspace and a second kernel adds them.
 #include <hip/hip_runtime.h>
+#include <type_traits>
 #include <algorithm>
 #include "lcd_internal.h"
 #include "lcd_device.h"
@@ -112,26 +113,30 @@ struct BucketBatch {
 #endif
 
 // Walks the (visit, segment, tile) sequence of one workgroup.  Everything is wave-uniform.
-// Each (visit, segment) run is padded to a multiple of kSets steps so that the register-set
-// rotation is static; padding steps load nothing and compute nothing.
+// Padded (the tokens kernel): each (visit, segment) run is padded to a multiple of kSets steps so
+// that the register-set rotation is static; padding steps load nothing and compute nothing.
+// Unpadded (the bucket kernel): the sequence has real steps only and the kernel keeps track of the
+// set a run starts with.
 struct Cursor {
     int v0, v1, range_end, sg, i, steps;
-    bool done;
+    bool done, padded;
 };
 
-__device__ __forceinline__ int pad_sets(int n) { return (n + kSets - 1) / kSets * kSets; }
+__device__ __forceinline__ int run_steps(const Cursor &c) { return c.padded ? (c.v1 - c.v0 + kSets - 1) / kSets * kSets : c.v1 - c.v0; }
 
+template <bool PADDED>
 __device__ __forceinline__ void cursor_begin(Cursor &c, int ta, int tb)
 {
+    c.padded = PADDED;
     c.v0 = ta; c.range_end = tb; c.v1 = min(tb, ta + kVisitTiles);
-    c.sg = 0; c.i = 0; c.steps = pad_sets(c.v1 - c.v0); c.done = ta >= tb;
+    c.sg = 0; c.i = 0; c.steps = run_steps(c); c.done = ta >= tb;
 }
 
 __device__ __forceinline__ void cursor_next_visit(Cursor &c)
 {
     c.sg = 0; c.i = 0;
     if (c.v1 < c.range_end) {
-        c.v0 = c.v1; c.v1 = min(c.range_end, c.v0 + kVisitTiles); c.steps = pad_sets(c.v1 - c.v0);
+        c.v0 = c.v1; c.v1 = min(c.range_end, c.v0 + kVisitTiles); c.steps = run_steps(c);
     } else {
         c.done = true;
     }
@@ -157,6 +162,14 @@ struct StepRegs {
 // (bq, j) then also fetches the multipliers of rows 4bq..4bq+3, bucket j % NC, of the group's
 // tile j / NC (fp32, accumulator order, straight from the table: every wave reads the same few
 // hundred bytes, so they come from the L1/L2 cache).
+template <int NC>
+__device__ __forceinline__ uint4v load_multipliers(__amdgpu_buffer_rsrc_t rs_lut, int tile, int v1, int lane)
+{
+    const int j = lane & 15, bq = lane >> 4;
+    const int t = tile + j / NC;
+    return __builtin_amdgcn_raw_buffer_load_b128(rs_lut, t < v1 ? (uint32_t)((t * 4 + bq) * NC + (j % NC)) * 16 : kOob, 0, 0);
+}
+
 template <int BITS, bool WITH_CF>
 __device__ __forceinline__ void issue_step_loads(StepRegs<BITS> &r, const Cursor &c, __amdgpu_buffer_rsrc_t rs,
                                                  __amdgpu_buffer_rsrc_t rs_lut, int kc, int wave, int lane)
@@ -174,11 +187,7 @@ __device__ __forceinline__ void issue_step_loads(StepRegs<BITS> &r, const Cursor
         r.lo[ch] = __builtin_amdgcn_raw_buffer_load_b128(rs, v ? o + 16 * lane : kOob, 0, kStreamPolicy);
         if (BITS == 3) r.hi[ch] = __builtin_amdgcn_raw_buffer_load_b64(rs, v ? o + 1024 + 8 * lane : kOob, 0, kStreamPolicy);
     }
-    if (WITH_CF) {
-        const int j = lane & 15, bq = lane >> 4;
-        const int t = tile + j / NC;
-        r.cf = __builtin_amdgcn_raw_buffer_load_b128(rs_lut, (!c.done && t < c.v1) ? (uint32_t)((t * 4 + bq) * NC + (j % NC)) * 16 : kOob, 0, 0);
-    }
+    if (WITH_CF) r.cf = load_multipliers<NC>(rs_lut, tile, c.done ? 0 : c.v1, lane);
 }
 
 template <int BITS>
@@ -227,7 +236,7 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
     const __amdgpu_buffer_rsrc_t rs_lut = make_rsrc(pb.lutA, (uint32_t)pb.nt * 16 * NC * 4);
 
     Cursor pf{}, cur{};
-    cursor_begin(pf, ta, tb);
+    cursor_begin<false>(pf, ta, tb);
     cur = pf;
 
     // Activations.  A segment is kBSeg*256 = 8 * (threads of the workgroup) columns, and thread t of
@@ -250,8 +259,8 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
     const unsigned long long tt3 = __builtin_amdgcn_s_memrealtime();
 #endif
     load_x(0, true);
-    StepRegs<BITS> r0, r1, r2, r3;
-    issue_step_loads<BITS, true>(r0, pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
+    StepRegs<BITS> rs[kSets];   // always indexed by compile-time constants: four sets of registers
+    issue_step_loads<BITS, true>(rs[0], pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
     if (cur.done) return;   // no row tiles (the host never launches such a workgroup); the loads above moved nothing
 
     uint4v A[kBCH][8];   // this wave's smoothed activations of the current segment, 8 operands per chunk
@@ -322,33 +331,35 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
         }
     };
 
-    // four steps = one turn of the register-set rotation; cur.i is the first step's tile
-    auto four_steps = [&]() {
-        // a run is padded to a multiple of four steps; the padding steps (wave-uniform test)
-        // skip their arithmetic
-        const int left = (cur.v1 - cur.v0) - cur.i;
-        const float4v zero = {0.f, 0.f, 0.f, 0.f};
-        float4v t0, t1 = zero, t3 = zero;
+    // Four steps = one turn of the register-set rotation: the step at position p uses set p and is
+    // followed by the loads of the step three further on, into the set that position p - 1 has
+    // just used.  The sequence of steps has no padding: a run (visit, segment) whose length is no
+    // multiple of four ends in a shorter turn, after which the loads of the next run's first
+    // three steps are under way in the sets behind its last step; the next run moves them to sets
+    // 0..2 before its first turn (after the activations have been switched, so that they have had
+    // that time to land) and fetches the multipliers of its first tiles again.  So the loads stay
+    // three real steps ahead across segment and visit boundaries.
+    StepRegs<BITS> &r0 = rs[0], &r1 = rs[1], &r2 = rs[2], &r3 = rs[3];
+    const float4v zero = {0.f, 0.f, 0.f, 0.f};
+    auto full_turn = [&]() __attribute__((always_inline)) {
+        float4v t0, t1, t3;
         issue_step_loads<BITS, false>(r3, pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
         t0 = tile_sums(r0);
         const uint4v cf_a = r0.cf;   // taken before the set is loaded again
         issue_step_loads<BITS, true>(r0, pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
-        if (left > 1) t1 = tile_sums(r1);
+        t1 = tile_sums(r1);
 #pragma unroll
         for (int u = 0; u < 4; ++u) t0[u] += dpp_f32<(TG == 2 ? 0x118 : 0x114)>(t1[u]);   // row_shr:8 / row_shr:4
         if (TG == 2) reduce_group(t0, cur.i, cf_a);
         issue_step_loads<BITS, false>(r1, pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
-        t1 = zero;
-        if (left > 2) t1 = tile_sums(r2);
+        t1 = tile_sums(r2);
         const uint4v cf_b = r2.cf;
         issue_step_loads<BITS, TG == 2>(r2, pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
-        if (left > 3) t3 = tile_sums(r3);
+        t3 = tile_sums(r3);
         if (TG == 2) {
-            if (left > 2) {
 #pragma unroll
-                for (int u = 0; u < 4; ++u) t1[u] += dpp_f32<0x118>(t3[u]);
-                reduce_group(t1, cur.i + 2, cf_b);
-            }
+            for (int u = 0; u < 4; ++u) t1[u] += dpp_f32<0x118>(t3[u]);
+            reduce_group(t1, cur.i + 2, cf_b);
         } else {
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
@@ -359,10 +370,56 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
         }
         cur.i += 4;
     };
+    // the last 1..3 steps of a run (wave-uniform `left`): as many loads as steps
+    auto short_turn = [&](int left) __attribute__((always_inline)) {
+        float4v t0, t1 = zero;
+        issue_step_loads<BITS, false>(r3, pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
+        t0 = tile_sums(r0);
+        const uint4v cf_a = r0.cf, cf_b = r2.cf;
+        if (left > 1) {
+            issue_step_loads<BITS, false>(r0, pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
+            t1 = tile_sums(r1);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) t0[u] += dpp_f32<(TG == 2 ? 0x118 : 0x114)>(t1[u]);
+        if (TG == 2) reduce_group(t0, cur.i, cf_a);
+        t1 = zero;
+        if (left > 2) {
+            issue_step_loads<BITS, false>(r1, pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
+            t1 = tile_sums(r2);
+        }
+        if (TG == 2) {
+            if (left > 2) reduce_group(t1, cur.i + 2, cf_b);
+        } else {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) t0[u] += dpp_f32<0x118>(t1[u]);
+            reduce_group(t0, cur.i, cf_a);
+        }
+        cur.i += 4;
+    };
+    int behind = 0;   // 1..3: the previous run ended in a short turn of that many steps (wave-uniform)
+    // all turns of the run `cur` stands at
+    auto run_turns = [&]() __attribute__((always_inline)) {
+        if (behind) {
+            // the next three steps' packed words sit in sets behind, behind + 1, behind + 2 (mod 4)
+            auto take = [](StepRegs<BITS> &d, const StepRegs<BITS> &f) __attribute__((always_inline)) {
+#pragma unroll
+                for (int ch = 0; ch < kBCH; ++ch) { d.lo[ch] = f.lo[ch]; if (BITS == 3) d.hi[ch] = f.hi[ch]; }
+            };
+            if (behind == 1) { take(r0, r1); take(r1, r2); take(r2, r3); }
+            else if (behind == 2) { StepRegs<BITS> t; take(t, r0); take(r0, r2); take(r1, r3); take(r2, t); }
+            else { StepRegs<BITS> t, u; take(t, r0); take(u, r1); take(r0, r3); take(r1, t); take(r2, u); }
+            r0.cf = load_multipliers<NC>(rs_lut, cur.v0, cur.v1, lane);
+            if (TG == 2) r2.cf = load_multipliers<NC>(rs_lut, cur.v0 + 2, cur.v1, lane);
+            behind = 0;
+        }
+        for (cur.i = 0; cur.i + 4 <= cur.steps;) full_turn();
+        if (cur.i < cur.steps) { behind = cur.steps - cur.i; short_turn(behind); }
+    };
 
     // the remaining two sets of the pipeline
-    issue_step_loads<BITS, false>(r1, pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
-    issue_step_loads<BITS, TG == 2>(r2, pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
+    issue_step_loads<BITS, false>(rs[1], pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
+    issue_step_loads<BITS, TG == 2>(rs[2], pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
     LCD_STAMP(2);
 #ifdef LCD_TRACE
     if (threadIdx.x == 0 && batch.trace) { batch.trace[blockIdx.x * 16 + 13] = tt0; batch.trace[blockIdx.x * 16 + 14] = tt1; batch.trace[blockIdx.x * 16 + 15] = tt2; batch.trace[blockIdx.x * 16 + 12] = tt3; }
@@ -398,7 +455,7 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
                 for (int g = 0; g < 8; ++g)   // written by this wave only: no barrier
                     A[ch][g] = *reinterpret_cast<const uint4v *>(&xs_lds[(wave * kBCH + ch) * kTileCols + 64 * q + 8 * g]);
             }
-            for (cur.i = 0; cur.i < cur.steps;) four_steps();
+            run_turns();
         }
         LCD_STAMP(4);
 #ifdef LCD_TRACE
@@ -509,7 +566,7 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_tokens_kernel(const uint32_t
                                                    (uint32_t)N * (BITS == 2 ? 8 : BITS == 3 ? 16 : 32));
 
     Cursor pf{}, cur{};
-    cursor_begin(pf, ta, tb_end);
+    cursor_begin<true>(pf, ta, tb_end);
     cur = pf;
 
     TokStepRegs<BITS, CH> r0, r1, r2, r3;
