@@ -15,11 +15,12 @@ from .generators import (
     make_activations,
     make_smoothing,
     make_layer,
+    make_layer_uniform,
     seed_for,
 )
 
 __all__ = [
     "CONFIGS", "LayerSpec", "Config", "get_config", "centroid_set", "make_codebook",
     "make_indices", "outlier_channels", "make_activations", "make_smoothing",
-    "make_layer", "seed_for",
+    "make_layer", "make_layer_uniform", "seed_for",
 ]

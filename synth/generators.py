@@ -99,3 +99,20 @@ def make_layer(config: int, matrix_id: int, N: int, K: int, bits: int, M: int,
         "s": make_smoothing(K, rng("calib"), out_ch),
         "outliers": out_ch,
     }
+
+
+def make_layer_uniform(N: int, K: int, bits: int, M: int, seed: int) -> Dict[str, np.ndarray]:
+    """A cheap layer for large structural tests: indices uniform over the 2^bits codes (one integer
+    draw per weight instead of a normal draw and a search), everything else as in make_layer."""
+    def rng(stream: int) -> np.random.Generator:
+        return np.random.default_rng([seed, stream, N, K, bits])
+
+    out_ch = outlier_channels(K, rng(0))
+    return {
+        "codebook": make_codebook(N, bits, rng(1), "B"),
+        "idx": rng(2).integers(0, 1 << bits, size=(N, K), dtype=np.uint8),
+        "x": make_activations(M, K, rng(3), out_ch),
+        "s": make_smoothing(K, rng(4), out_ch),
+        "outliers": out_ch,
+    }
+

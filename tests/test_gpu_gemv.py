@@ -19,6 +19,23 @@ def test_gemv_m1_small(bits, shape):
     print(shape, bits, err)
 
 
+@pytest.mark.parametrize("bits", [2, 3])
+@pytest.mark.parametrize("tiles_per_workgroup,K", [(3, 4352), (5, 4352), (6, 4352), (7, 4352), (3, 8704), (33, 512)])
+def test_gemv_m1_runs_of_every_length_modulo_four(bits, tiles_per_workgroup, K):
+    # The single-token kernel loads packed words three steps ahead through four register sets; a run of
+    # row tiles (one visit in one K segment) whose length is no multiple of four ends in a short turn and
+    # hands the next run its loads in other sets.  One layer over all compute units gives every workgroup
+    # the same run length: 3, 5, 6, 7 (remainders 3, 1, 2, 3) with two or three segments, and 33 = a full
+    # visit of 32 plus one tile.  M = 2 takes the other kernel over the same sequence.
+    import torch
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    N = cus * tiles_per_workgroup * 16
+    for M in (1, 2):
+        layer = synth.make_layer_uniform(N, K, bits, M, seed=100 * tiles_per_workgroup + bits + M)
+        err = check_layer(layer, bits)
+        print(N, K, bits, M, err)
+
+
 @pytest.mark.parametrize("bits", [2, 3, 4])
 def test_gemv_m1_one_hot_reads_single_centroids(bits):
     # x = e_k, s = 1: y[n] must be exactly C[n][idx[n,k]] -- sweeps every bit position of a tile
