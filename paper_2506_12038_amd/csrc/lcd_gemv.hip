@@ -180,12 +180,15 @@ __device__ __forceinline__ void issue_step_loads(StepRegs<BITS> &r, const Cursor
     const int tile = c.v0 + c.i;
     const bool tv = !c.done && tile < c.v1;
 #pragma unroll
+    // the (tile, chunk) part of the address is wave-uniform and travels as the scalar offset, the
+    // lane's part never changes; only the latter is range-checked, so an invalid step swaps it for
+    // an offset that is out of range (and the scalar part for zero)
     for (int ch = 0; ch < kBCH; ++ch) {
         const int chunk = wave_chunk(c.sg, wave, ch);
         const bool v = tv && chunk < kc;
-        const uint32_t o = ((uint32_t)tile * (uint32_t)kc + (uint32_t)chunk) * TB;
-        r.lo[ch] = __builtin_amdgcn_raw_buffer_load_b128(rs, v ? o + 16 * lane : kOob, 0, kStreamPolicy);
-        if (BITS == 3) r.hi[ch] = __builtin_amdgcn_raw_buffer_load_b64(rs, v ? o + 1024 + 8 * lane : kOob, 0, kStreamPolicy);
+        const uint32_t o = v ? ((uint32_t)tile * (uint32_t)kc + (uint32_t)chunk) * TB : 0u;
+        r.lo[ch] = __builtin_amdgcn_raw_buffer_load_b128(rs, v ? 16 * lane : kOob, o, kStreamPolicy);
+        if (BITS == 3) r.hi[ch] = __builtin_amdgcn_raw_buffer_load_b64(rs, v ? 8 * lane : kOob, o + 1024, kStreamPolicy);
     }
     if (WITH_CF) r.cf = load_multipliers<NC>(rs_lut, tile, c.done ? 0 : c.v1, lane);
 }
@@ -313,6 +316,7 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
 
     // TG tiles share one multiply-and-reduce: tile u of the group moves to columns [u*NC, (u+1)*NC)
     auto reduce_group = [&](float4v m, int tl0, uint4v cfreg) {
+#pragma clang fp contract(off)   // product, then lane-exchanging adds: fused into the product they cost an extra move each
         const int tl = tl0 + j / NC;                    // this lane's tile inside the visit
         const float4v cf = __builtin_bit_cast(float4v, cfreg);   // zeros past the end of the visit
         float4v pv;
@@ -322,6 +326,7 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
             v += dpp_f32<kDppQuadXor1>(v);
             v += dpp_f32<kDppQuadXor2>(v);
             if (NC == 8) v += dpp_f32<kDppRowHalfMirror>(v);
+            asm volatile("" : "+v"(v));   // keeps the last add out of the branch below, where it could not take the lane exchange along
             pv[u] = v;
         }
         if ((j % NC) == 0 && cur.v0 + tl < cur.v1) {
