@@ -12,13 +12,14 @@
 // For 3-bit indices the third bit h flips the sign of the activation in a second pass that
 // lands in columns 4..7:  C[n][4h+l] = P[n][l] + (1-2h) Q[n][l]  gives
 //     y[n] = sum_l P[n][l] * (sum_{k: l_k==l} xs[k]) + Q[n][l] * (sum_{k: l_k==l} (-1)^{h_k} xs[k]).
-// The sign flip is one shift and one v_bfi_b32 per pair of weights.
+// The sign flips cost one xor-and (v_bitop3_b32) per pair of weights plus one 64-bit shift per
+// two pairs.
 //
-// Work split: a wave owns CH consecutive 256-column chunks and keeps their activations in
-// registers for its whole life; it walks over row tiles (16 rows), streaming CH KiB-sized
-// contiguous pieces of the packed matrix per tile.  The waves of a workgroup cover a
-// contiguous K range; their partial outputs meet in LDS (fixed order).  If K needs more than
-// one workgroup, fp32 partials go to the workspace and a second kernel adds them.
+// Work split: the 8 waves of a workgroup split K into segments of 16 chunks (256 columns each),
+// two chunks per wave, and keep their chunks' activations in registers for a whole segment; the
+// workgroup walks over its row tiles (16 rows) segment by segment, every wave streaming two
+// KiB-sized contiguous pieces of the packed matrix per tile.  The waves' partial outputs meet in
+// LDS and are added in a fixed order; K of any length stays inside one workgroup.
 #include <hip/hip_runtime.h>
 #include <type_traits>
 #include <algorithm>
@@ -50,13 +51,13 @@ constexpr uint32_t kOob = 0xFFFFFFF0u;
 // The host gives every layer of the group a number of workgroups proportional to its work; a
 // workgroup owns a contiguous run of row tiles of ONE layer and walks it in "visits" of up to
 // kVisitTiles row tiles.  Per visit:
-//   prologue   smoothed activations of the layer (all K, first visit only) and the visit's
-//              per-bucket multipliers go to LDS; one barrier;
 //   segments   the 8 waves split K into segments of 16 chunks (two 256-column chunks per wave).
-//              For each segment a wave loads its activations LDS -> registers once, then streams
-//              the visit's row tiles: 2-3 KiB of packed indices per tile, 16-32 sparse MFMAs,
-//              and (once per 2 or 4 tiles) a few VALU ops that turn bucket sums into partial
-//              outputs, which the wave adds into its own LDS slot (no synchronisation);
+//              For each segment a wave smooths its own activations (x / s), fans them out to the
+//              lanes through its own piece of LDS (no workgroup synchronisation) and keeps them
+//              in registers, then streams the visit's row tiles: 2-3 KiB of packed indices per
+//              tile, 16-32 sparse MFMAs, and (once per 2 or 4 tiles) a few VALU ops that turn
+//              bucket sums into partial outputs with the per-bucket multipliers (prefetched from
+//              the table together with the tiles), which the wave adds into its own LDS slot;
 //   epilogue   one barrier; the workgroup adds the 8 waves' slots in a fixed order, stores y.
 // Loads of packed indices run kSets-1 steps ahead of the arithmetic, across segment and visit
 // boundaries.  Matrix and vector instructions of one SIMD do not overlap in time (measured), so
