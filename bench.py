@@ -101,6 +101,14 @@ class LayerSet:
             self.groups = [lcd.GemvGroup([(m["packed"][r], m["lut"][r], m["x"], m["s"], m["y"], m["spec"].N) for m in self.mats],
                                          self.bits, s_q=[m["s_q"] for m in self.mats] if act_int8 else None)
                            for r in range(replicas)]
+        elif not per_layer:   # prefill: one grouped call (a smoothing launch and a matrix launch) for the whole set
+            shared_ws = None
+            self.groups = []
+            for r in range(replicas):
+                g = lcd.GemmGroup([(m["packed"][r], m["lut"][r], m["x"], m["s"], m["y"], m["spec"].N) for m in self.mats],
+                                  self.bits, workspace=shared_ws)
+                shared_ws = g.workspace
+                self.groups.append(g)
 
     def step(self, replica):
         if self.groups is not None and not self.per_layer:
@@ -314,7 +322,7 @@ def main():
     wall_ms, event_ms = time_steps(ls, replicas, args.steps, args.warmup, args.eager)
 
     decode = M <= 16
-    n_launch = 1 if (decode and not args.per_layer) else len(ls.mats)
+    n_launch = 1 if not args.per_layer else len(ls.mats)
     decode_kernel = "gemv_bucket_kernel" if (M == 1 and cfg.bits < 4) else "gemv_tokens_kernel"
     # the tokens kernel is preceded by a small activation-transform kernel for INT8 codes and for wide layers
     prepass = decode_kernel == "gemv_tokens_kernel" and not args.per_layer and (args.act_int8 or max(s.K for _, s in cfg.matrices()) >= 16384)
@@ -335,7 +343,8 @@ def main():
         roofline = {
             "bound": "mfma", "achieved": ls.flops / (event_ms * 1e-3) / 1e12, "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
             "frac": ls.flops / (event_ms * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS, "traffic": None,
-            "kernel": "gemm_kernel", "launches_per_step": n_launch, "algorithmic_flops_per_step": ls.flops,
+            "kernel": "gemm_kernel" if args.per_layer else "gemm_group_kernel", "launches_per_step": n_launch,
+            "kernels_per_launch": 2, "algorithmic_flops_per_step": ls.flops,
             "avg_launch_us": event_ms * 1e3 / n_launch,
         }
     out = {

@@ -198,6 +198,21 @@ lcd_status lcd_lut_gemv_grouped_mixed(const lcd_gemv_problem *problems /*HOST*/,
 lcd_status lcd_lut_gemv_q8_grouped(const lcd_gemv_problem *problems /*HOST*/, const float *s_q /*HOST*/, int count,
                                    int M, int bits, void *workspace, size_t workspace_bytes, void *stream);
 
+/* ---- grouped prefill: several independent layers in ONE pair of launches ------------------- *
+ *
+ * The same product as lcd_lut_gemm for `count` (1..16) layers with one token count M >= 1 and one
+ * index width: one smoothing launch for all layers, then one matrix launch whose workgroups take
+ * the layers' output tiles one layer after the other (those with the largest K first), so that
+ * the compute units the tail of one layer leaves idle start on the next.  Results are bit for
+ * bit those of lcd_lut_gemm on every layer.  `problems` is a HOST array, read during the call
+ * only; outputs must not overlap.  Workspace: at least
+ * lcd_workspace_bytes_gemm_grouped(problems, count, M, bits) bytes (DEVICE; the sum of the
+ * layers' lcd_workspace_bytes): every layer's smoothed activations side by side.
+ */
+size_t lcd_workspace_bytes_gemm_grouped(const lcd_gemv_problem *problems /*HOST*/, int count, int M, int bits);
+lcd_status lcd_lut_gemm_grouped(const lcd_gemv_problem *problems /*HOST*/, int count, int M, int bits,
+                                void *workspace, size_t workspace_bytes, void *stream);
+
 /* ---- clustering-side steps that need no calibration data (offline) ------------------------ *
  *
  * Codebooks here are per output row, fp16 [N][2^bits], of which the first `ncent` entries are in

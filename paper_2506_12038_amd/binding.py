@@ -21,6 +21,7 @@ EXPORTS = (
     "lcd_pack_indices", "lcd_unpack_indices", "lcd_pack_indices_host", "lcd_unpack_indices_host",
     "lcd_build_lut", "lcd_lut_gemv", "lcd_lut_gemm", "lcd_lut_gemv_q8",
     "lcd_workspace_bytes_grouped", "lcd_lut_gemv_grouped", "lcd_lut_gemv_q8_grouped", "lcd_lut_gemv_grouped_mixed",
+    "lcd_workspace_bytes_gemm_grouped", "lcd_lut_gemm_grouped",
     "lcd_assign_indices", "lcd_cluster_counts", "lcd_merge_closest",
 )
 
@@ -79,6 +80,10 @@ def load_library():
     lib.lcd_workspace_bytes_grouped.argtypes = [ctypes.POINTER(_Problem), ci, ci, ci]
     lib.lcd_lut_gemv_grouped.restype = ci
     lib.lcd_lut_gemv_grouped.argtypes = [ctypes.POINTER(_Problem), ci, ci, ci, vp, sz, vp]
+    lib.lcd_workspace_bytes_gemm_grouped.restype = sz
+    lib.lcd_workspace_bytes_gemm_grouped.argtypes = [ctypes.POINTER(_Problem), ci, ci, ci]
+    lib.lcd_lut_gemm_grouped.restype = ci
+    lib.lcd_lut_gemm_grouped.argtypes = [ctypes.POINTER(_Problem), ci, ci, ci, vp, sz, vp]
     lib.lcd_lut_gemv_q8_grouped.restype = ci
     lib.lcd_lut_gemv_q8_grouped.argtypes = [ctypes.POINTER(_Problem), ctypes.POINTER(ctypes.c_float), ci, ci, ci, vp, sz, vp]
     lib.lcd_lut_gemv_grouped_mixed.restype = ci
@@ -291,6 +296,40 @@ class GemvGroup:
         else:
             _check(load_library().lcd_lut_gemv_q8_grouped(self._arr, self._s_q, self.count, self.M, self.bits, ws,
                                                           self.workspace.numel(), _stream(stream)))
+
+
+class GemmGroup:
+    """Marshalled argument block of lcd_lut_gemm_grouped (prefill, several layers, one pair of launches):
+    problems = [(packed, lut, x, s, y, N), ...] with one token count and one index width."""
+
+    def __init__(self, problems, bits: int, workspace=None):
+        import torch
+        lib = load_library()
+        self.count, self.bits = len(problems), bits
+        self._keep = list(problems)
+        self.M = problems[0][2].shape[0]
+        arr = (_Problem * self.count)()
+        for i, (packed, lut, x, s, y, N) in enumerate(problems):
+            if x.shape[0] != self.M:
+                raise ValueError("all problems of a group share M")
+            arr[i] = _Problem(_dev(packed, torch.uint8, "packed").value, _dev(lut, torch.uint8, "lut").value,
+                              _dev(x, torch.float16, "x").value, _dev(s, torch.float32, "s").value,
+                              _dev(y, torch.float16, "y").value, N, x.shape[1])
+        self._arr = arr
+        need = lib.lcd_workspace_bytes_gemm_grouped(arr, self.count, self.M, bits)
+        if need == 0:
+            raise ValueError("invalid group (shapes, M or bits)")
+        self.workspace = workspace if workspace is not None else torch.empty(need, dtype=torch.uint8, device=problems[0][2].device)
+
+    def __call__(self, stream=None):
+        import torch
+        _check(load_library().lcd_lut_gemm_grouped(self._arr, self.count, self.M, self.bits, _dev(self.workspace, torch.uint8, "workspace"),
+                                                   self.workspace.numel(), _stream(stream)))
+
+
+def lcd_lut_gemm_grouped(problems, bits: int, workspace=None, stream=None):
+    """Prefill for several layers at once: problems = [(packed, lut, x, s, y, N), ...]; writes every y."""
+    GemmGroup(problems, bits, workspace)(stream)
 
 
 def lcd_workspace_bytes_grouped(problems, bits: int) -> int:

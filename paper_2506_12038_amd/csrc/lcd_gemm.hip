@@ -19,6 +19,7 @@
 //     conflict-free) through a 4-register rotating window.
 // Each decoded A operand is used for 4 token blocks, each B operand for 2 row pairs.
 #include <hip/hip_runtime.h>
+#include <algorithm>
 #include "lcd_internal.h"
 #include "lcd_device.h"
 
@@ -413,28 +414,16 @@ __device__ unsigned long long *g_gemm_trace;   // debug builds only
 #define GEMM_STAMP(slot) do { } while (0)
 #endif
 
+// One output tile (row block bx, token block by) of one layer: the whole life of a workgroup.
 template <int BITS>
-__global__ void __launch_bounds__(kGemmWaves * 64, 1)
-gemm_kernel(const uint8_t *__restrict__ packed_, const uint8_t *__restrict__ lutB, const uint8_t *__restrict__ xs,
-            uint16_t *__restrict__ y, int M, int Mpad, int N, int K, int grid_rows, int tiles_per_xcd)
+__device__ __forceinline__ void gemm_tile(const uint8_t *__restrict__ packed_, const uint8_t *__restrict__ lutB, const uint8_t *__restrict__ xs,
+                                          uint16_t *__restrict__ y, int M, int Mpad, int N, int K, int bx, int by, uint8_t *lds)
 {
-    extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];  // 2 stages x 64 KiB
     constexpr uint32_t TB = kTileRows * kTileCols * BITS / 8;
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: keeps addresses scalar
     const int kc = K / kTileCols, nt = N / kTileRows;
-#ifdef LCD_TRACE
-    if (threadIdx.x == 0 && g_gemm_trace && blockIdx.x < 1024) g_gemm_trace[3072 + blockIdx.x] = __builtin_amdgcn_s_memrealtime();
-#endif
-    // XCD-aware tile order.  Workgroup ids go round-robin over the 8 XCDs, each with its own L2.
-    // Output tiles are numbered token-block-major and cut into 8 contiguous runs, one per XCD, so
-    // the workgroups that are resident on an XCD at the same time share one or two 128-token
-    // blocks of activations (1 MiB each at K = 4096), which then stay in that XCD's 4 MiB L2.
-    const int out_tile = (int)(blockIdx.x % kXcds) * tiles_per_xcd + (int)(blockIdx.x / kXcds);
-    const int total_tiles = grid_rows * (Mpad / kGemmTokens);
-    if ((int)(blockIdx.x / kXcds) >= tiles_per_xcd || out_tile >= total_tiles) return;
-    const int bx = out_tile % grid_rows, by = out_tile / grid_rows;
     const int rgrp = wave & (kGemmRowGroups - 1), khalf = wave >> 2;     // row group and chunk half of this wave
     const int t0 = (bx * kGemmRowGroups + rgrp) * (2 * kGemmPairs);      // first row tile of this wave
     const int tb0 = by * kGemmTokBlks;                                   // first 32-token block of this workgroup
@@ -611,6 +600,52 @@ gemm_kernel(const uint8_t *__restrict__ packed_, const uint8_t *__restrict__ lut
 #endif
 }
 
+// XCD-aware tile order.  Workgroup ids go round-robin over the 8 XCDs, each with its own L2.
+// Output tiles are numbered token-block-major and cut into 8 contiguous runs, one per XCD, so
+// the workgroups that are resident on an XCD at the same time share one or two 128-token
+// blocks of activations (1 MiB each at K = 4096), which then stay in that XCD's 4 MiB L2.
+template <int BITS>
+__global__ void __launch_bounds__(kGemmWaves * 64, 1)
+gemm_kernel(const uint8_t *__restrict__ packed_, const uint8_t *__restrict__ lutB, const uint8_t *__restrict__ xs,
+            uint16_t *__restrict__ y, int M, int Mpad, int N, int K, int grid_rows, int tiles_per_xcd)
+{
+    extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];  // 2 stages x 64 KiB
+#ifdef LCD_TRACE
+    if (threadIdx.x == 0 && g_gemm_trace && blockIdx.x < 1024) g_gemm_trace[3072 + blockIdx.x] = __builtin_amdgcn_s_memrealtime();
+#endif
+    const int out_tile = (int)(blockIdx.x % kXcds) * tiles_per_xcd + (int)(blockIdx.x / kXcds);
+    const int total_tiles = grid_rows * (Mpad / kGemmTokens);
+    if ((int)(blockIdx.x / kXcds) >= tiles_per_xcd || out_tile >= total_tiles) return;
+    gemm_tile<BITS>(packed_, lutB, xs, y, M, Mpad, N, K, out_tile % grid_rows, out_tile / grid_rows, lds);
+}
+
+// Several layers in one launch (same token count and index width): every XCD's queue of
+// workgroups holds its run of every layer's tiles, layer after layer in the order of the batch
+// (the host puts the layers with the longest tiles first), so the tail of one layer is filled by
+// the head of the next and only the last layer leaves compute units idle at the end.
+struct GemmProblem {
+    const uint8_t *packed, *lutB, *xs;
+    uint16_t *y;
+    int N, K, grid_rows, tiles_per_xcd;
+    int queue_begin;   // position of this layer's first tile in an XCD's queue
+};
+struct GemmBatch {
+    GemmProblem p[kMaxGroup];
+    int count, M, Mpad;
+};
+template <int BITS>
+__global__ void __launch_bounds__(kGemmWaves * 64, 1) gemm_group_kernel(const GemmBatch batch)
+{
+    extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];  // 2 stages x 64 KiB
+    const int xcd = (int)(blockIdx.x % kXcds), pos = (int)(blockIdx.x / kXcds);
+    int pi = 0;
+    for (int i = 1; i < batch.count; ++i) pi += pos >= batch.p[i].queue_begin ? 1 : 0;   // queue_begin grows with i
+    const GemmProblem pb = batch.p[pi];
+    const int out_tile = xcd * pb.tiles_per_xcd + (pos - pb.queue_begin);
+    if (out_tile >= pb.grid_rows * (batch.Mpad / kGemmTokens)) return;
+    gemm_tile<BITS>(pb.packed, pb.lutB, pb.xs, pb.y, batch.M, batch.Mpad, pb.N, pb.K, out_tile % pb.grid_rows, out_tile / pb.grid_rows, lds);
+}
+
 int launch_gemm(const void *packed, const void *lut, const uint16_t *x, const float *s, uint16_t *y,
                 int M, int N, int K, int bits, void *workspace, const GemmPlan &plan, void *stream_)
 {
@@ -636,6 +671,50 @@ int launch_gemm(const void *packed, const void *lut, const uint16_t *x, const fl
     int M_arg = M, Mpad_arg = Mpad, N_arg = N, K_arg = K, rows_arg = grid_rows, xcd_arg = tiles_per_xcd;
     void *args[] = {&packed_arg, &lutB, &xs_arg, &y, &M_arg, &Mpad_arg, &N_arg, &K_arg, &rows_arg, &xcd_arg};
     if (hipError_t e = hipLaunchKernel(fn, grid, block, args, lds_bytes, stream)) return (int)e;
+    return (int)hipGetLastError();
+}
+
+int launch_gemm_group(const GroupItem *items, int count, int M, int bits, void *workspace, void *stream_)
+{
+    hipStream_t stream = (hipStream_t)stream_;
+    const int Mpad = plan_gemm(M, items[0].N, items[0].K, bits).m_pad;
+    // layers with the longest tiles (largest K) first in every XCD's queue
+    int order[kMaxGroup];
+    for (int i = 0; i < count; ++i) order[i] = i;
+    std::stable_sort(order, order + count, [&](int a, int b) { return items[a].K > items[b].K; });
+    SmoothItem sm[kMaxGroup];
+    GemmBatch batch{};
+    size_t offset = 0;
+    int queue = 0;
+    for (int q = 0; q < count; ++q) {
+        const GroupItem &it = items[order[q]];
+        uint8_t *xs = static_cast<uint8_t *>(workspace) + offset;
+        offset += plan_gemm(M, it.N, it.K, bits).xs_bytes;
+        sm[q] = SmoothItem{it.x, it.s, xs, it.K};
+        GemmProblem &p = batch.p[q];
+        p.packed = static_cast<const uint8_t *>(it.packed);
+        p.lutB = static_cast<const uint8_t *>(it.lut) + (bits == 4 ? 0 : (size_t)it.N * (bits == 2 ? 4 : 8) * 4);
+        p.xs = xs;
+        p.y = it.y;
+        p.N = it.N; p.K = it.K;
+        const int nt = it.N / kTileRows, tiles_per_wg = kGemmRowGroups * 2 * kGemmPairs;
+        p.grid_rows = (nt + tiles_per_wg - 1) / tiles_per_wg;
+        const int total_tiles = p.grid_rows * (Mpad / kGemmTokens);
+        p.tiles_per_xcd = (total_tiles + kXcds - 1) / kXcds;
+        p.queue_begin = queue;
+        queue += p.tiles_per_xcd;
+    }
+    batch.count = count; batch.M = M; batch.Mpad = Mpad;
+    if (int e = launch_smooth_group(sm, count, M, Mpad, stream)) return e;
+    const size_t lds_bytes = 2 * kStageBytes;
+    static bool attr_set[3] = {false, false, false};
+    const void *fn = bits == 2 ? (const void *)gemm_group_kernel<2> : bits == 3 ? (const void *)gemm_group_kernel<3> : (const void *)gemm_group_kernel<4>;
+    if (!attr_set[bits - 2]) {
+        if (hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes)) return (int)e;
+        attr_set[bits - 2] = true;
+    }
+    void *args[] = {&batch};
+    if (hipError_t e = hipLaunchKernel(fn, dim3((unsigned)queue * kXcds), dim3(kGemmWaves * 64), args, lds_bytes, stream)) return (int)e;
     return (int)hipGetLastError();
 }
 

@@ -329,6 +329,37 @@ lcd_status lcd_lut_gemm(const void *packed, const void *lut, const uint16_t *x, 
     return LCD_OK;
 }
 
+size_t lcd_workspace_bytes_gemm_grouped(const lcd_gemv_problem *problems, int count, int M, int bits)
+{
+    if (!problems || count < 1 || count > kMaxGroup || M < 1) return 0;
+    size_t total = 0;
+    for (int i = 0; i < count; ++i) {
+        if (check_shape(problems[i].N, problems[i].K, bits) != LCD_OK) return 0;
+        total += plan_gemm(M, problems[i].N, problems[i].K, bits).xs_bytes;
+    }
+    return total;
+}
+
+lcd_status lcd_lut_gemm_grouped(const lcd_gemv_problem *problems, int count, int M, int bits,
+                                void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!problems) return fail(LCD_ERR_NULL, "problems is NULL");
+    if (count < 1 || count > kMaxGroup) return fail(LCD_ERR_SIZE, "count=%d must be in 1..%d", count, kMaxGroup);
+    GroupItem items[kMaxGroup];
+    size_t need = 0;
+    for (int i = 0; i < count; ++i) {
+        const lcd_gemv_problem &p = problems[i];
+        // every layer's share of the workspace is checked below against the sum
+        if (lcd_status st = check_product(p.packed, p.lut, p.x, p.s, p.y, M, p.N, p.K, bits, workspace, (size_t)-1)) return st;
+        need += plan_gemm(M, p.N, p.K, bits).xs_bytes;
+        items[i] = GroupItem{p.packed, p.lut, p.x, p.s, p.y, p.N, p.K, 0.0f};
+    }
+    if (workspace_bytes < need) return fail(LCD_ERR_SIZE, "workspace_bytes=%zu < %zu", workspace_bytes, need);
+    if (int e = launch_gemm_group(items, count, M, bits, workspace, stream))
+        return fail(LCD_ERR_HIP, "grouped gemm launch: %s", hip_error_name(e));
+    return LCD_OK;
+}
+
 static lcd_status check_ncent(int ncent, int bits, int least)
 {
     if (ncent < least || ncent > (1 << bits))

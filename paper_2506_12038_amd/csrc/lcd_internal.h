@@ -48,5 +48,9 @@ int launch_merge(const uint16_t *cb_in, const uint32_t *counts, const uint8_t *i
                  uint16_t *cb_out, uint8_t *idx_out, uint8_t *merged, void *stream);
 const char *hip_error_name(int err);
 int launch_smooth(const uint16_t *x, const float *s, void *xs, int M, int Mpad, int K, void *stream);
+struct SmoothItem { const uint16_t *x; const float *s; void *xs; int K; };
+int launch_smooth_group(const SmoothItem *items, int count, int M, int Mpad, void *stream);
+// prefill, several layers in one launch; the workspace holds every layer's smoothed activations side by side
+int launch_gemm_group(const GroupItem *items, int count, int M, int bits, void *workspace, void *stream);
 
 }  // namespace lcd

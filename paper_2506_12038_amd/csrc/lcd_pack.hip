@@ -172,11 +172,11 @@ __global__ void __launch_bounds__(256) build_lut_kernel(const uint16_t *__restri
 // thread smooths 8 values, and the tile is turned into operand order through LDS so that the
 // stores are coalesced too (16-byte stores scattered 1 KiB apart ran at a third of the rate).
 constexpr int kSmoothRowBytes = 32 * 16 + 16;   // one [m 32][16 B] row of the tile in LDS, padded
-__global__ void __launch_bounds__(256) smooth_kernel(const uint16_t *__restrict__ x, const float *__restrict__ s,
-                                                     _Float16 *__restrict__ xs, int M, int Mpad, int K)
+__device__ __forceinline__ void smooth_tile(const uint16_t *__restrict__ x, const float *__restrict__ s,
+                                            _Float16 *__restrict__ xs, int M, int Mpad, int K, int c, int mb)
 {
     __shared__ __attribute__((aligned(16))) uint8_t tile[32 * kSmoothRowBytes];
-    const int c = blockIdx.x, mb = blockIdx.y, t = threadIdx.x;
+    const int t = threadIdx.x;
     // a thread's four groups are the same 8 columns of four token rows: one set of reciprocals
     const int kg = t & 31, k = c * kTileCols + 8 * kg;
     float r[8];
@@ -223,6 +223,31 @@ __global__ void __launch_bounds__(256) smooth_kernel(const uint16_t *__restrict_
         const int row = grp >> 5, ml = grp & 31;
         *reinterpret_cast<half8 *>(dst + (size_t)grp * 8) = *reinterpret_cast<const half8 *>(tile + row * kSmoothRowBytes + ml * 16);
     }
+}
+
+__global__ void __launch_bounds__(256) smooth_kernel(const uint16_t *__restrict__ x, const float *__restrict__ s,
+                                                     _Float16 *__restrict__ xs, int M, int Mpad, int K)
+{
+    smooth_tile(x, s, xs, M, Mpad, K, blockIdx.x, blockIdx.y);
+}
+
+// the activations of several layers in one launch: grid.z = layer, grid.x = the widest layer's chunks
+struct SmoothBatch { SmoothItem p[kMaxGroup]; };
+__global__ void __launch_bounds__(256) smooth_group_kernel(const SmoothBatch batch, int M, int Mpad)
+{
+    const SmoothItem it = batch.p[blockIdx.z];
+    if ((int)blockIdx.x * kTileCols >= it.K) return;   // uniform over the workgroup
+    smooth_tile(it.x, it.s, (_Float16 *)it.xs, M, Mpad, it.K, blockIdx.x, blockIdx.y);
+}
+
+int launch_smooth_group(const SmoothItem *items, int count, int M, int Mpad, void *stream)
+{
+    SmoothBatch batch{};
+    int widest = 0;
+    for (int i = 0; i < count; ++i) { batch.p[i] = items[i]; widest = items[i].K > widest ? items[i].K : widest; }
+    const dim3 grid((unsigned)(widest / kTileCols), (unsigned)(Mpad / 32), (unsigned)count), block(256);
+    hipLaunchKernelGGL(smooth_group_kernel, grid, block, 0, (hipStream_t)stream, batch, M, Mpad);
+    return (int)hipGetLastError();
 }
 
 int launch_smooth(const uint16_t *x, const float *s, void *xs, int M, int Mpad, int K, void *stream)

@@ -109,3 +109,67 @@ def test_codebooks_with_fewer_centroids_than_the_container_holds(bits, ncent, M,
     layer["codebook"][:, ncent:] = 0
     assert int(layer["idx"].max()) == ncent - 1
     check_layer(layer, bits, entry)
+
+
+@pytest.mark.parametrize("bits,M", [(2, 200), (3, 64), (3, 300), (4, 129)])
+def test_grouped_prefill_matches_single_calls_and_oracle(bits, M):
+    # several layers of different N and K in one pair of launches: the same bits as lcd_lut_gemm layer by layer
+    import torch
+    shapes = [(272, 1024), (1040, 512), (48, 2816), (4112, 256), (16, 4352)]
+    problems, layers, singles = [], [], []
+    for i, (N, K) in enumerate(shapes):
+        layer = synth.make_layer(3, i, N, K, bits, M, seed_offset=5 * i + bits + M)
+        packed = lcd.lcd_pack_indices(to_dev(layer["idx"]), bits)
+        lut = lcd.lcd_build_lut(to_dev(layer["codebook"]), bits)
+        x, s = to_dev(layer["x"]), to_dev(layer["s"])
+        y = torch.full((M, N), float("nan"), dtype=torch.float16, device="cuda")
+        problems.append((packed, lut, x, s, y, N))
+        layers.append(layer)
+        singles.append(lcd.lcd_lut_gemm(packed, lut, x, s, N, bits))
+    lcd.lcd_lut_gemm_grouped(problems, bits)
+    torch.cuda.synchronize()
+    for (packed, lut, x, s, y, N), layer, single in zip(problems, layers, singles):
+        assert torch.equal(y, single)
+        Y = oracle.lut_matmul(layer["codebook"], layer["idx"], layer["x"], layer["s"], bits)
+        assert oracle.parity_errors(y.cpu().numpy(), Y)["max_rel_floored"] <= TOL
+
+
+def test_grouped_prefill_config3_sampled_and_replayed_from_a_hip_graph():
+    # the launch configuration bench.py times for the prefill config: the whole 7B set in one grouped
+    # call, captured once and replayed; sampled rows against the oracle, every replay against the eager call
+    import torch
+    from paper_2506_12038_amd.binding import GemmGroup
+    config = synth.get_config(3)
+    M = 256
+    problems, samples = [], []
+    for mid, spec in config.matrices():
+        layer = synth.make_layer(3, mid, spec.N, spec.K, config.bits, M)
+        packed = lcd.lcd_pack_indices(to_dev(layer["idx"]), config.bits)
+        lut = lcd.lcd_build_lut(to_dev(layer["codebook"]), config.bits)
+        y = torch.zeros((M, spec.N), dtype=torch.float16, device="cuda")
+        problems.append((packed, lut, to_dev(layer["x"]), to_dev(layer["s"]), y, spec.N))
+        rs = np.sort(np.random.default_rng(mid).choice(spec.N, size=64, replace=False))
+        rs[0] = 0; rs[-1] = spec.N - 1
+        samples.append((rs, oracle.lut_matmul(layer["codebook"][rs], layer["idx"][rs], layer["x"], layer["s"], config.bits)))
+        del layer
+    group = GemmGroup(problems, config.bits)
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        group(stream)
+    torch.cuda.synchronize()
+    eager = [p[4].clone() for p in problems]
+    for (rs, Y), e in zip(samples, eager):
+        assert oracle.parity_errors(e.cpu().numpy()[:, rs], Y)["max_rel_floored"] <= TOL
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=stream):
+        group(stream)
+    for rep in range(3):
+        for p in problems:
+            p[4].fill_(float("nan"))
+        torch.cuda.synchronize()
+        with torch.cuda.stream(stream):
+            graph.replay()
+        torch.cuda.synchronize()
+        for p, e in zip(problems, eager):
+            assert torch.equal(p[4], e), rep
+

@@ -182,6 +182,32 @@ def test_grouped_entry_point_validates_on_host():
     assert st(lib.lcd_lut_gemv_grouped_mixed(arr, widths, 2, 4, ctypes.c_void_p(a), 256, None)) == b"LCD_ERR_SIZE"
 
 
+def test_grouped_prefill_entry_point_validates_on_host():
+    from paper_2506_12038_amd.binding import _Problem
+    lib = lcd.load_library()
+    a = 0x1000
+    arr = (_Problem * 2)(_Problem(a, a, a, a, a, 16, 256), _Problem(a, a, a, a, a, 32, 512))
+    st = lambda code: lib.lcd_status_string(code)
+    # the workspace is the sum of the layers' own: smoothed activations side by side
+    need = lib.lcd_workspace_bytes_gemm_grouped(arr, 2, 200, 3)
+    assert need == lcd.lcd_workspace_bytes(200, 16, 256, 3) + lcd.lcd_workspace_bytes(200, 32, 512, 3)
+    assert lib.lcd_workspace_bytes_gemm_grouped(arr, 0, 200, 3) == 0
+    assert lib.lcd_workspace_bytes_gemm_grouped(arr, 17, 200, 3) == 0
+    assert lib.lcd_workspace_bytes_gemm_grouped(arr, 2, 0, 3) == 0
+    assert lib.lcd_workspace_bytes_gemm_grouped(arr, 2, 200, 5) == 0
+    assert st(lib.lcd_lut_gemm_grouped(None, 2, 200, 3, ctypes.c_void_p(a), need, None)) == b"LCD_ERR_NULL"
+    assert st(lib.lcd_lut_gemm_grouped(arr, 0, 200, 3, ctypes.c_void_p(a), need, None)) == b"LCD_ERR_SIZE"
+    assert st(lib.lcd_lut_gemm_grouped(arr, 2, 0, 3, ctypes.c_void_p(a), need, None)) == b"LCD_ERR_BAD_M"
+    assert st(lib.lcd_lut_gemm_grouped(arr, 2, 200, 1, ctypes.c_void_p(a), need, None)) == b"LCD_ERR_BAD_BITS"
+    assert st(lib.lcd_lut_gemm_grouped(arr, 2, 200, 3, ctypes.c_void_p(a), need - 256, None)) == b"LCD_ERR_SIZE"
+    assert st(lib.lcd_lut_gemm_grouped(arr, 2, 200, 3, None, need, None)) == b"LCD_ERR_NULL"
+    arr[1].N = 40
+    assert st(lib.lcd_lut_gemm_grouped(arr, 2, 200, 3, ctypes.c_void_p(a), need, None)) == b"LCD_ERR_BAD_SHAPE"
+    arr[1].N = 32
+    arr[0].x = 0x1008
+    assert st(lib.lcd_lut_gemm_grouped(arr, 2, 200, 3, ctypes.c_void_p(a), need, None)) == b"LCD_ERR_ALIGN"
+
+
 def test_clustering_entry_points_validate_on_host():
     lib = lcd.load_library()
     a = ctypes.c_void_p(0x1000)
