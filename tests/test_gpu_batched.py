@@ -173,3 +173,26 @@ def test_grouped_prefill_config3_sampled_and_replayed_from_a_hip_graph():
         for p, e in zip(problems, eager):
             assert torch.equal(p[4], e), rep
 
+
+@pytest.mark.parametrize("count", [1, 16])
+def test_grouped_prefill_smallest_and_largest_group(count):
+    # one layer (the grouped call degenerates to lcd_lut_gemm) and the largest group the entry point takes
+    import torch
+    bits, M = 3, 70
+    problems, singles = [], []
+    for i in range(count):
+        N, K = 16 * (1 + i % 5), 256 * (1 + (3 * i) % 4)
+        layer = synth.make_layer(3, i, N, K, bits, M, seed_offset=11 * i + count)
+        packed = lcd.lcd_pack_indices(to_dev(layer["idx"]), bits)
+        lut = lcd.lcd_build_lut(to_dev(layer["codebook"]), bits)
+        x, s = to_dev(layer["x"]), to_dev(layer["s"])
+        y = torch.full((M, N), float("nan"), dtype=torch.float16, device="cuda")
+        problems.append((packed, lut, x, s, y, N))
+        singles.append(lcd.lcd_lut_gemm(packed, lut, x, s, N, bits))
+        Y = oracle.lut_matmul(layer["codebook"], layer["idx"], layer["x"], layer["s"], bits)
+        assert oracle.parity_errors(singles[-1].cpu().numpy(), Y)["max_rel_floored"] <= TOL
+    lcd.lcd_lut_gemm_grouped(problems, bits)
+    torch.cuda.synchronize()
+    for p, single in zip(problems, singles):
+        assert torch.equal(p[4], single)
+
