@@ -70,6 +70,21 @@ MUTATIONS = [
     ("binary32 quantiser clips symmetrically",
      "float lo = -ldexpf(1.0f, b - 1), hi = ldexpf(1.0f, b - 1) - 1.0f;",
      "float lo = -ldexpf(1.0f, b - 1) + 1.0f, hi = ldexpf(1.0f, b - 1) - 1.0f;"),
+    ("smoothed input multiplied instead of divided",
+     "xs[(size_t)m * K + k] = oracle_half_to_double(x[(size_t)m * K + k]) / (double)s[k];",
+     "xs[(size_t)m * K + k] = oracle_half_to_double(x[(size_t)m * K + k]) * (double)s[k];"),
+    ("smoothed input takes the factor of the token, not of the channel",
+     "xs[(size_t)m * K + k] = oracle_half_to_double(x[(size_t)m * K + k]) / (double)s[k];",
+     "xs[(size_t)m * K + k] = oracle_half_to_double(x[(size_t)m * K + k]) / (double)s[m];"),
+    ("smoothed input divides in single precision",
+     "xs[(size_t)m * K + k] = oracle_half_to_double(x[(size_t)m * K + k]) / (double)s[k];",
+     "xs[(size_t)m * K + k] = (float)oracle_half_to_double(x[(size_t)m * K + k]) / s[k];"),
+    ("dequantised weight from the codebook of row 0",
+     "What[(size_t)n * K + k] = oracle_half_to_double(codebook[(size_t)n * ncent + c]);",
+     "What[(size_t)n * K + k] = oracle_half_to_double(codebook[c]);"),
+    ("dequantised weights written transposed",
+     "What[(size_t)n * K + k] = oracle_half_to_double(codebook[(size_t)n * ncent + c]);",
+     "What[((size_t)k * N + n) % ((size_t)N * K)] = oracle_half_to_double(codebook[(size_t)n * ncent + c]);"),
     ("dequantised weight of the wrong centroid",
      "What[(size_t)n * K + k] = oracle_half_to_double(codebook[(size_t)n * ncent + c]);",
      "What[(size_t)n * K + k] = oracle_half_to_double(codebook[(size_t)n * ncent + (c ^ 1)]);"),

@@ -183,6 +183,45 @@ def test_row_dependence(bits):
     assert changed[4] and changed.sum() == 1
 
 
+def test_smoothed_input_power_of_two_and_exact_rational():
+    # xs[m][k] = x[m][k] / s[k] (Sec. 3.4).  A power-of-two s only changes the exponent, so the result
+    # is exact; any other s must give the double nearest to the exact quotient.  M != K and a different
+    # s in every column, so a factor taken from the wrong axis or a product instead of a quotient shows.
+    rng = np.random.default_rng(12)
+    M, K = 3, 11
+    x = (rng.standard_normal((M, K)) * 4).astype(np.float16)
+    j = np.arange(K) - 5
+    s2 = (2.0 ** j).astype(np.float32)
+    xs = oracle.smooth(x, s2)
+    assert xs.shape == (M, K) and np.array_equal(xs, x.astype(np.float64) * (2.0 ** -j.astype(np.float64))[None, :])
+    s = (0.3 + rng.random(K) * 5).astype(np.float32)
+    xs = oracle.smooth(x, s)
+    for m in range(M):
+        for k in range(K):
+            exact = Fraction(float(x[m, k])) / Fraction(float(s[k]))
+            assert abs(Fraction(float(xs[m, k])) - exact) <= abs(exact) * Fraction(1, 2 ** 53)
+    # hand-worked: 3 / 4 = 0.75, -5 / 0.5 = -10, 1 / 3 -> the double next to one third
+    got = oracle.smooth(np.array([[3.0, -5.0, 1.0]], dtype=np.float16), np.array([4.0, 0.5, 3.0], dtype=np.float32))
+    assert got.tolist() == [[0.75, -10.0, 1.0 / 3.0]]
+
+
+@pytest.mark.parametrize("bits", [2, 3, 4])
+def test_dequantised_weights_are_a_gather(bits):
+    # What[n][k] = C[n][idx[n][k]] (Sec. 3.2: a clustered weight is its centroid): numpy's own gather,
+    # on a non-square matrix with per-row codebooks, and one entry by hand
+    rng = np.random.default_rng(40 + bits)
+    N, K = 7, 13
+    codebook = (rng.standard_normal((N, 1 << bits)) * 0.02).astype(np.float16)
+    idx = rng.integers(0, 1 << bits, size=(N, K), dtype=np.uint8)
+    What = oracle.dequant(codebook, idx, bits)
+    assert What.shape == (N, K)
+    assert np.array_equal(What, np.take_along_axis(codebook.astype(np.float64), idx.astype(np.int64), axis=1))
+    assert What[5, 9] == float(codebook[5, idx[5, 9]])
+    bad = idx.copy(); bad[2, 3] = 1 << bits
+    with pytest.raises(ValueError):
+        oracle.dequant(codebook, bad, bits)
+
+
 def test_index_out_of_range_is_rejected():
     codebook, idx, x, s = small_case(2, 1, 4, 8, 3)
     idx[1, 2] = 4
