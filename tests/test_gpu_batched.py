@@ -5,7 +5,7 @@ import pytest
 import oracle
 import synth
 import paper_2506_12038_amd as lcd
-from gpu_common import TOL, check_layer, run_hip, to_dev
+from gpu_common import TOL, assert_parity, check_layer, config_layers, run_hip, to_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -49,52 +49,69 @@ def test_batched_one_hot_rows_are_exact(bits, entry):
             assert np.array_equal(y[m], layer["codebook"][np.arange(N), layer["idx"][:, k]]), (m, k)
 
 
-def _sampled_check(cfg, mid, spec, bits, M, entry, rows=192, toks=24):
-    """Full-size matrix on the GPU; the oracle evaluates a seeded sample of rows and tokens."""
-    layer = synth.make_layer(cfg, mid, spec.N, spec.K, bits, M)
-    y = run_hip(layer, bits, entry)
-    rng = np.random.default_rng(99 + mid)
-    rs = np.sort(rng.choice(spec.N, size=min(rows, spec.N), replace=False))
-    rs[-1] = spec.N - 1; rs[0] = 0
-    ms = np.sort(rng.choice(M, size=min(toks, M), replace=False))
-    Y = oracle.lut_matmul(layer["codebook"][rs], layer["idx"][rs], layer["x"][ms], layer["s"], bits)
-    Yfull_rows = y[np.ix_(ms, rs)]
-    # rms over the sampled rows stands in for the row rms (rows are i.i.d. by construction)
-    err = oracle.parity_errors(Yfull_rows, Y)
-    assert np.all(np.isfinite(y.astype(np.float32)))
-    assert err["max_rel_floored"] <= TOL, (spec, err)
-    return err
+def _grouped_outputs(cfg_index, M, entry):
+    """All matrices of a config through ONE grouped call (the launch configuration bench.py times);
+    returns [(spec, layer, y)] with y as numpy.  Outputs start as NaN."""
+    import torch
+    config = synth.get_config(cfg_index)
+    problems, keep = [], []
+    for mid, spec, layer in config_layers(cfg_index, M, distinct_shapes_only=False):
+        packed = lcd.lcd_pack_indices(to_dev(layer["idx"]), config.bits)
+        lut = lcd.lcd_build_lut(to_dev(layer["codebook"]), config.bits)
+        y = torch.full((M, spec.N), float("nan"), dtype=torch.float16, device="cuda")
+        problems.append((packed, lut, to_dev(layer["x"]), to_dev(layer["s"]), y, spec.N))
+        keep.append((spec, layer))
+    (lcd.lcd_lut_gemv_grouped if entry == "gemv" else lcd.lcd_lut_gemm_grouped)(problems, config.bits)
+    torch.cuda.synchronize()
+    return [(spec, layer, p[4].cpu().numpy()) for (spec, layer), p in zip(keep, problems)]
 
 
-def test_config2_batched_decode_full_size():
-    config = synth.get_config(2)
+def _check_every_output(cfg_index, M):
+    """Every output of every matrix of a decode config against the oracle: the grouped call over the
+    whole set, and the single call on the first matrix of each shape."""
+    bits = synth.get_config(cfg_index).bits
     seen = set()
-    for mid, spec in config.matrices():
-        if (spec.N, spec.K) in seen:
-            continue
-        seen.add((spec.N, spec.K))
-        _sampled_check(2, mid, spec, config.bits, 16, "gemv")
+    for spec, layer, y in _grouped_outputs(cfg_index, M, "gemv"):
+        Y = oracle.lut_matmul(layer["codebook"], layer["idx"], layer["x"], layer["s"], bits)
+        assert_parity(y, Y, what=("grouped call", cfg_index, M, spec))
+        if (spec.N, spec.K) not in seen:
+            seen.add((spec.N, spec.K))
+            assert_parity(run_hip(layer, bits, "gemv"), Y, what=("single call", cfg_index, M, spec))
 
 
-def test_config3_prefill_full_size():
-    config = synth.get_config(3)
-    seen = set()
-    for mid, spec in config.matrices():
-        if (spec.N, spec.K) in seen:
-            continue
-        seen.add((spec.N, spec.K))
-        _sampled_check(3, mid, spec, config.bits, 2048, "gemm", rows=96, toks=16)
+def test_config2_batched_decode_full_size_every_output():
+    _check_every_output(2, 16)
 
 
 @pytest.mark.parametrize("M", [1, 8])
-def test_config4_70b_mlp_full_size(M):
-    config = synth.get_config(4)
-    seen = set()
-    for mid, spec in config.matrices():
-        if (spec.N, spec.K) in seen:
-            continue
-        seen.add((spec.N, spec.K))
-        _sampled_check(4, mid, spec, config.bits, M, "gemv", rows=128, toks=8)
+def test_config4_70b_mlp_full_size_every_output(M):
+    _check_every_output(4, M)
+
+
+def _check_prefill_sample(spec, layer, y, bits, mid, M):
+    """Prefill outputs are too many for the oracle (2048 tokens): every row for 8 sampled tokens and
+    every token for 96 sampled rows, both with the first and the last one; finite everywhere."""
+    assert np.all(np.isfinite(y.astype(np.float32))), spec
+    rng = np.random.default_rng(99 + mid)
+    ms = np.sort(rng.choice(M, size=8, replace=False)); ms[0] = 0; ms[-1] = M - 1
+    Y = oracle.lut_matmul(layer["codebook"], layer["idx"], layer["x"][ms], layer["s"], bits)
+    assert_parity(y[ms], Y, what=("all rows of sampled tokens", spec))
+    rs = np.sort(rng.choice(spec.N, size=96, replace=False)); rs[0] = 0; rs[-1] = spec.N - 1
+    Y = oracle.lut_matmul(layer["codebook"][rs], layer["idx"][rs], layer["x"], layer["s"], bits)
+    # rms over the sampled rows stands in for the row rms (rows are i.i.d. by construction)
+    assert_parity(y[:, rs], Y, what=("all tokens of sampled rows", spec))
+
+
+def test_config3_prefill_full_size_single_calls():
+    bits, M = synth.get_config(3).bits, 2048
+    for mid, spec, layer in config_layers(3, M, distinct_shapes_only=True):
+        _check_prefill_sample(spec, layer, run_hip(layer, bits, "gemm"), bits, mid, M)
+
+
+def test_config3_prefill_full_size_grouped_call():
+    bits, M = synth.get_config(3).bits, 2048
+    for mid, (spec, layer, y) in enumerate(_grouped_outputs(3, M, "gemm")):
+        _check_prefill_sample(spec, layer, y, bits, mid, M)
 
 
 @pytest.mark.parametrize("bits,ncent", [(3, 5), (3, 6), (4, 10), (4, 13)])

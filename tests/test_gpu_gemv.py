@@ -5,7 +5,7 @@ import pytest
 import oracle
 import synth
 import paper_2506_12038_amd as lcd
-from gpu_common import TOL, check_layer, run_hip, to_dev
+from gpu_common import TOL, assert_parity, check_layer, config_layers, run_hip, to_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -97,25 +97,24 @@ def test_grouped_launch_matches_oracle_and_single_calls(bits, M):
         assert torch.equal(y, single)  # same kernel, same reduction order: bit-identical
 
 
-def test_grouped_config1_full_size_sampled():
+@pytest.mark.parametrize("cfg", [0, 1])
+def test_grouped_config_full_size_every_output(cfg):
+    # the launch configuration bench.py times (config 1: the whole 7B set in one grouped call), every
+    # output of every matrix against the oracle, outputs NaN before the launch
     import torch
-    config = synth.get_config(1)
+    config = synth.get_config(cfg)
     problems, layers = [], []
-    for mid, spec in config.matrices():
-        layer = synth.make_layer(1, mid, spec.N, spec.K, config.bits, 1)
+    for mid, spec, layer in config_layers(cfg, 1, distinct_shapes_only=False):
         packed = lcd.lcd_pack_indices(to_dev(layer["idx"]), config.bits)
         lut = lcd.lcd_build_lut(to_dev(layer["codebook"]), config.bits)
-        y = torch.empty((1, spec.N), dtype=torch.float16, device="cuda")
+        y = torch.full((1, spec.N), float("nan"), dtype=torch.float16, device="cuda")
         problems.append((packed, lut, to_dev(layer["x"]), to_dev(layer["s"]), y, spec.N))
-        rs = np.sort(np.random.default_rng(mid).choice(spec.N, size=256, replace=False))
-        rs[0] = 0; rs[-1] = spec.N - 1
-        layers.append((rs, oracle.lut_matmul(layer["codebook"][rs], layer["idx"][rs], layer["x"], layer["s"], config.bits)))
-        del layer
+        layers.append((spec, layer))
     lcd.lcd_lut_gemv_grouped(problems, config.bits)
     torch.cuda.synchronize()
-    for (packed, lut, x, s, y, N), (rs, Y) in zip(problems, layers):
-        err = oracle.parity_errors(y.cpu().numpy()[:, rs], Y)
-        assert err["max_rel_floored"] <= TOL, err
+    for p, (spec, layer) in zip(problems, layers):
+        Y = oracle.lut_matmul(layer["codebook"], layer["idx"], layer["x"], layer["s"], config.bits)
+        assert_parity(p[4].cpu().numpy(), Y, what=(cfg, spec))
 
 
 @pytest.mark.parametrize("bits,M,quantised", [(3, 1, False), (2, 16, False), (2, 16, True), (4, 3, True), (3, 1, True)])
