@@ -142,6 +142,24 @@ lcd_status lcd_lut_gemm(const void *packed, const void *lut, const uint16_t *x, 
                         uint16_t *y, int M, int N, int K, int bits,
                         void *workspace, size_t workspace_bytes, void *stream);
 
+/* ---- decode for callers that cannot allocate -------------------------------------------------- *
+ *
+ * For code under HIP graph capture, tight serving loops and harnesses that forbid hipMalloc: the
+ * product of lcd_lut_gemv (same arguments, same result bit for bit) with no workspace argument.
+ * The scratch the several-token route needs (the smoothed activations, M*K fp16 numbers) lives in a
+ * device array inside the library, 1 MiB per GPU, held until the process ends; the call itself
+ * allocates and frees nothing, on the host or on the device.
+ *   - Limit: 1 <= M <= 16 and M*K <= 16*32768 (so K <= 32768 at 16 tokens); beyond it
+ *     LCD_ERR_SIZE and nothing is launched.
+ *   - Every call on a GPU uses that GPU's one array: calls that may overlap in time on one GPU
+ *     (different streams, different threads) race and must be ordered by the caller.  Nothing in the
+ *     array has to start at zero; each call overwrites what it reads.
+ *   - The first call on a device looks up the array's device address (once per device, with that
+ *     device current); make that call outside stream capture.
+ */
+lcd_status lcd_lut_gemv_noalloc(const void *packed, const void *lut, const uint16_t *x, const float *s,
+                                uint16_t *y, int M, int N, int K, int bits, void *stream);
+
 /* ---- decode with the paper's input transformation in front (Sec. 4.1, Eq. 10-11, b = 8) ---- *
  *
  * The activations are smoothed and quantised to INT8 codes in one step, as the paper's own

@@ -19,7 +19,7 @@ EXPORTS = (
     "lcd_version", "lcd_layout_revision", "lcd_last_error_string", "lcd_status_string",
     "lcd_packed_bytes", "lcd_lut_bytes", "lcd_workspace_bytes",
     "lcd_pack_indices", "lcd_unpack_indices", "lcd_pack_indices_host", "lcd_unpack_indices_host",
-    "lcd_build_lut", "lcd_lut_gemv", "lcd_lut_gemm", "lcd_lut_gemv_q8",
+    "lcd_build_lut", "lcd_lut_gemv", "lcd_lut_gemm", "lcd_lut_gemv_q8", "lcd_lut_gemv_noalloc",
     "lcd_workspace_bytes_grouped", "lcd_lut_gemv_grouped", "lcd_lut_gemv_q8_grouped", "lcd_lut_gemv_grouped_mixed",
     "lcd_workspace_bytes_gemm_grouped", "lcd_lut_gemm_grouped",
     "lcd_assign_indices", "lcd_cluster_counts", "lcd_merge_closest",
@@ -74,6 +74,8 @@ def load_library():
         fn = getattr(lib, name)
         fn.restype = ci
         fn.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, vp, sz, vp]
+    lib.lcd_lut_gemv_noalloc.restype = ci
+    lib.lcd_lut_gemv_noalloc.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, vp]
     lib.lcd_lut_gemv_q8.restype = ci
     lib.lcd_lut_gemv_q8.argtypes = [vp, vp, vp, vp, ctypes.c_float, vp, ci, ci, ci, ci, vp, sz, vp]
     lib.lcd_workspace_bytes_grouped.restype = sz
@@ -217,6 +219,17 @@ def _product(fn_name, packed, lut, x, s, N, bits, y, workspace, stream):
 def lcd_lut_gemv(packed, lut, x, s, N: int, bits: int, y=None, workspace=None, stream=None):
     """Decode path, x: CUDA float16 [M<=16, K] -> y float16 [M, N]."""
     return _product("lcd_lut_gemv", packed, lut, x, s, N, bits, y, workspace, stream)
+
+
+def lcd_lut_gemv_noalloc(packed, lut, x, s, N: int, bits: int, y, stream=None):
+    """lcd_lut_gemv without a workspace: the library's own static device array serves as scratch.
+    The caller brings y (this wrapper allocates nothing either)."""
+    import torch
+    M, K = x.shape
+    _check(load_library().lcd_lut_gemv_noalloc(
+        _dev(packed, torch.uint8, "packed"), _dev(lut, torch.uint8, "lut"), _dev(x, torch.float16, "x"),
+        _dev(s, torch.float32, "s"), _dev(y, torch.float16, "y"), M, N, K, bits, _stream(stream)))
+    return y
 
 
 def lcd_lut_gemv_q8(packed, lut, x, s, s_q: float, N: int, bits: int, y=None, workspace=None, stream=None):

@@ -23,6 +23,7 @@
 #include <hip/hip_runtime.h>
 #include <type_traits>
 #include <algorithm>
+#include <mutex>
 #include "lcd_internal.h"
 #include "lcd_device.h"
 
@@ -816,7 +817,7 @@ static int num_cus()
 }
 
 // One launch for a group of decode problems: the bucket kernel for one token, the tokens kernel for 2..16.
-int launch_decode_group(const GroupItem *items, int count, int M, int bits, void *workspace, void *stream_)
+int launch_decode_group(const GroupItem *items, int count, int M, int bits, void *workspace, void *stream_, bool force_prepass)
 {
     hipStream_t stream = (hipStream_t)stream_;
     BucketBatch batch{};
@@ -828,7 +829,7 @@ int launch_decode_group(const GroupItem *items, int count, int M, int bits, void
     const uint16_t *codes[kMaxGroup] = {};
     int widest = 0;
     for (int i = 0; i < count; ++i) widest = items[i].K > widest ? items[i].K : widest;
-    if (tokens_path && (items[0].act_scale != 0.0f || widest >= kPrepassMinK)) {
+    if (tokens_path && (force_prepass || items[0].act_scale != 0.0f || widest >= kPrepassMinK)) {
         TransformBatch qb{};
         size_t offset = 0;
         int max_k = 0;
@@ -979,11 +980,48 @@ int launch_decode_group(const GroupItem *items, int count, int M, int bits, void
     return (int)hipGetLastError();
 }
 
+// ---- scratch for callers that cannot allocate ---------------------------------------------------
+// lcd_lut_gemv_noalloc keeps the transformed activations (at most 16 tokens x kStaticScratchCols
+// columns, fp16) in this file-scope device array instead of a workspace the caller brings.  Every GPU
+// holds its own copy at its own address; the array's name is only a host-side handle, so the device
+// address is asked for once per device and kernels are given that address.
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+static void *g_scratch_ptr[kMaxDevices] = {};
+static std::mutex g_scratch_mutex;
+
+// Device address of the current device's scratch array (hipError_t as int; 0 = success).
+static int static_scratch(void **out)
+{
+    int dev = 0;
+    if (hipError_t e = hipGetDevice(&dev)) return (int)e;
+    if (dev < 0 || dev >= kMaxDevices) return (int)hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch))) return (int)e;
+        if (!p) return (int)hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return 0;
+}
+
+int launch_gemv_noalloc(const void *packed, const void *lut, const uint16_t *x, const float *s, uint16_t *y,
+                        int M, int N, int K, int bits, void *stream_)
+{
+    void *ws = nullptr;
+    if (int e = static_scratch(&ws)) return e;
+    GroupItem it{packed, lut, x, s, y, N, K, 0.0f};
+    // the activations always go through the scratch array on the several-token route, whatever K is
+    return launch_decode_group(&it, 1, M, bits, ws, stream_, true);
+}
+
 int launch_gemv(const void *packed, const void *lut, const uint16_t *x, const float *s, uint16_t *y,
                 int M, int N, int K, int bits, float act_scale, void *workspace, void *stream_)
 {
     GroupItem it{packed, lut, x, s, y, N, K, act_scale};
-    return launch_decode_group(&it, 1, M, bits, workspace, stream_);
+    return launch_decode_group(&it, 1, M, bits, workspace, stream_, false);
 }
 
 }  // namespace lcd

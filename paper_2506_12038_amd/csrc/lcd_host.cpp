@@ -205,8 +205,8 @@ lcd_status lcd_build_lut(const uint16_t *codebook, int N, int bits, void *lut, s
     return LCD_OK;
 }
 
-static lcd_status check_product(const void *packed, const void *lut, const uint16_t *x, const float *s, uint16_t *y,
-                                int M, int N, int K, int bits, void *workspace, size_t workspace_bytes)
+static lcd_status check_operands(const void *packed, const void *lut, const uint16_t *x, const float *s, uint16_t *y,
+                                 int M, int N, int K, int bits)
 {
     if (lcd_status st = check_shape(N, K, bits)) return st;
     if (M < 1) return fail(LCD_ERR_BAD_M, "M=%d must be >= 1", M);
@@ -215,6 +215,13 @@ static lcd_status check_product(const void *packed, const void *lut, const uint1
     if (lcd_status st = check_aligned(x, "x")) return st;
     if (lcd_status st = check_aligned(s, "s")) return st;
     if (lcd_status st = check_aligned(y, "y")) return st;
+    return LCD_OK;
+}
+
+static lcd_status check_product(const void *packed, const void *lut, const uint16_t *x, const float *s, uint16_t *y,
+                                int M, int N, int K, int bits, void *workspace, size_t workspace_bytes)
+{
+    if (lcd_status st = check_operands(packed, lut, x, s, y, M, N, K, bits)) return st;
     if (lcd_status st = check_aligned(workspace, "workspace")) return st;
     const size_t need = lcd_workspace_bytes(M, N, K, bits);
     if (workspace_bytes < need) return fail(LCD_ERR_SIZE, "workspace_bytes=%zu < %zu", workspace_bytes, need);
@@ -227,6 +234,20 @@ lcd_status lcd_lut_gemv(const void *packed, const void *lut, const uint16_t *x, 
     if (M > 16) return fail(LCD_ERR_BAD_M, "lcd_lut_gemv: M=%d > 16 (use lcd_lut_gemm)", M);
     if (lcd_status st = check_product(packed, lut, x, s, y, M, N, K, bits, workspace, workspace_bytes)) return st;
     if (int e = launch_gemv(packed, lut, x, s, y, M, N, K, bits, 0.0f, workspace, stream))
+        return fail(LCD_ERR_HIP, "gemv launch: %s", hip_error_name(e));
+    return LCD_OK;
+}
+
+lcd_status lcd_lut_gemv_noalloc(const void *packed, const void *lut, const uint16_t *x, const float *s, uint16_t *y,
+                                int M, int N, int K, int bits, void *stream)
+{
+    if (M > 16) return fail(LCD_ERR_BAD_M, "lcd_lut_gemv_noalloc: M=%d > 16", M);
+    if (lcd_status st = check_operands(packed, lut, x, s, y, M, N, K, bits)) return st;
+    const size_t need = decode_codes_bytes(M, K);
+    if (need > kStaticScratchBytes)
+        return fail(LCD_ERR_SIZE, "lcd_lut_gemv_noalloc: M*K=%d*%d fp16 activations (%zu bytes) exceed the library's static scratch of %zu bytes",
+                    M, K, need, kStaticScratchBytes);
+    if (int e = launch_gemv_noalloc(packed, lut, x, s, y, M, N, K, bits, stream))
         return fail(LCD_ERR_HIP, "gemv launch: %s", hip_error_name(e));
     return LCD_OK;
 }

@@ -31,7 +31,9 @@ struct GroupItem {
 };
 // one launch for `count` decode problems (1 <= M <= 16 tokens each)
 // (workspace: decode_codes_bytes(M, K) per item, in item order, when M > 1 and act_scale != 0)
-int launch_decode_group(const GroupItem *items, int count, int M, int bits, void *workspace, void *stream);
+// force_prepass: the activations are transformed ahead of the product (into the workspace) whenever the
+// several-token kernel runs, not only where that is the faster route
+int launch_decode_group(const GroupItem *items, int count, int M, int bits, void *workspace, void *stream, bool force_prepass = false);
 inline size_t decode_codes_bytes(int M, int K) { return ((size_t)M * K * 2 + 255) / 256 * 256; }
 
 // Launchers implemented in the .hip files.  All return hipError_t as int (0 = success).
@@ -40,6 +42,11 @@ int launch_unpack(const void *packed, int N, int K, int bits, uint8_t *idx, void
 int launch_build_lut(const uint16_t *codebook, int N, int bits, void *lut, void *stream);
 int launch_gemv(const void *packed, const void *lut, const uint16_t *x, const float *s, uint16_t *y,
                 int M, int N, int K, int bits, float act_scale, void *workspace, void *stream);
+// the same product with the library's own static device array as the workspace (no allocation anywhere)
+constexpr int kStaticScratchCols = 32768;                                   // largest K at 16 tokens
+constexpr size_t kStaticScratchBytes = (size_t)16 * kStaticScratchCols * 2;  // 1 MiB per GPU
+int launch_gemv_noalloc(const void *packed, const void *lut, const uint16_t *x, const float *s, uint16_t *y,
+                        int M, int N, int K, int bits, void *stream);
 int launch_gemm(const void *packed, const void *lut, const uint16_t *x, const float *s, uint16_t *y,
                 int M, int N, int K, int bits, void *workspace, const GemmPlan &plan, void *stream);
 int launch_assign(const uint16_t *w, const uint16_t *codebook, int ncent, int N, int K, int bits, uint8_t *idx, void *stream);

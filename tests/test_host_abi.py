@@ -135,6 +135,13 @@ def test_device_entry_points_validate_before_launch():
     assert st(lib.lcd_lut_gemv_q8(a, a, a, a, -1.0, a, 1, 16, 256, 2, a, big, None)) == b"LCD_ERR_BAD_SCALE"
     assert st(lib.lcd_lut_gemv_q8(a, a, a, a, 0.5, a, 17, 16, 256, 2, a, big, None)) == b"LCD_ERR_BAD_M"
     assert st(lib.lcd_lut_gemv_q8(a, None, a, a, 0.5, a, 1, 16, 256, 2, a, big, None)) == b"LCD_ERR_NULL"
+    # the allocation-free variant: its static scratch holds 16 x 32768 fp16 activations
+    assert st(lib.lcd_lut_gemv_noalloc(a, a, a, a, a, 17, 16, 256, 2, None)) == b"LCD_ERR_BAD_M"
+    assert st(lib.lcd_lut_gemv_noalloc(a, a, a, a, a, 16, 16, 33024, 2, None)) == b"LCD_ERR_SIZE"
+    assert b"static scratch" in lib.lcd_last_error_string()
+    assert st(lib.lcd_lut_gemv_noalloc(a, a, a, a, a, 9, 16, 65536, 3, None)) == b"LCD_ERR_SIZE"
+    assert st(lib.lcd_lut_gemv_noalloc(a, a, odd, a, a, 2, 16, 256, 2, None)) == b"LCD_ERR_ALIGN"
+    assert st(lib.lcd_lut_gemv_noalloc(a, a, a, a, None, 2, 16, 256, 2, None)) == b"LCD_ERR_NULL"
     assert st(lib.lcd_lut_gemm(a, a, None, a, a, 64, 16, 256, 3, a, big, None)) == b"LCD_ERR_NULL"
     assert st(lib.lcd_lut_gemm(a, a, a, a, a, 64, 16, 256, 1, a, big, None)) == b"LCD_ERR_BAD_BITS"
 
