@@ -5,7 +5,7 @@
  *
  *     Y[m][n] = sum_k ( X[m][k] / s[k] ) * C[n][ idx[n][k] ]        m < M, n < N, k < K
  *
- *   idx[n][k]  2- or 3-bit index of the centroid that weight (n,k) was clustered to
+ *   idx[n][k]  2-, 3- or 4-bit index of the centroid that weight (n,k) was clustered to
  *              (Sec. 3.2: a clustered weight W' is its centroid);
  *   C[n][c]    per-output-row codebook of 2^bits fp16 centroids; the centroids already
  *              contain the offline smoothing of the weights (Sec. 3.4: weights are scaled by
@@ -24,8 +24,12 @@
  *   - Arguments are validated on the host before anything is launched; a failed call
  *     launches nothing and returns a status != LCD_OK.  lcd_last_error_string() then holds a
  *     message (thread-local).
- *   - Shapes: bits in {2,3};  N % 16 == 0;  K % 256 == 0;  N, K >= 1 tile.
+ *   - Shapes: bits in {2,3,4};  N % 16 == 0;  K % 256 == 0;  N, K >= 1 tile.
  *   - Two calls that share a workspace buffer must be ordered on one stream.
+ *   - One device per process, and product calls from one thread at a time: the launchers keep a
+ *     few host-side statics (the device's compute-unit count, "kernel attributes already set"
+ *     flags) per process, not per device, and do not lock them.  The per-thread state is the error
+ *     string and the remembered workgroup split of the last grouped decode call.
  */
 #ifndef LCD_H
 #define LCD_H
@@ -234,20 +238,21 @@ lcd_status lcd_lut_gemm_grouped(const lcd_gemv_problem *problems /*HOST*/, int c
 /* ---- clustering-side steps that need no calibration data (offline) ------------------------ *
  *
  * Codebooks here are per output row, fp16 [N][2^bits], of which the first `ncent` entries are in
- * use and STRICTLY ASCENDING (the paper sorts the centroids, Sec. 3.3); the rest is ignored.
+ * use and STRICTLY ASCENDING (the paper sorts the centroids, Sec. 3.2); the rest is ignored.
  *
  * lcd_assign_indices: idx[n][k] = the centroid of row n nearest to w[n][k] (w: DEVICE fp16 [N][K],
- *   e.g. the smoothed weights).  This is the state the reclassification rule of Sec. 3.3 (Eq. 6)
+ *   e.g. the smoothed weights).  This is the state the reclassification rule of Sec. 3.2 (Eq. 6)
  *   maintains: a weight leaves its cluster once it crosses half the gap to a neighbouring
  *   centroid.  A weight exactly half way stays with the lower centroid; NaN goes to centroid 0.
  *   The decision is exact (no rounding anywhere).  Output as lcd_pack_indices takes it.
  * lcd_cluster_counts: counts[n][i] = number of k with idx[n][k] == i, for i < 2^bits
- *   (DEVICE uint32 [N][2^bits]; the cluster sizes of Sec. 3.5).  idx must be < 16.
- * lcd_merge_closest: Sec. 3.5, Eq. 8, per row: the two closest centroids a, a+1 (smallest gap,
+ *   (DEVICE uint32 [N][2^bits]; the cluster sizes of Sec. 3.3).  idx must be < 16.
+ * lcd_merge_closest: Sec. 3.3, Eq. 8, per row: the two closest centroids a, a+1 (smallest gap,
  *   the lowest pair on equal gaps) are replaced by their mean weighted by their cluster sizes --
  *   each centroid by its OWN count, as the text defines it (the printed formula has the counts
- *   crossed), the plain mean if both clusters are empty -- computed in fp64 and rounded to fp16
- *   (at most one fp16 step from the correctly rounded value).  codebook_out gets ncent-1 ascending
+ *   crossed), the plain mean if both clusters are empty -- correctly rounded to fp16, ties to even
+ *   (the decision between the two neighbouring fp16 numbers is taken in exact integer arithmetic;
+ *   centroids must be finite).  codebook_out gets ncent-1 ascending
  *   entries followed by zeros, merged[n] = a (DEVICE uint8 [N]), idx_out the re-numbered indices
  *   (idx - 1 above a; idx_out may be idx itself; codebook_out must not be codebook).
  * Errors: as above; ncent outside 1..2^bits (2..2^bits for the merge) is LCD_ERR_SIZE.

@@ -15,10 +15,10 @@ from .lcd_oracle import (
     num_threads,
 )
 from .metrics import parity_errors
-from .cluster_oracle import assign_nearest, cluster_counts, merge_closest
+from .cluster_oracle import assign_nearest, cluster_counts, merge_closest, merge_closest_stored, round_to_half
 
 __all__ = [
     "build_oracle", "half_to_double", "dequant", "smooth", "lut_matmul", "bucket_matmul",
     "input_transform", "quantised_lut_matmul", "num_threads", "parity_errors",
-    "assign_nearest", "cluster_counts", "merge_closest",
+    "assign_nearest", "cluster_counts", "merge_closest", "merge_closest_stored", "round_to_half",
 ]

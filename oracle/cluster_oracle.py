@@ -3,11 +3,11 @@
 Plain numpy in fp64 (every fp16 input converts exactly), no blocking, no shortcuts:
 
 * nearest-centroid assignment -- a weight belongs to the cluster whose centroid is closest.  This is
-  the state the reclassification rule of Sec. 3.3 (Eq. 6) preserves: a weight changes cluster once
+  the state the reclassification rule of Sec. 3.2 (Eq. 6) preserves: a weight changes cluster once
   it crosses half the distance to a neighbouring centroid, i.e. once that neighbour is the nearer
   one.  A weight exactly half way between two centroids has crossed nothing and stays with the lower.
-* cluster sizes n_i (the "number of points in each cluster" of Sec. 3.5).
-* merge of the two closest centroids into their count-weighted mean (Sec. 3.5, Eq. 8).  The printed
+* cluster sizes n_i (the "number of points in each cluster" of Sec. 3.3).
+* merge of the two closest centroids into their count-weighted mean (Sec. 3.3, Eq. 8).  The printed
   formula pairs each centroid with the OTHER cluster's count; the sentence above it defines the new
   centroid as the average weighted by the clusters' own sizes, which is also the only choice that
   keeps sum_i n_i C_i (the clustered weights' total) unchanged.  That reading is taken here.
@@ -16,6 +16,8 @@ Codebooks are per output row, [N, 2**bits], of which the first `ncent` entries a
 strictly ascending.
 """
 from __future__ import annotations
+
+from fractions import Fraction
 
 import numpy as np
 
@@ -54,4 +56,44 @@ def merge_closest(codebook: np.ndarray, counts: np.ndarray, idx: np.ndarray, nce
         merged[n] = a
     idx = np.asarray(idx, dtype=np.uint8)
     new_idx = idx - (idx > merged[:, None]).astype(np.uint8)
+    return out, merged, new_idx
+
+
+def round_to_half(v: Fraction) -> np.float16:
+    """The fp16 number nearest to the rational v, ties to the even mantissa (IEEE 754 roundTiesToEven),
+    straight from the format: normal numbers are m * 2^(e-10) with 1024 <= m < 2048 and -14 <= e <= 15,
+    subnormal ones m * 2^-24 with m < 1024.  |v| must be at most the largest finite fp16 number."""
+    v = Fraction(v)
+    sign, a = (-1 if v < 0 else 1), abs(v)
+    if a > 65504:
+        raise ValueError("beyond the fp16 range")
+    e = -14
+    while e < 15 and a >= Fraction(2) ** (e + 1):
+        e += 1
+    ulp = Fraction(2) ** (e - 10)                  # spacing of fp16 numbers in [2^e, 2^(e+1)); 2^-24 below 2^-14
+    m, rem = divmod(a, ulp)
+    m = int(m)
+    if 2 * rem > ulp or (2 * rem == ulp and m % 2 == 1):
+        m += 1
+    if m == 0:
+        return np.float16(-0.0 if sign < 0 else 0.0)      # a negative value that rounds to zero keeps its sign; 0 itself is +0
+    return np.float16(float(sign * m * ulp))       # m * ulp is an fp16 number: both conversions are exact
+
+
+def merge_closest_stored(codebook: np.ndarray, counts: np.ndarray, idx: np.ndarray, ncent: int):
+    """merge_closest with the new centroid as it is stored: the weighted mean of Eq. 8 evaluated in exact
+    rational arithmetic and rounded ONCE to fp16, ties to even.  Returns (codebook fp16 [N, 2**bits],
+    merged position [N], re-numbered indices)."""
+    cb = np.asarray(codebook, dtype=np.float16)
+    _, merged, new_idx = merge_closest(cb, counts, idx, ncent)
+    cnt = np.asarray(counts)
+    out = np.zeros_like(cb)
+    for n in range(cb.shape[0]):
+        a = int(merged[n])
+        ca, cb_ = Fraction(float(cb[n, a])), Fraction(float(cb[n, a + 1]))
+        na, nb = int(cnt[n, a]), int(cnt[n, a + 1])
+        new = (na * ca + nb * cb_) / (na + nb) if na + nb > 0 else (ca + cb_) / 2
+        out[n, :a] = cb[n, :a]
+        out[n, a] = round_to_half(new)
+        out[n, a + 1:ncent - 1] = cb[n, a + 2:ncent]
     return out, merged, new_idx

@@ -1,6 +1,6 @@
 // Clustering-side kernels that need no calibration data (gfx950): nearest-centroid assignment of
-// dense fp16 weights (the state the reclassification rule of paper Sec. 3.3, Eq. 6 maintains),
-// cluster sizes, and the merge of the two closest centroids (Sec. 3.5, Eq. 8).  All of them stream
+// dense fp16 weights (the state the reclassification rule of paper Sec. 3.2, Eq. 6 maintains),
+// cluster sizes, and the merge of the two closest centroids (Sec. 3.3, Eq. 8).  All of them stream
 // the matrix once; none is a contraction, so there is no matrix-core work here.
 #include <hip/hip_runtime.h>
 #include "lcd_internal.h"
@@ -107,8 +107,51 @@ __global__ void __launch_bounds__(256) counts_kernel(const uint8_t *__restrict__
 
 // ---- merge decision: one thread per row ------------------------------------------------------------
 // The pair with the smallest gap (gaps are exact in fp64; the lowest pair on equal gaps) becomes the
-// mean of the two weighted by their cluster sizes, computed in fp64 and rounded to fp16 through
-// fp32 (at most one fp16 step from the correctly rounded value).
+// mean of the two weighted by their cluster sizes, correctly rounded to fp16 (ties to even).  A finite
+// fp16 number is an integer multiple of 2^-24 below 2^41 in magnitude and a cluster size is below 2^32,
+// so the mean is the ratio of two integers, num / den with |num| < 2^75 and den < 2^34, and "which of
+// two neighbouring fp16 numbers is nearer" is an integer comparison: no rounding happens anywhere.
+struct U128 { uint64_t hi, lo; };
+__device__ __forceinline__ U128 mul_64x64(uint64_t a, uint64_t b) { return U128{__umul64hi(a, b), a * b}; }
+__device__ __forceinline__ U128 add128(U128 a, U128 b) { const uint64_t lo = a.lo + b.lo; return U128{a.hi + b.hi + (lo < a.lo ? 1u : 0u), lo}; }
+__device__ __forceinline__ U128 sub128(U128 a, U128 b) { return U128{a.hi - b.hi - (a.lo < b.lo ? 1u : 0u), a.lo - b.lo}; }   // a >= b
+__device__ __forceinline__ int cmp128(U128 a, U128 b) { return a.hi != b.hi ? (a.hi < b.hi ? -1 : 1) : (a.lo != b.lo ? (a.lo < b.lo ? -1 : 1) : 0); }
+
+// magnitude of a finite fp16 bit pattern in units of 2^-24 (monotone in the 15-bit pattern)
+__device__ __forceinline__ uint64_t half_units(uint32_t h15)
+{
+    const uint32_t e = h15 >> 10, f = h15 & 1023u;
+    return e == 0 ? (uint64_t)f : (uint64_t)(1024u + f) << (e - 1);
+}
+
+// fp16 bit pattern nearest to (na * a + nb * b) / (na + nb), ties to even; (a + b) / 2 if na = nb = 0
+__device__ uint16_t weighted_mean_half(uint16_t a, uint16_t b, uint32_t na, uint32_t nb)
+{
+    if (na == 0 && nb == 0) na = nb = 1;
+    const U128 pa = mul_64x64(half_units(a & 0x7fffu), na), pb = mul_64x64(half_units(b & 0x7fffu), nb);
+    const bool sa = (a & 0x8000u) != 0, sb = (b & 0x8000u) != 0;
+    U128 num;
+    bool neg;
+    if (sa == sb) { num = add128(pa, pb); neg = sa; }
+    else if (cmp128(pa, pb) >= 0) { num = sub128(pa, pb); neg = sa; }
+    else { num = sub128(pb, pa); neg = sb; }
+    const uint64_t den = (uint64_t)na + nb;
+    // largest pattern h with units(h) * den <= num (the mean lies between the two centroids: h <= 0x7bff)
+    uint32_t lo = 0, hi = 0x7bffu;
+    while (lo < hi) {
+        const uint32_t mid = (lo + hi + 1) >> 1;
+        if (cmp128(mul_64x64(half_units(mid), den), num) <= 0) lo = mid; else hi = mid - 1;
+    }
+    uint32_t h = lo;
+    if (h < 0x7bffu) {   // nearer of h and h + 1: 2 * num against (units(h) + units(h + 1)) * den
+        const U128 twice = add128(num, num);
+        const int c = cmp128(twice, mul_64x64(half_units(h) + half_units(h + 1), den));
+        if (c > 0 || (c == 0 && (h & 1u))) ++h;
+    }
+    if (num.hi == 0 && num.lo == 0) neg = false;   // a mean of exactly zero is +0; a negative one that rounds to zero keeps its sign
+    return (uint16_t)(h | (neg ? 0x8000u : 0u));
+}
+
 __global__ void __launch_bounds__(256) merge_kernel(const uint16_t *__restrict__ cb_in, const uint32_t *__restrict__ counts,
                                                     uint16_t *__restrict__ cb_out, uint8_t *__restrict__ merged, int N, int ncent, int slots)
 {
@@ -121,14 +164,12 @@ __global__ void __launch_bounds__(256) merge_kernel(const uint16_t *__restrict__
         const double g = half_bits_to_double(src[i + 1]) - half_bits_to_double(src[i]);
         if (g < best) { best = g; a = i; }
     }
-    const double ca = half_bits_to_double(src[a]), cb = half_bits_to_double(src[a + 1]);
-    const double na = (double)counts[(size_t)n * slots + a], nb = (double)counts[(size_t)n * slots + a + 1];
-    const double nc = na + nb > 0.0 ? (na * ca + nb * cb) / (na + nb) : 0.5 * (ca + cb);
+    const uint16_t nc = weighted_mean_half(src[a], src[a + 1], counts[(size_t)n * slots + a], counts[(size_t)n * slots + a + 1]);
     uint16_t *dst = cb_out + (size_t)n * slots;
     for (int i = 0; i < slots; ++i) {
         uint16_t v = 0;
         if (i < a) v = src[i];
-        else if (i == a) v = __builtin_bit_cast(uint16_t, (_Float16)(float)nc);
+        else if (i == a) v = nc;
         else if (i < ncent - 1) v = src[i + 1];
         dst[i] = v;
     }

@@ -407,12 +407,6 @@ __device__ __forceinline__ void gemm_word(const WordOps &cur, WordOps &nxt, cons
 #undef LCD_GEMM_STEP
 }
 
-#ifdef LCD_TRACE
-__device__ unsigned long long *g_gemm_trace;   // debug builds only
-#define GEMM_STAMP(slot) do { if (lane == 0 && blockIdx.x == 0 && g_gemm_trace && (slot) < 120) g_gemm_trace[wave * 128 + (slot)] = __builtin_amdgcn_s_memrealtime(); } while (0)
-#else
-#define GEMM_STAMP(slot) do { } while (0)
-#endif
 
 // One output tile (row block bx, token block by) of one layer: the whole life of a workgroup.
 template <int BITS>
@@ -469,14 +463,9 @@ __device__ __forceinline__ void gemm_tile(const uint8_t *__restrict__ packed_, c
         }
     };
 
-#ifdef LCD_TRACE
-    if (lane == 0 && blockIdx.x == 0 && g_gemm_trace) { g_gemm_trace[wave * 128 + 120] = __builtin_amdgcn_s_memtime(); g_gemm_trace[wave * 128 + 121] = __builtin_amdgcn_s_memrealtime(); }
-    if (threadIdx.x == 0 && g_gemm_trace && blockIdx.x < 2048) g_gemm_trace[1024 + blockIdx.x * 2] = __builtin_amdgcn_s_memrealtime();
-#endif
     BWindow bw;
     WordOps wa, wb;          // operands of the current / next word, swapping roles word by word
     HighBits hb[kGemmPairs], hbn[kGemmPairs];
-    int stamp_base = 0;
     // Chunk c is computed from LDS stage c&1 and register set r; word D's matrix steps decode word
     // D+1, the last word's decode the first word of chunk c+1 (set rn, loaded at the top of chunk
     // c).  The copy of chunk c+1's stage is issued during word 0 (the other stage was released by
@@ -486,20 +475,15 @@ __device__ __forceinline__ void gemm_tile(const uint8_t *__restrict__ packed_, c
                        uint8_t *other_stage, const uint8_t *copy_src) {
         const uint32_t bbase = lds_address(stage) + khalf * 8 * 1024 + boff;
         const uint32_t obase = lds_address(other_stage) + khalf * 8 * 1024 + boff;
-        GEMM_STAMP(stamp_base + 0);
         gemm_word<BITS, 0, 1, true>(wa, wb, r, hb, tb, bbase, bw, copy_src, other_stage, wave, lane);
         gemm_word<BITS, 1, 2, false>(wb, wa, r, hb, tb, bbase, bw, nullptr, nullptr, wave, lane);
         gemm_word<BITS, 2, 3, false>(wa, wb, r, hb, tb, bbase, bw, nullptr, nullptr, wave, lane);
-        GEMM_STAMP(stamp_base + 1);
         high_bits(rn, hbn);
         gemm_word<BITS, 3, 0, false>(wb, wa, rn, hbn, tb, bbase, bw, nullptr, nullptr, wave, lane);
 #pragma unroll
         for (int p = 0; p < kGemmPairs; ++p) hb[p] = hbn[p];
-        GEMM_STAMP(stamp_base + 2);
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        GEMM_STAMP(stamp_base + 3);
         __syncthreads();   // the next stage has landed for every wave, and every wave is done with this one
-        GEMM_STAMP(stamp_base + 4);
         bw.w[0] = read_b<0, 0>(obase);
         bw.w[1] = read_b<0, 1>(obase);
         bw.w[2] = read_b<0, 2>(obase);
@@ -523,18 +507,12 @@ __device__ __forceinline__ void gemm_tile(const uint8_t *__restrict__ packed_, c
         const bool more1 = c + 1 < kc;
         if (more1) load_gemm_tiles<BITS>(r1, packed, t0, nt, kc, c + 1, khalf, lane);
         compute(r0, r1, lds, lds + kStageBytes, more1 ? xs_base + (size_t)(c + 1) * chunk_stride : nullptr);
-        GEMM_STAMP(stamp_base + 5); stamp_base += 6;
         if (!more1) break;
         const bool more2 = c + 2 < kc;
         if (more2) load_gemm_tiles<BITS>(r0, packed, t0, nt, kc, c + 2, khalf, lane);
         compute(r1, r0, lds + kStageBytes, lds, more2 ? xs_base + (size_t)(c + 2) * chunk_stride : nullptr);
-        GEMM_STAMP(stamp_base + 5); stamp_base += 6;
     }
 
-#ifdef LCD_TRACE
-    if (lane == 0 && blockIdx.x == 0 && g_gemm_trace) { g_gemm_trace[wave * 128 + 122] = __builtin_amdgcn_s_memtime(); g_gemm_trace[wave * 128 + 123] = __builtin_amdgcn_s_memrealtime(); }
-    if (threadIdx.x == 0 && g_gemm_trace && blockIdx.x < 2048) g_gemm_trace[1024 + blockIdx.x * 2 + 1] = __builtin_amdgcn_s_memrealtime();
-#endif
     // The two waves of a row group hold partial sums over the two halves of every chunk.  Each keeps
     // one 32-row pair and hands the other pair's four accumulators to its partner through LDS (the
     // stages are free now): per row group two 16 KiB areas, area h read by the wave with khalf == h,
@@ -594,10 +572,6 @@ __device__ __forceinline__ void gemm_tile(const uint8_t *__restrict__ packed_, c
         const int m = tb0 * 32 + tk;
         if (m < M && rows_ok) *reinterpret_cast<uint4v *>(y + (size_t)m * N + (size_t)tile_first * kTileRows + r4 * 8) = v;
     }
-#ifdef LCD_TRACE
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    if (threadIdx.x == 0 && g_gemm_trace && blockIdx.x < 1024) g_gemm_trace[2048 + blockIdx.x] = __builtin_amdgcn_s_memrealtime();
-#endif
 }
 
 // XCD-aware tile order.  Workgroup ids go round-robin over the 8 XCDs, each with its own L2.
@@ -610,9 +584,6 @@ gemm_kernel(const uint8_t *__restrict__ packed_, const uint8_t *__restrict__ lut
             uint16_t *__restrict__ y, int M, int Mpad, int N, int K, int grid_rows, int tiles_per_xcd)
 {
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];  // 2 stages x 64 KiB
-#ifdef LCD_TRACE
-    if (threadIdx.x == 0 && g_gemm_trace && blockIdx.x < 1024) g_gemm_trace[3072 + blockIdx.x] = __builtin_amdgcn_s_memrealtime();
-#endif
     const int out_tile = (int)(blockIdx.x % kXcds) * tiles_per_xcd + (int)(blockIdx.x / kXcds);
     const int total_tiles = grid_rows * (Mpad / kGemmTokens);
     if ((int)(blockIdx.x / kXcds) >= tiles_per_xcd || out_tile >= total_tiles) return;
@@ -718,8 +689,5 @@ int launch_gemm_group(const GroupItem *items, int count, int M, int bits, void *
     return (int)hipGetLastError();
 }
 
-#ifdef LCD_TRACE
-extern "C" void lcd_debug_set_gemm_trace(unsigned long long *p) { hipMemcpyToSymbol(HIP_SYMBOL(g_gemm_trace), &p, sizeof(p)); }
-#endif
 
 }  // namespace lcd

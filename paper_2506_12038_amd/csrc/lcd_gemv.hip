@@ -104,15 +104,7 @@ __device__ __forceinline__ int layer_of_workgroup(uint32_t b, uint32_t t0, uint3
 struct BucketBatch {
     BucketProblem p[kMaxGroup];
     int count;
-#ifdef LCD_TRACE
-    unsigned long long *trace;   // debug builds only: 16 timestamps per workgroup
-#endif
 };
-#ifdef LCD_TRACE
-#define LCD_STAMP(slot) do { if (threadIdx.x == 0 && batch.trace) batch.trace[blockIdx.x * 16 + (slot)] = __builtin_amdgcn_s_memrealtime(); } while (0)
-#else
-#define LCD_STAMP(slot) do { } while (0)
-#endif
 
 // Walks the (visit, segment, tile) sequence of one workgroup.  Everything is wave-uniform.
 // Padded (the tokens kernel): each (visit, segment) run is padded to a multiple of kSets steps so
@@ -212,23 +204,11 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: keeps addresses scalar
     const int q = lane >> 4, j = lane & 15, bq = lane >> 4;
-#ifdef LCD_TRACE
-    const unsigned long long tt0 = __builtin_amdgcn_s_memrealtime();
-#endif
-    LCD_STAMP(0);
 
     // which layer, which row tiles
     // (entries past the last layer hold the total, so they never count: no loop over `count`)
     const int pi = layer_of_workgroup(blockIdx.x, t0, t1, t2, t3, t4, t5, t6, t7);
-#ifdef LCD_TRACE
-    asm volatile("" :: "s"(pi));
-    const unsigned long long tt1 = __builtin_amdgcn_s_memrealtime();
-#endif
     const BucketProblem pb = batch.p[pi];
-#ifdef LCD_TRACE
-    asm volatile("" :: "s"(pb.kc), "s"(pb.nt));
-    const unsigned long long tt2 = __builtin_amdgcn_s_memrealtime();
-#endif
     const int li = (int)blockIdx.x - pb.wg_first;
     const int ta = li * pb.tiles_base + min(li, pb.tiles_extra);
     const int tb = ta + pb.tiles_base + (li < pb.tiles_extra ? 1 : 0);
@@ -260,9 +240,6 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
         s0 = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(rs_s, valid ? g * 32 : kOob, 0, 0));
         s1 = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(rs_s, valid ? g * 32 + 16 : kOob, 0, 0));
     };
-#ifdef LCD_TRACE
-    const unsigned long long tt3 = __builtin_amdgcn_s_memrealtime();
-#endif
     load_x(0, true);
     StepRegs<BITS> rs[kSets];   // always indexed by compile-time constants: four sets of registers
     issue_step_loads<BITS, true>(rs[0], pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
@@ -272,7 +249,6 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
     bool chunk_in_k[kBCH] = {};   // wave-uniform: a short last segment leaves some of the wave's chunks empty
     half16 B1;        // constant routing matrix (index c -> column c), built after the prologue
     float *my_part = part + wave * (kVisitTiles * 16);
-    LCD_STAMP(1);
 
     // bucket sums of one (tile, chunk): columns [0, NC) of a 16x16 accumulator
     auto tile_sums = [&](const StepRegs<BITS> &r) -> float4v {
@@ -427,10 +403,6 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
     // the remaining two sets of the pipeline
     issue_step_loads<BITS, false>(rs[1], pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
     issue_step_loads<BITS, TG == 2>(rs[2], pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
-    LCD_STAMP(2);
-#ifdef LCD_TRACE
-    if (threadIdx.x == 0 && batch.trace) { batch.trace[blockIdx.x * 16 + 13] = tt0; batch.trace[blockIdx.x * 16 + 14] = tt1; batch.trace[blockIdx.x * 16 + 15] = tt2; batch.trace[blockIdx.x * 16 + 12] = tt3; }
-#endif
     while (!cur.done) {
         // (no workgroup synchronisation at the start of a visit: activations and multipliers are
         // per wave; the barrier that ends a visit's epilogue protects the reuse of `part`)
@@ -464,15 +436,7 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
             }
             run_turns();
         }
-        LCD_STAMP(4);
-#ifdef LCD_TRACE
-        if (lane == 0 && batch.trace && wave < 4) batch.trace[blockIdx.x * 16 + 8 + wave] = __builtin_amdgcn_s_memrealtime();
-#ifdef LCD_TRACE_WAVES
-        if (lane == 0 && batch.trace && wave >= 4) batch.trace[blockIdx.x * 16 + 8 + wave] = __builtin_amdgcn_s_memrealtime();
-#endif
-#endif
         __syncthreads();
-        LCD_STAMP(5);
         // ---- visit epilogue: add the waves' slots in a fixed order, round once, store
         for (int e = threadIdx.x; e < (cur.v1 - cur.v0) * 16; e += NT) {
             float sum = 0.f;
@@ -482,7 +446,6 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
         }
         cursor_next_visit(cur);
         if (!cur.done) __syncthreads();   // the next visit's waves overwrite their slots
-        LCD_STAMP(6);
     }
 }
 
@@ -720,12 +683,10 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_tokens_kernel(const uint32_t
         cur.i += 4;
     };
 
-    LCD_STAMP(0);
     issue_activation_loads(0);   // they start the longest dependency chain: ahead of the tile loads
     issue_tok_loads<BITS, CH>(r0, pf, rs_packed, rs_tb, kc, wave, lane); cursor_advance(pf, nseg);
     issue_tok_loads<BITS, CH>(r1, pf, rs_packed, rs_tb, kc, wave, lane); cursor_advance(pf, nseg);
     issue_tok_loads<BITS, CH>(r2, pf, rs_packed, rs_tb, kc, wave, lane); cursor_advance(pf, nseg);
-    LCD_STAMP(1);
     if (cur.done) return;   // no row tiles (the host never launches such a workgroup); the loads above moved nothing
     finish_activations(0);
     bool primed = true;   // the first segment's activations are in place
@@ -736,17 +697,10 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_tokens_kernel(const uint32_t
                 finish_activations(cur.sg);
             }
             primed = false;
-#ifdef LCD_TRACE
-            if (cur.sg < 4) LCD_STAMP(2 + cur.sg);
-#endif
             for (cur.i = 0; cur.i < cur.steps;) four_steps();
-#ifdef LCD_TRACE
-            if (lane == 0 && batch.trace && cur.sg < 4) batch.trace[blockIdx.x * 16 + 8 + cur.sg * 2 + (wave >> 2)] = __builtin_amdgcn_s_memrealtime();
-#endif
         }
         cursor_next_visit(cur);
     }
-    LCD_STAMP(6);
 }
 
 // ---- activation transformation ahead of the tokens kernel (Sec. 4.1) -----------------------------
@@ -801,10 +755,6 @@ __global__ __launch_bounds__(kQuantThreads) void transform_kernel(TransformBatch
     }
 }
 
-#ifdef LCD_TRACE
-unsigned long long *g_trace = nullptr;
-extern "C" void lcd_debug_set_trace(unsigned long long *p) { g_trace = p; }
-#endif
 static int g_num_cus = 0;
 static int num_cus()
 {
@@ -954,9 +904,6 @@ int launch_decode_group(const GroupItem *items, int count, int M, int bits, void
     WgTable table;
     for (int i = 0; i < kMaxGroup / 2; ++i) table.t[i] = (uint32_t)wg_begin[2 * i + 1] | (uint32_t)wg_begin[2 * i + 2] << 16;
     for (int i = 0; i < count; ++i) batch.p[i].wg_first = wg_begin[i];
-#ifdef LCD_TRACE
-    batch.trace = g_trace;
-#endif
     const int NC = bits == 2 ? 4 : 8;
     size_t lds;
     const void *fn;

@@ -39,6 +39,27 @@ MUTATIONS = [
     ("re-numbering shifts the merged pair's upper index too late",
      "new_idx = idx - (idx > merged[:, None]).astype(np.uint8)",
      "new_idx = idx - (idx > merged[:, None] + 1).astype(np.uint8)"),
+    ("rounding to fp16: ties go up",
+     "if 2 * rem > ulp or (2 * rem == ulp and m % 2 == 1):",
+     "if 2 * rem >= ulp:"),
+    ("rounding to fp16: truncation",
+     "if 2 * rem > ulp or (2 * rem == ulp and m % 2 == 1):",
+     "if False:"),
+    ("rounding to fp16: subnormals get the spacing of the first normal binade wrong",
+     "e = -14\n    while e < 15",
+     "e = -15\n    while e < 15"),
+    ("stored merge rounds through binary32 first",
+     "out[n, a] = round_to_half(new)",
+     "out[n, a] = np.float16(np.float32(float(new)))"),
+    ("stored merge takes the plain mean",
+     "new = (na * ca + nb * cb_) / (na + nb) if na + nb > 0 else (ca + cb_) / 2",
+     "new = (ca + cb_) / 2"),
+    ("stored merge crosses the counts",
+     "new = (na * ca + nb * cb_) / (na + nb) if na + nb > 0 else (ca + cb_) / 2",
+     "new = (nb * ca + na * cb_) / (na + nb) if na + nb > 0 else (ca + cb_) / 2"),
+    ("stored merge drops a centroid behind the pair",
+     "out[n, a + 1:ncent - 1] = cb[n, a + 2:ncent]",
+     "out[n, a + 1:ncent - 2] = cb[n, a + 3:ncent]"),
     ("merged centroid written one slot too far",
      "row = np.concatenate([c64[n, :a], [new], c64[n, a + 2:ncent]])",
      "row = np.concatenate([c64[n, :a + 1], [new], c64[n, a + 3:ncent], [0.0]])[:ncent - 1]"),
@@ -80,7 +101,7 @@ def test_planted_mistake_is_caught(name, old, new, monkeypatch):
     assert SRC.count(old) == 1, f"mutation text not found exactly once: {name}"
     mutant = types.ModuleType("cluster_oracle_mutant")
     exec(compile(SRC.replace(old, new), "cluster_oracle_mutant", "exec"), mutant.__dict__)
-    for fn in ("assign_nearest", "cluster_counts", "merge_closest"):
+    for fn in ("assign_nearest", "cluster_counts", "merge_closest", "merge_closest_stored", "round_to_half"):
         monkeypatch.setattr(oracle, fn, getattr(mutant, fn))
     failed = _run_pins()
     assert failed, f"no pin noticed: {name}"

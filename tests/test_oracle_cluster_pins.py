@@ -146,3 +146,71 @@ def test_merge_conserves_the_clustered_weights_total(ncent, slots):
     new_vals = np.take_along_axis(new_cb, new_idx.astype(np.int64), axis=1)
     untouched = (idx != merged[:, None]) & (idx != merged[:, None] + 1)
     assert np.array_equal(old_vals[untouched], new_vals[untouched])
+
+
+def test_rounding_to_fp16_against_the_format_and_a_library_conversion():
+    from fractions import Fraction
+    # hand-worked: fp16 numbers near 1 are 2^-10 apart
+    one, u = Fraction(1), Fraction(1, 1024)
+    assert oracle.round_to_half(one + u / 2) == np.float16(1.0)                      # tie: mantissa 1024 is even
+    assert oracle.round_to_half(one + 3 * u / 2) == np.float16(1.0 + 2.0 ** -9)      # tie: up to the even 1026
+    assert oracle.round_to_half(one + u / 2 + Fraction(1, 10 ** 12)) == np.float16(1.0 + 2.0 ** -10)   # just above a tie
+    assert oracle.round_to_half(-(one + u / 2 + Fraction(1, 10 ** 12))) == np.float16(-1.0 - 2.0 ** -10)
+    assert oracle.round_to_half(Fraction(2) - u / 4) == np.float16(2.0)               # rounds up into the next binade
+    assert oracle.round_to_half(Fraction(3, 2 ** 25)) == np.float16(2.0 ** -23)       # subnormal tie 1.5 -> 2
+    assert oracle.round_to_half(Fraction(1, 2 ** 25)) == np.float16(0.0)              # subnormal tie 0.5 -> 0
+    assert oracle.round_to_half(Fraction(1, 2 ** 14) - Fraction(1, 2 ** 26)) == np.float16(2.0 ** -14)   # largest subnormal + 3/4
+    assert oracle.round_to_half(Fraction(65504)) == np.float16(65504.0)
+    with pytest.raises(ValueError):
+        oracle.round_to_half(Fraction(65505))
+    # numpy's float64 -> float16 conversion rounds once, to nearest even: it must agree on every value that
+    # a double holds exactly (the double is then the rational itself)
+    rng = np.random.default_rng(17)
+    vals = np.concatenate([rng.standard_normal(3000) * 0.05, rng.standard_normal(500) * 1e-6,
+                           rng.standard_normal(500) * 100.0,
+                           # exact ties and their neighbours: midpoints of adjacent fp16 numbers, +- one double ulp
+                           *[[m, np.nextafter(m, np.inf), np.nextafter(m, -np.inf)]
+                             for h in rng.integers(1, 0x7bff, size=300)
+                             for m in [(float(np.array([h], dtype=np.uint16).view(np.float16)[0]) +
+                                        float(np.array([h + 1], dtype=np.uint16).view(np.float16)[0])) / 2]]])
+    for v in vals:
+        assert oracle.round_to_half(Fraction(float(v))).view(np.uint16) == np.float64(v).astype(np.float16).view(np.uint16), v
+
+
+def test_stored_merge_rounds_the_exact_mean_once():
+    from fractions import Fraction
+    # hand-worked: centroids 1 and 1 + 2^-10 (adjacent fp16 numbers), gap smallest
+    a, b = 1.0, 1.0 + 2.0 ** -10
+    C = np.array([[-1.0, a, b, 4.0]], dtype=np.float16)
+    idx = np.array([[0, 1, 2, 3]], dtype=np.uint8)
+    # equal sizes: the mean is the midpoint, a tie -> the even neighbour 1.0
+    cb, merged, new_idx = oracle.merge_closest_stored(C, np.array([[1, 5, 5, 1]], dtype=np.uint32), idx, 4)
+    assert merged.tolist() == [1] and cb.tolist() == [[-1.0, 1.0, 4.0, 0.0]] and new_idx.tolist() == [[0, 1, 1, 2]]
+    # sizes 1000000 and 1000001: the mean is above the midpoint by 2.4e-10 -- less than half a binary32
+    # step, so rounding to binary32 first would land ON the midpoint and then go to the even 1.0;
+    # rounded once it is the upper neighbour
+    cb, _, _ = oracle.merge_closest_stored(C, np.array([[1, 1000000, 1000001, 1]], dtype=np.uint32), idx, 4)
+    assert cb[0, 1] == np.float16(b)
+    assert np.float16(np.float32((1000000 * a + 1000001 * b) / 2000001)) == np.float16(a)      # what double rounding gives
+    cb, _, _ = oracle.merge_closest_stored(C, np.array([[1, 1000001, 1000000, 1]], dtype=np.uint32), idx, 4)
+    assert cb[0, 1] == np.float16(a)
+    # both clusters empty: the plain mean; untouched centroids are copied, the tail is zero
+    cb, _, _ = oracle.merge_closest_stored(np.array([[0.5, 0.75, 2.0, 4.0]], dtype=np.float16), np.array([[0, 0, 3, 3]]), idx, 4)
+    assert cb.tolist() == [[0.625, 2.0, 4.0, 0.0]]
+    # against merge_closest (the unrounded fp64 mean): same decisions, value within half an fp16 step
+    w, cbk = _case(9, 300, 6, 8, 77)
+    ix = oracle.assign_nearest(w, cbk, 6)
+    counts = oracle.cluster_counts(ix, 8)
+    ref, merged_ref, idx_ref = oracle.merge_closest(cbk, counts, ix, 6)
+    got, merged, new_idx = oracle.merge_closest_stored(cbk, counts, ix, 6)
+    assert np.array_equal(merged, merged_ref) and np.array_equal(new_idx, idx_ref) and got.dtype == np.float16
+    up = np.nextafter(got, np.float16(np.inf)).astype(np.float64)
+    down = np.nextafter(got, np.float16(-np.inf)).astype(np.float64)
+    g64 = got.astype(np.float64)
+    assert np.all(ref <= (g64 + up) / 2) and np.all(ref >= (g64 + down) / 2)
+    # exact rational check of one row, written out
+    n = 4
+    a_ = int(merged[n]); na, nb = int(counts[n, a_]), int(counts[n, a_ + 1])
+    exact = (na * Fraction(float(cbk[n, a_])) + nb * Fraction(float(cbk[n, a_ + 1]))) / (na + nb)
+    assert abs(Fraction(float(got[n, a_])) - exact) <= min(Fraction(float(up[n, a_])) - Fraction(float(got[n, a_])),
+                                                           Fraction(float(got[n, a_])) - Fraction(float(down[n, a_]))) / 2
