@@ -58,6 +58,21 @@ def resolve_config(index, bits=None):
     return cfg
 
 
+def dependency_stages(cfg):
+    """Indices of the config's matrices grouped into the launches of a decoder block: layers that read the
+    same input share a launch (q, k, v | o | gate, up | down); a single matrix is a stage of its own."""
+    stages, i = [], 0
+    for spec in cfg.layers:
+        if spec.name == "qkvo":
+            stages += [[i, i + 1, i + 2], [i + 3]]
+        elif spec.name == "gate_up":
+            stages.append([i, i + 1])
+        else:
+            stages += [[i + j] for j in range(spec.count)]
+        i += spec.count
+    return stages
+
+
 class LayerSet:
     """Device-resident inputs of one config: per matrix R replicas of (packed, lut), x, s, y, workspace."""
 
@@ -97,10 +112,24 @@ class LayerSet:
             m["spec"].N * (1 << self.bits) * 2 + M * m["spec"].K * 2 + m["spec"].K * 4 + M * m["spec"].N * 2 for m in self.mats)
 
         self.groups = None
+        self.block_groups = None
         if M <= 16:
             self.groups = [lcd.GemvGroup([(m["packed"][r], m["lut"][r], m["x"], m["s"], m["y"], m["spec"].N) for m in self.mats],
                                          self.bits, s_q=[m["s_q"] for m in self.mats] if act_int8 else None)
                            for r in range(replicas)]
+            # The same layers as a decoder block would run them: layers that read the same input go out together
+            # (q, k, v | o | gate, up | down), the launches of a step one after the other on the stream, and the
+            # layers of one launch share ONE input vector and smoothing factor, as they do in a block.
+            self.stages = dependency_stages(self.cfg)
+            self.block_groups = []
+            for r in range(replicas):
+                per_stage = []
+                for stage in self.stages:
+                    first = self.mats[stage[0]]
+                    per_stage.append(lcd.GemvGroup([(self.mats[i]["packed"][r], self.mats[i]["lut"][r], first["x"], first["s"],
+                                                     self.mats[i]["y"], self.mats[i]["spec"].N) for i in stage],
+                                                   self.bits, s_q=[first["s_q"]] * len(stage) if act_int8 else None))
+                self.block_groups.append(per_stage)
         elif not per_layer:   # prefill: one grouped call (a smoothing launch and a matrix launch) for the whole set
             shared_ws = None
             self.groups = []
@@ -109,6 +138,16 @@ class LayerSet:
                                   self.bits, workspace=shared_ws)
                 shared_ws = g.workspace
                 self.groups.append(g)
+
+    def block_step(self, replica):
+        """One decode step in dependency order: one grouped launch per stage."""
+        for g in self.block_groups[replica]:
+            g()
+
+    def matrix_step(self, index, replica):
+        """One single-matrix call (lcd_lut_gemv / lcd_lut_gemm) on matrix `index`."""
+        m = self.mats[index]
+        self.entry(m["packed"][replica], m["lut"][replica], m["x"], m["s"], m["spec"].N, self.bits, y=m["y"], workspace=m["ws"])
 
     def step(self, replica):
         if self.groups is not None and not self.per_layer:
@@ -119,19 +158,23 @@ class LayerSet:
                        y=m["y"], workspace=m["ws"])
 
 
-def time_steps(ls, replicas, steps, warmup, eager):
-    """Returns (wall ms per step, event ms per step).  Exactly `steps` timed steps."""
+def time_steps(ls, replicas, steps, warmup, eager, step_fn=None, per_replay=False):
+    """Returns (wall ms per step, event ms per step).  Exactly `steps` timed steps of step_fn(replica)
+    (default: the set's step).  per_replay: a third result, the event time per step of every graph replay
+    (one replay = `replicas` steps), taken with an event between replays."""
     import torch
 
     stream = torch.cuda.Stream()
     graphs = {}
+    step = step_fn or ls.step
+    marks = []
 
     def run(n_steps, first):
         """Enqueue n_steps on `stream`, rotating replicas starting at `first`."""
         if eager:
             with torch.cuda.stream(stream):
                 for i in range(n_steps):
-                    ls.step((first + i) % replicas)
+                    step((first + i) % replicas)
             return
         done = 0
         while done < n_steps:
@@ -141,14 +184,22 @@ def time_steps(ls, replicas, steps, warmup, eager):
                 g = torch.cuda.CUDAGraph()
                 with torch.cuda.graph(g, stream=stream):
                     for r in range(chunk):
-                        ls.step(r)
+                        step(r)
                 graphs[key] = g
             with torch.cuda.stream(stream):
                 graphs[key].replay()
+                if per_replay and timing[0]:
+                    e = spare.pop()
+                    e.record(stream)
+                    marks.append((e, chunk))
             done += chunk
 
+    timing = [False]
+    spare = [torch.cuda.Event(enable_timing=True) for _ in range(steps // max(replicas, 1) + 2)] if per_replay else []
+    for e in spare:
+        e.record(stream)               # events are created lazily: not inside the timed region
     with torch.cuda.stream(stream):
-        ls.step(0)                     # first call outside capture (lazy module load)
+        step(0)                        # first call outside capture (lazy module load)
     torch.cuda.synchronize()
     if not eager:                      # build every graph the timed loop needs before timing
         run(replicas, 0)
@@ -164,12 +215,64 @@ def time_steps(ls, replicas, steps, warmup, eager):
     t0 = time.perf_counter()
     with torch.cuda.stream(stream):
         e0.record(stream)
+    timing[0] = True
     run(steps, 0)
     with torch.cuda.stream(stream):
         e1.record(stream)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    return (t1 - t0) * 1e3 / steps, e0.elapsed_time(e1) / steps
+    if not per_replay:
+        return (t1 - t0) * 1e3 / steps, e0.elapsed_time(e1) / steps
+    samples, prev = [], e0
+    for e, chunk in marks:
+        samples.append(prev.elapsed_time(e) / chunk)
+        prev = e
+    return (t1 - t0) * 1e3 / steps, e0.elapsed_time(e1) / steps, samples
+
+
+def percentiles(samples_ms):
+    """median / p10 / p90 of per-step times (us) over graph replays."""
+    import numpy as np
+    a = np.asarray(samples_ms, dtype=np.float64) * 1e3
+    if a.size == 0:          # eager launches: there are no replays to tell apart
+        return {"median_us": None, "p10_us": None, "p90_us": None, "samples": 0}
+    return {"median_us": float(np.median(a)), "p10_us": float(np.percentile(a, 10)), "p90_us": float(np.percentile(a, 90)),
+            "min_us": float(a.min()), "max_us": float(a.max()), "samples": int(a.size)}
+
+
+def secondary_measurements(ls, replicas, steps, warmup, eager, decode):
+    """Beside the headline (same inputs, separate timed regions, HIP events on the launch stream):
+    the spread of the step time over graph replays, the step in the dependency order of a decoder block
+    (decode only), and every distinct matrix on its own (one single-matrix call per step)."""
+    out = {}
+    steps2 = max(replicas * 8, min(steps, 1000) // replicas * replicas)
+    _, ev, samples = time_steps(ls, replicas, steps2, min(warmup, 50), eager, per_replay=True)
+    out["step_time_over_replays"] = dict(percentiles(samples), steps_per_replay=replicas, mean_us=ev * 1e3)
+    if decode and ls.block_groups is not None and len(ls.stages) > 1:
+        _, ev, samples = time_steps(ls, replicas, steps2, min(warmup, 50), eager, step_fn=ls.block_step, per_replay=True)
+        out["block_order_step"] = dict(
+            percentiles(samples), mean_us=ev * 1e3, launches_per_step=len(ls.stages),
+            stages=[[f"{ls.mats[i]['spec'].N}x{ls.mats[i]['spec'].K}" for i in st] for st in ls.stages],
+            effective_GBps=ls.index_bytes / (ev * 1e-3) / 1e9, frac_of_hbm_peak=ls.index_bytes / (ev * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            what="the same set as a decoder block runs it: one grouped launch per group of layers that read the same input "
+                 "(they share one x and s), the launches of a step in order on one stream, replayed from a HIP graph")
+    per_matrix, seen = [], set()
+    for i, m in enumerate(ls.mats):
+        shape = (m["spec"].N, m["spec"].K)
+        if shape in seen:
+            continue
+        seen.add(shape)
+        _, ev, samples = time_steps(ls, replicas, steps2, min(warmup, 50), eager, step_fn=lambda r, i=i: ls.matrix_step(i, r), per_replay=True)
+        row = dict(percentiles(samples), matrix=f"{shape[0]}x{shape[1]}", mean_us=ev * 1e3)
+        if decode:
+            b = shape[0] * shape[1] * ls.bits // 8
+            row.update(index_bytes=b, effective_GBps=b / (ev * 1e-3) / 1e9, frac_of_hbm_peak=b / (ev * 1e-3) / 1e9 / HBM_PEAK_GBS)
+        else:
+            f = 2.0 * ls.M * shape[0] * shape[1]
+            row.update(flops=f, TFLOPs=f / (ev * 1e-3) / 1e12, frac_of_mfma_peak=f / (ev * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS)
+        per_matrix.append(row)
+    out["per_matrix_single_calls"] = per_matrix
+    return out
 
 
 def cpu_baseline(cfg_index, M, budget_s=12.0, bits=None):
@@ -210,15 +313,16 @@ def cpu_baseline(cfg_index, M, budget_s=12.0, bits=None):
 
 
 def measured_traffic(kernel, cfg_index):
-    """HBM bytes per launch of the dominant kernel, from the committed rocprofv3 --pmc summary
-    (FETCH_SIZE / WRITE_SIZE, scaled by a copy of known size); None if there is no such file."""
+    """HBM bytes per launch of the dominant kernel.  NOT measured by this run: rocprofv3 --pmc cannot run
+    inside the timed program, so the figure is read from the committed summary of two counter runs
+    (FETCH_SIZE / WRITE_SIZE, scaled by a copy of known size).  Returns (bytes, file name) or (None, None)."""
     f = ROOT / "profiles" / f"{kernel}_config{cfg_index}_hbm_traffic.txt"
     if not f.exists():
-        return None
+        return None, None
     for line in f.read_text().splitlines():
         if line.startswith("traffic_bytes_per_launch:"):
-            return int(line.split(":")[1])
-    return None
+            return int(line.split(":")[1]), f"profiles/{f.name}"
+    return None, None
 
 
 def library_dense_gemm(cfg, M, steps, warmup):
@@ -329,10 +433,14 @@ def main():
     if decode:
         metric, unit = "lut_gemv_effective_bandwidth_packed_index_bytes", "GB/s"
         value = ls.index_bytes / (wall_ms * 1e-3) / 1e9
+        traffic, traffic_file = (measured_traffic(decode_kernel, args.config) if (n_launch == 1 and args.bits is None and not args.act_int8)
+                                 else (None, None))
         roofline = {
             "bound": "hbm", "achieved": ls.index_bytes / (event_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": ls.index_bytes / (event_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-            "traffic": measured_traffic(decode_kernel, args.config) if (n_launch == 1 and args.bits is None and not args.act_int8) else None,
+            "traffic": traffic,
+            "traffic_source": (f"{traffic_file}: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command, committed with the "
+                               "kernel; not measured by this run") if traffic is not None else None,
             "kernel": decode_kernel,
             "launches_per_step": n_launch, "kernels_per_launch": 2 if prepass else 1, "algorithmic_bytes_per_step": ls.index_bytes,
             "avg_launch_us": event_ms * 1e3 / n_launch,
@@ -358,6 +466,8 @@ def main():
                    "launch": ("eager" if args.eager else "hip graph replay") + (", one grouped launch per step" if n_launch == 1 else ", one call per matrix")},
         "roofline": roofline,
     }
+    if not args.no_extra and not args.per_layer:
+        out["secondary"] = secondary_measurements(ls, replicas, args.steps, args.warmup, args.eager, decode)
     del ls
     torch.cuda.empty_cache()
     if args.library_gemm and not decode:
