@@ -181,6 +181,15 @@ lcd_status lcd_lut_gemv_q8(const void *packed, const void *lut, const uint16_t *
                            uint16_t *y, int M, int N, int K, int bits,
                            void *workspace, size_t workspace_bytes, void *stream);
 
+/* The prefill path with the same input transformation (Sec. 4.1 applies it to the input of every
+ * table-lookup layer, whatever the number of tokens): the smoothing kernel ahead of the matrix kernel
+ * quantises instead (same binary32 quantiser, codes bit for bit those of lcd_lut_gemv_q8) and the
+ * matrix kernel multiplies the fp32 sums by s_q before the one rounding to fp16.  Any M >= 1;
+ * all other arguments, the workspace and the precondition on s*s_q as above. */
+lcd_status lcd_lut_gemm_q8(const void *packed, const void *lut, const uint16_t *x, const float *s, float s_q,
+                           uint16_t *y, int M, int N, int K, int bits,
+                           void *workspace, size_t workspace_bytes, void *stream);
+
 /* ---- grouped decode: several independent layers in ONE launch ---------------------------- *
  *
  * A decoder block applies several table-lookup linear layers per token (Sec. 5 evaluates whole
@@ -234,6 +243,14 @@ lcd_status lcd_lut_gemv_q8_grouped(const lcd_gemv_problem *problems /*HOST*/, co
 size_t lcd_workspace_bytes_gemm_grouped(const lcd_gemv_problem *problems /*HOST*/, int count, int M, int bits);
 lcd_status lcd_lut_gemm_grouped(const lcd_gemv_problem *problems /*HOST*/, int count, int M, int bits,
                                 void *workspace, size_t workspace_bytes, void *stream);
+/* Layers whose x, s and K are the same pointers and size (q/k/v or gate/up of a decoder block read one
+ * input) share one smoothed copy: the activations are transformed once per distinct input.
+ *
+ * The same with the input transformation of lcd_lut_gemm_q8 in front of every layer (Sec. 4.1):
+ * s_q is a HOST array of `count` activation quantisation steps, one per layer (layers share a
+ * transformed copy only if their steps are equal too). */
+lcd_status lcd_lut_gemm_q8_grouped(const lcd_gemv_problem *problems /*HOST*/, const float *s_q /*HOST*/, int count,
+                                   int M, int bits, void *workspace, size_t workspace_bytes, void *stream);
 
 /* ---- clustering-side steps that need no calibration data (offline) ------------------------ *
  *

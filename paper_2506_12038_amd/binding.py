@@ -21,7 +21,7 @@ EXPORTS = (
     "lcd_pack_indices", "lcd_unpack_indices", "lcd_pack_indices_host", "lcd_unpack_indices_host",
     "lcd_build_lut", "lcd_lut_gemv", "lcd_lut_gemm", "lcd_lut_gemv_q8", "lcd_lut_gemv_noalloc",
     "lcd_workspace_bytes_grouped", "lcd_lut_gemv_grouped", "lcd_lut_gemv_q8_grouped", "lcd_lut_gemv_grouped_mixed",
-    "lcd_workspace_bytes_gemm_grouped", "lcd_lut_gemm_grouped",
+    "lcd_workspace_bytes_gemm_grouped", "lcd_lut_gemm_grouped", "lcd_lut_gemm_q8", "lcd_lut_gemm_q8_grouped",
     "lcd_assign_indices", "lcd_cluster_counts", "lcd_merge_closest",
 )
 
@@ -76,8 +76,12 @@ def load_library():
         fn.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, vp, sz, vp]
     lib.lcd_lut_gemv_noalloc.restype = ci
     lib.lcd_lut_gemv_noalloc.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, vp]
-    lib.lcd_lut_gemv_q8.restype = ci
-    lib.lcd_lut_gemv_q8.argtypes = [vp, vp, vp, vp, ctypes.c_float, vp, ci, ci, ci, ci, vp, sz, vp]
+    for name in ("lcd_lut_gemv_q8", "lcd_lut_gemm_q8"):
+        fn = getattr(lib, name)
+        fn.restype = ci
+        fn.argtypes = [vp, vp, vp, vp, ctypes.c_float, vp, ci, ci, ci, ci, vp, sz, vp]
+    lib.lcd_lut_gemm_q8_grouped.restype = ci
+    lib.lcd_lut_gemm_q8_grouped.argtypes = [ctypes.POINTER(_Problem), ctypes.POINTER(ctypes.c_float), ci, ci, ci, vp, sz, vp]
     lib.lcd_workspace_bytes_grouped.restype = sz
     lib.lcd_workspace_bytes_grouped.argtypes = [ctypes.POINTER(_Problem), ci, ci, ci]
     lib.lcd_lut_gemv_grouped.restype = ci
@@ -234,6 +238,15 @@ def lcd_lut_gemv_noalloc(packed, lut, x, s, N: int, bits: int, y, stream=None):
 
 def lcd_lut_gemv_q8(packed, lut, x, s, s_q: float, N: int, bits: int, y=None, workspace=None, stream=None):
     """Decode path with the INT8 input transformation in front: y = s_q * sum_k q_k * C[n][idx], M <= 16."""
+    return _product_q8("lcd_lut_gemv_q8", packed, lut, x, s, s_q, N, bits, y, workspace, stream)
+
+
+def lcd_lut_gemm_q8(packed, lut, x, s, s_q: float, N: int, bits: int, y=None, workspace=None, stream=None):
+    """Prefill path with the INT8 input transformation in front (any M)."""
+    return _product_q8("lcd_lut_gemm_q8", packed, lut, x, s, s_q, N, bits, y, workspace, stream)
+
+
+def _product_q8(fn_name, packed, lut, x, s, s_q, N, bits, y, workspace, stream):
     import torch
     lib = load_library()
     M, K = x.shape
@@ -241,7 +254,7 @@ def lcd_lut_gemv_q8(packed, lut, x, s, s_q: float, N: int, bits: int, y=None, wo
         y = torch.empty((M, N), dtype=torch.float16, device=x.device)
     if workspace is None:
         workspace = torch.empty(max(lib.lcd_workspace_bytes(M, N, K, bits), 256), dtype=torch.uint8, device=x.device)
-    _check(lib.lcd_lut_gemv_q8(
+    _check(getattr(lib, fn_name)(
         _dev(packed, torch.uint8, "packed"), _dev(lut, torch.uint8, "lut"), _dev(x, torch.float16, "x"),
         _dev(s, torch.float32, "s"), float(s_q), _dev(y, torch.float16, "y"), M, N, K, bits,
         _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream)))
@@ -315,12 +328,17 @@ class GemmGroup:
     """Marshalled argument block of lcd_lut_gemm_grouped (prefill, several layers, one pair of launches):
     problems = [(packed, lut, x, s, y, N), ...] with one token count and one index width."""
 
-    def __init__(self, problems, bits: int, workspace=None):
+    def __init__(self, problems, bits: int, workspace=None, s_q=None):
         import torch
         lib = load_library()
         self.count, self.bits = len(problems), bits
         self._keep = list(problems)
         self.M = problems[0][2].shape[0]
+        self._s_q = None
+        if s_q is not None:      # one activation quantisation step per layer: lcd_lut_gemm_q8_grouped
+            if len(s_q) != self.count:
+                raise ValueError("one s_q per problem")
+            self._s_q = (ctypes.c_float * self.count)(*[float(v) for v in s_q])
         arr = (_Problem * self.count)()
         for i, (packed, lut, x, s, y, N) in enumerate(problems):
             if x.shape[0] != self.M:
@@ -336,8 +354,12 @@ class GemmGroup:
 
     def __call__(self, stream=None):
         import torch
-        _check(load_library().lcd_lut_gemm_grouped(self._arr, self.count, self.M, self.bits, _dev(self.workspace, torch.uint8, "workspace"),
-                                                   self.workspace.numel(), _stream(stream)))
+        ws = _dev(self.workspace, torch.uint8, "workspace")
+        if self._s_q is None:
+            _check(load_library().lcd_lut_gemm_grouped(self._arr, self.count, self.M, self.bits, ws, self.workspace.numel(), _stream(stream)))
+        else:
+            _check(load_library().lcd_lut_gemm_q8_grouped(self._arr, self._s_q, self.count, self.M, self.bits, ws,
+                                                          self.workspace.numel(), _stream(stream)))
 
 
 def lcd_lut_gemm_grouped(problems, bits: int, workspace=None, stream=None):

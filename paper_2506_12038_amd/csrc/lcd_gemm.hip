@@ -44,11 +44,17 @@ typedef __attribute__((address_space(1))) const uint32_t glb_u32;
 // inline assembly below, so the compiler never copies them (as loop-carried values it would move
 // all 128 registers to VGPRs and back in every iteration).  This file is compiled with AGPR
 // spilling disabled, and uses no MFMA builtins, so the compiler itself never allocates an AGPR.
+// The compiler does not look inside the assembly text, so it cannot keep the distance the hardware
+// requires between a vector instruction that writes a register and a matrix instruction that reads it
+// as an operand (it is free to place the last instruction of an operand's dequantisation directly in
+// front of the matrix instruction, and does so depending on unrelated details of the source): every
+// matrix instruction therefore brings its own two wait states.  Two waves share a SIMD and a 32x32x16
+// instruction occupies the matrix pipe for 32 cycles, so the two issue cycles are hidden.
 template <int IDX> __device__ __forceinline__ void mfma_acc(uint4v a, uint4v b);
 template <int IDX> __device__ __forceinline__ float16v read_acc();
 template <> __device__ __forceinline__ void mfma_acc<0>(uint4v a, uint4v b)
 {
-    asm volatile("v_mfma_f32_32x32x16_f16 a[0:15], %0, %1, a[0:15]" : : "v"(a), "v"(b) : "a0", "a1", "a2", "a3", "a4", "a5", "a6", "a7", "a8", "a9", "a10", "a11", "a12", "a13", "a14", "a15");
+    asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_f16 a[0:15], %0, %1, a[0:15]" : : "v"(a), "v"(b) : "a0", "a1", "a2", "a3", "a4", "a5", "a6", "a7", "a8", "a9", "a10", "a11", "a12", "a13", "a14", "a15");
 }
 template <> __device__ __forceinline__ float16v read_acc<0>()
 {
@@ -75,7 +81,7 @@ template <> __device__ __forceinline__ float16v read_acc<0>()
 }
 template <> __device__ __forceinline__ void mfma_acc<1>(uint4v a, uint4v b)
 {
-    asm volatile("v_mfma_f32_32x32x16_f16 a[16:31], %0, %1, a[16:31]" : : "v"(a), "v"(b) : "a16", "a17", "a18", "a19", "a20", "a21", "a22", "a23", "a24", "a25", "a26", "a27", "a28", "a29", "a30", "a31");
+    asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_f16 a[16:31], %0, %1, a[16:31]" : : "v"(a), "v"(b) : "a16", "a17", "a18", "a19", "a20", "a21", "a22", "a23", "a24", "a25", "a26", "a27", "a28", "a29", "a30", "a31");
 }
 template <> __device__ __forceinline__ float16v read_acc<1>()
 {
@@ -102,7 +108,7 @@ template <> __device__ __forceinline__ float16v read_acc<1>()
 }
 template <> __device__ __forceinline__ void mfma_acc<2>(uint4v a, uint4v b)
 {
-    asm volatile("v_mfma_f32_32x32x16_f16 a[32:47], %0, %1, a[32:47]" : : "v"(a), "v"(b) : "a32", "a33", "a34", "a35", "a36", "a37", "a38", "a39", "a40", "a41", "a42", "a43", "a44", "a45", "a46", "a47");
+    asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_f16 a[32:47], %0, %1, a[32:47]" : : "v"(a), "v"(b) : "a32", "a33", "a34", "a35", "a36", "a37", "a38", "a39", "a40", "a41", "a42", "a43", "a44", "a45", "a46", "a47");
 }
 template <> __device__ __forceinline__ float16v read_acc<2>()
 {
@@ -129,7 +135,7 @@ template <> __device__ __forceinline__ float16v read_acc<2>()
 }
 template <> __device__ __forceinline__ void mfma_acc<3>(uint4v a, uint4v b)
 {
-    asm volatile("v_mfma_f32_32x32x16_f16 a[48:63], %0, %1, a[48:63]" : : "v"(a), "v"(b) : "a48", "a49", "a50", "a51", "a52", "a53", "a54", "a55", "a56", "a57", "a58", "a59", "a60", "a61", "a62", "a63");
+    asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_f16 a[48:63], %0, %1, a[48:63]" : : "v"(a), "v"(b) : "a48", "a49", "a50", "a51", "a52", "a53", "a54", "a55", "a56", "a57", "a58", "a59", "a60", "a61", "a62", "a63");
 }
 template <> __device__ __forceinline__ float16v read_acc<3>()
 {
@@ -156,7 +162,7 @@ template <> __device__ __forceinline__ float16v read_acc<3>()
 }
 template <> __device__ __forceinline__ void mfma_acc<4>(uint4v a, uint4v b)
 {
-    asm volatile("v_mfma_f32_32x32x16_f16 a[64:79], %0, %1, a[64:79]" : : "v"(a), "v"(b) : "a64", "a65", "a66", "a67", "a68", "a69", "a70", "a71", "a72", "a73", "a74", "a75", "a76", "a77", "a78", "a79");
+    asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_f16 a[64:79], %0, %1, a[64:79]" : : "v"(a), "v"(b) : "a64", "a65", "a66", "a67", "a68", "a69", "a70", "a71", "a72", "a73", "a74", "a75", "a76", "a77", "a78", "a79");
 }
 template <> __device__ __forceinline__ float16v read_acc<4>()
 {
@@ -183,7 +189,7 @@ template <> __device__ __forceinline__ float16v read_acc<4>()
 }
 template <> __device__ __forceinline__ void mfma_acc<5>(uint4v a, uint4v b)
 {
-    asm volatile("v_mfma_f32_32x32x16_f16 a[80:95], %0, %1, a[80:95]" : : "v"(a), "v"(b) : "a80", "a81", "a82", "a83", "a84", "a85", "a86", "a87", "a88", "a89", "a90", "a91", "a92", "a93", "a94", "a95");
+    asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_f16 a[80:95], %0, %1, a[80:95]" : : "v"(a), "v"(b) : "a80", "a81", "a82", "a83", "a84", "a85", "a86", "a87", "a88", "a89", "a90", "a91", "a92", "a93", "a94", "a95");
 }
 template <> __device__ __forceinline__ float16v read_acc<5>()
 {
@@ -210,7 +216,7 @@ template <> __device__ __forceinline__ float16v read_acc<5>()
 }
 template <> __device__ __forceinline__ void mfma_acc<6>(uint4v a, uint4v b)
 {
-    asm volatile("v_mfma_f32_32x32x16_f16 a[96:111], %0, %1, a[96:111]" : : "v"(a), "v"(b) : "a96", "a97", "a98", "a99", "a100", "a101", "a102", "a103", "a104", "a105", "a106", "a107", "a108", "a109", "a110", "a111");
+    asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_f16 a[96:111], %0, %1, a[96:111]" : : "v"(a), "v"(b) : "a96", "a97", "a98", "a99", "a100", "a101", "a102", "a103", "a104", "a105", "a106", "a107", "a108", "a109", "a110", "a111");
 }
 template <> __device__ __forceinline__ float16v read_acc<6>()
 {
@@ -237,7 +243,7 @@ template <> __device__ __forceinline__ float16v read_acc<6>()
 }
 template <> __device__ __forceinline__ void mfma_acc<7>(uint4v a, uint4v b)
 {
-    asm volatile("v_mfma_f32_32x32x16_f16 a[112:127], %0, %1, a[112:127]" : : "v"(a), "v"(b) : "a112", "a113", "a114", "a115", "a116", "a117", "a118", "a119", "a120", "a121", "a122", "a123", "a124", "a125", "a126", "a127");
+    asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_f16 a[112:127], %0, %1, a[112:127]" : : "v"(a), "v"(b) : "a112", "a113", "a114", "a115", "a116", "a117", "a118", "a119", "a120", "a121", "a122", "a123", "a124", "a125", "a126", "a127");
 }
 template <> __device__ __forceinline__ float16v read_acc<7>()
 {
@@ -411,7 +417,8 @@ __device__ __forceinline__ void gemm_word(const WordOps &cur, WordOps &nxt, cons
 // One output tile (row block bx, token block by) of one layer: the whole life of a workgroup.
 template <int BITS>
 __device__ __forceinline__ void gemm_tile(const uint8_t *__restrict__ packed_, const uint8_t *__restrict__ lutB, const uint8_t *__restrict__ xs,
-                                          uint16_t *__restrict__ y, int M, int Mpad, int N, int K, int bx, int by, uint8_t *lds)
+                                          uint16_t *__restrict__ y, int M, int Mpad, int N, int K, int bx, int by, uint8_t *lds,
+                                          float out_scale)   // 1, or the quantisation step when xs holds INT8 codes (Eq. 11)
 {
     constexpr uint32_t TB = kTileRows * kTileCols * BITS / 8;
 
@@ -546,7 +553,7 @@ __device__ __forceinline__ void gemm_tile(const uint8_t *__restrict__ packed_, c
             const float4v other = area_in[(slot * 4 + rg) * 64 + lane];
             half4 o;
 #pragma unroll
-            for (int u = 0; u < 4; ++u) o[u] = (_Float16)(own[4 * rg + u] + other[u]);
+            for (int u = 0; u < 4; ++u) o[u] = (_Float16)((own[4 * rg + u] + other[u]) * out_scale);
             outv[slot][rg] = __builtin_bit_cast(uint2v, o);
         }
     };
@@ -581,13 +588,13 @@ __device__ __forceinline__ void gemm_tile(const uint8_t *__restrict__ packed_, c
 template <int BITS>
 __global__ void __launch_bounds__(kGemmWaves * 64, 1)
 gemm_kernel(const uint8_t *__restrict__ packed_, const uint8_t *__restrict__ lutB, const uint8_t *__restrict__ xs,
-            uint16_t *__restrict__ y, int M, int Mpad, int N, int K, int grid_rows, int tiles_per_xcd)
+            uint16_t *__restrict__ y, int M, int Mpad, int N, int K, int grid_rows, int tiles_per_xcd, float out_scale)
 {
     extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];  // 2 stages x 64 KiB
     const int out_tile = (int)(blockIdx.x % kXcds) * tiles_per_xcd + (int)(blockIdx.x / kXcds);
     const int total_tiles = grid_rows * (Mpad / kGemmTokens);
     if ((int)(blockIdx.x / kXcds) >= tiles_per_xcd || out_tile >= total_tiles) return;
-    gemm_tile<BITS>(packed_, lutB, xs, y, M, Mpad, N, K, out_tile % grid_rows, out_tile / grid_rows, lds);
+    gemm_tile<BITS>(packed_, lutB, xs, y, M, Mpad, N, K, out_tile % grid_rows, out_tile / grid_rows, lds, out_scale);
 }
 
 // Several layers in one launch (same token count and index width): every XCD's queue of
@@ -599,6 +606,7 @@ struct GemmProblem {
     uint16_t *y;
     int N, K, grid_rows, tiles_per_xcd;
     int queue_begin;   // position of this layer's first tile in an XCD's queue
+    float out_scale;   // 1, or the layer's activation quantisation step
 };
 struct GemmBatch {
     GemmProblem p[kMaxGroup];
@@ -614,15 +622,16 @@ __global__ void __launch_bounds__(kGemmWaves * 64, 1) gemm_group_kernel(const Ge
     const GemmProblem pb = batch.p[pi];
     const int out_tile = xcd * pb.tiles_per_xcd + (pos - pb.queue_begin);
     if (out_tile >= pb.grid_rows * (batch.Mpad / kGemmTokens)) return;
-    gemm_tile<BITS>(pb.packed, pb.lutB, pb.xs, pb.y, batch.M, batch.Mpad, pb.N, pb.K, out_tile % pb.grid_rows, out_tile / pb.grid_rows, lds);
+    gemm_tile<BITS>(pb.packed, pb.lutB, pb.xs, pb.y, batch.M, batch.Mpad, pb.N, pb.K, out_tile % pb.grid_rows, out_tile / pb.grid_rows, lds,
+                    pb.out_scale);
 }
 
 int launch_gemm(const void *packed, const void *lut, const uint16_t *x, const float *s, uint16_t *y,
-                int M, int N, int K, int bits, void *workspace, const GemmPlan &plan, void *stream_)
+                int M, int N, int K, int bits, float act_scale, void *workspace, const GemmPlan &plan, void *stream_)
 {
     hipStream_t stream = (hipStream_t)stream_;
     const int Mpad = plan.m_pad;
-    if (int e = launch_smooth(x, s, workspace, M, Mpad, K, stream)) return e;
+    if (int e = launch_smooth(x, s, workspace, M, Mpad, K, act_scale, stream)) return e;
     // byte-split tables: behind the bucket multipliers (2 and 3 bits), the whole table (4 bits)
     const uint8_t *lutB = static_cast<const uint8_t *>(lut) + (bits == 4 ? 0 : (size_t)N * (bits == 2 ? 4 : 8) * 4);
     const int nt = N / kTileRows;
@@ -640,7 +649,8 @@ int launch_gemm(const void *packed, const void *lut, const uint16_t *x, const fl
     }
     const uint8_t *packed_arg = static_cast<const uint8_t *>(packed), *xs_arg = static_cast<const uint8_t *>(workspace);
     int M_arg = M, Mpad_arg = Mpad, N_arg = N, K_arg = K, rows_arg = grid_rows, xcd_arg = tiles_per_xcd;
-    void *args[] = {&packed_arg, &lutB, &xs_arg, &y, &M_arg, &Mpad_arg, &N_arg, &K_arg, &rows_arg, &xcd_arg};
+    float scale_arg = act_scale != 0.0f ? act_scale : 1.0f;
+    void *args[] = {&packed_arg, &lutB, &xs_arg, &y, &M_arg, &Mpad_arg, &N_arg, &K_arg, &rows_arg, &xcd_arg, &scale_arg};
     if (hipError_t e = hipLaunchKernel(fn, grid, block, args, lds_bytes, stream)) return (int)e;
     return (int)hipGetLastError();
 }
@@ -653,15 +663,23 @@ int launch_gemm_group(const GroupItem *items, int count, int M, int bits, void *
     int order[kMaxGroup];
     for (int i = 0; i < count; ++i) order[i] = i;
     std::stable_sort(order, order + count, [&](int a, int b) { return items[a].K > items[b].K; });
+    // Layers that read the same input (same x, s, K and quantisation step: q/k/v, gate/up of a decoder
+    // block) share one transformed copy of it: the activations are smoothed once per distinct input.
     SmoothItem sm[kMaxGroup];
+    int distinct = 0;
     GemmBatch batch{};
     size_t offset = 0;
     int queue = 0;
     for (int q = 0; q < count; ++q) {
         const GroupItem &it = items[order[q]];
-        uint8_t *xs = static_cast<uint8_t *>(workspace) + offset;
-        offset += plan_gemm(M, it.N, it.K, bits).xs_bytes;
-        sm[q] = SmoothItem{it.x, it.s, xs, it.K};
+        uint8_t *xs = nullptr;
+        for (int d = 0; d < distinct && !xs; ++d)
+            if (sm[d].x == it.x && sm[d].s == it.s && sm[d].K == it.K && sm[d].s_q == it.act_scale) xs = static_cast<uint8_t *>(sm[d].xs);
+        if (!xs) {
+            xs = static_cast<uint8_t *>(workspace) + offset;
+            offset += plan_gemm(M, it.N, it.K, bits).xs_bytes;
+            sm[distinct++] = SmoothItem{it.x, it.s, xs, it.K, it.act_scale};
+        }
         GemmProblem &p = batch.p[q];
         p.packed = static_cast<const uint8_t *>(it.packed);
         p.lutB = static_cast<const uint8_t *>(it.lut) + (bits == 4 ? 0 : (size_t)it.N * (bits == 2 ? 4 : 8) * 4);
@@ -673,10 +691,11 @@ int launch_gemm_group(const GroupItem *items, int count, int M, int bits, void *
         const int total_tiles = p.grid_rows * (Mpad / kGemmTokens);
         p.tiles_per_xcd = (total_tiles + kXcds - 1) / kXcds;
         p.queue_begin = queue;
+        p.out_scale = it.act_scale != 0.0f ? it.act_scale : 1.0f;
         queue += p.tiles_per_xcd;
     }
     batch.count = count; batch.M = M; batch.Mpad = Mpad;
-    if (int e = launch_smooth_group(sm, count, M, Mpad, stream)) return e;
+    if (int e = launch_smooth_group(sm, distinct, M, Mpad, stream)) return e;
     const size_t lds_bytes = 2 * kStageBytes;
     static bool attr_set[3] = {false, false, false};
     const void *fn = bits == 2 ? (const void *)gemm_group_kernel<2> : bits == 3 ? (const void *)gemm_group_kernel<3> : (const void *)gemm_group_kernel<4>;

@@ -345,7 +345,18 @@ lcd_status lcd_lut_gemm(const void *packed, const void *lut, const uint16_t *x, 
 {
     if (lcd_status st = check_product(packed, lut, x, s, y, M, N, K, bits, workspace, workspace_bytes)) return st;
     const GemmPlan plan = plan_gemm(M, N, K, bits);
-    if (int e = launch_gemm(packed, lut, x, s, y, M, N, K, bits, workspace, plan, stream))
+    if (int e = launch_gemm(packed, lut, x, s, y, M, N, K, bits, 0.0f, workspace, plan, stream))
+        return fail(LCD_ERR_HIP, "gemm launch: %s", hip_error_name(e));
+    return LCD_OK;
+}
+
+lcd_status lcd_lut_gemm_q8(const void *packed, const void *lut, const uint16_t *x, const float *s, float s_q, uint16_t *y,
+                           int M, int N, int K, int bits, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!(s_q > 0.0f) || !(s_q < 3.0e38f)) return fail(LCD_ERR_BAD_SCALE, "s_q=%g must be positive and finite", (double)s_q);
+    if (lcd_status st = check_product(packed, lut, x, s, y, M, N, K, bits, workspace, workspace_bytes)) return st;
+    const GemmPlan plan = plan_gemm(M, N, K, bits);
+    if (int e = launch_gemm(packed, lut, x, s, y, M, N, K, bits, s_q, workspace, plan, stream))
         return fail(LCD_ERR_HIP, "gemm launch: %s", hip_error_name(e));
     return LCD_OK;
 }
@@ -361,8 +372,8 @@ size_t lcd_workspace_bytes_gemm_grouped(const lcd_gemv_problem *problems, int co
     return total;
 }
 
-lcd_status lcd_lut_gemm_grouped(const lcd_gemv_problem *problems, int count, int M, int bits,
-                                void *workspace, size_t workspace_bytes, void *stream)
+static lcd_status gemm_grouped(const lcd_gemv_problem *problems, const float *s_q, int count, int M, int bits,
+                               void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!problems) return fail(LCD_ERR_NULL, "problems is NULL");
     if (count < 1 || count > kMaxGroup) return fail(LCD_ERR_SIZE, "count=%d must be in 1..%d", count, kMaxGroup);
@@ -373,12 +384,27 @@ lcd_status lcd_lut_gemm_grouped(const lcd_gemv_problem *problems, int count, int
         // every layer's share of the workspace is checked below against the sum
         if (lcd_status st = check_product(p.packed, p.lut, p.x, p.s, p.y, M, p.N, p.K, bits, workspace, (size_t)-1)) return st;
         need += plan_gemm(M, p.N, p.K, bits).xs_bytes;
-        items[i] = GroupItem{p.packed, p.lut, p.x, p.s, p.y, p.N, p.K, 0.0f};
+        if (s_q && (!(s_q[i] > 0.0f) || !(s_q[i] < 3.0e38f)))
+            return fail(LCD_ERR_BAD_SCALE, "s_q[%d]=%g must be positive and finite", i, (double)s_q[i]);
+        items[i] = GroupItem{p.packed, p.lut, p.x, p.s, p.y, p.N, p.K, s_q ? s_q[i] : 0.0f};
     }
     if (workspace_bytes < need) return fail(LCD_ERR_SIZE, "workspace_bytes=%zu < %zu", workspace_bytes, need);
     if (int e = launch_gemm_group(items, count, M, bits, workspace, stream))
         return fail(LCD_ERR_HIP, "grouped gemm launch: %s", hip_error_name(e));
     return LCD_OK;
+}
+
+lcd_status lcd_lut_gemm_grouped(const lcd_gemv_problem *problems, int count, int M, int bits,
+                                void *workspace, size_t workspace_bytes, void *stream)
+{
+    return gemm_grouped(problems, nullptr, count, M, bits, workspace, workspace_bytes, stream);
+}
+
+lcd_status lcd_lut_gemm_q8_grouped(const lcd_gemv_problem *problems, const float *s_q, int count, int M, int bits,
+                                   void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!s_q) return fail(LCD_ERR_NULL, "s_q is NULL");
+    return gemm_grouped(problems, s_q, count, M, bits, workspace, workspace_bytes, stream);
 }
 
 static lcd_status check_ncent(int ncent, int bits, int least)

@@ -48,14 +48,15 @@ constexpr size_t kStaticScratchBytes = (size_t)16 * kStaticScratchCols * 2;  // 
 int launch_gemv_noalloc(const void *packed, const void *lut, const uint16_t *x, const float *s, uint16_t *y,
                         int M, int N, int K, int bits, void *stream);
 int launch_gemm(const void *packed, const void *lut, const uint16_t *x, const float *s, uint16_t *y,
-                int M, int N, int K, int bits, void *workspace, const GemmPlan &plan, void *stream);
+                int M, int N, int K, int bits, float act_scale, void *workspace, const GemmPlan &plan, void *stream);
 int launch_assign(const uint16_t *w, const uint16_t *codebook, int ncent, int N, int K, int bits, uint8_t *idx, void *stream);
 int launch_counts(const uint8_t *idx, int N, int K, int bits, uint32_t *counts, void *stream);
 int launch_merge(const uint16_t *cb_in, const uint32_t *counts, const uint8_t *idx_in, int ncent, int N, int K, int bits,
                  uint16_t *cb_out, uint8_t *idx_out, uint8_t *merged, void *stream);
 const char *hip_error_name(int err);
-int launch_smooth(const uint16_t *x, const float *s, void *xs, int M, int Mpad, int K, void *stream);
-struct SmoothItem { const uint16_t *x; const float *s; void *xs; int K; };
+// s_q = 0: xs = x / s; s_q > 0: the INT8 codes of Sec. 4.1 (as fp16 numbers)
+int launch_smooth(const uint16_t *x, const float *s, void *xs, int M, int Mpad, int K, float s_q, void *stream);
+struct SmoothItem { const uint16_t *x; const float *s; void *xs; int K; float s_q; };
 int launch_smooth_group(const SmoothItem *items, int count, int M, int Mpad, void *stream);
 // prefill, several layers in one launch; the workspace holds every layer's smoothed activations side by side
 int launch_gemm_group(const GroupItem *items, int count, int M, int bits, void *workspace, void *stream);

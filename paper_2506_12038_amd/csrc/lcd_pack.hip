@@ -172,19 +172,28 @@ __global__ void __launch_bounds__(256) build_lut_kernel(const uint16_t *__restri
 // thread smooths 8 values, and the tile is turned into operand order through LDS so that the
 // stores are coalesced too (16-byte stores scattered 1 KiB apart ran at a third of the rate).
 constexpr int kSmoothRowBytes = 32 * 16 + 16;   // one [m 32][16 B] row of the tile in LDS, padded
+// s_q != 0: the input transformation of Sec. 4.1 (Eq. 10-11) instead -- the activations leave as INT8 codes
+// (integers up to 128 in magnitude, exact as fp16 numbers); the divisor-only part of the division is
+// shared by the thread's four token rows.
 __device__ __forceinline__ void smooth_tile(const uint16_t *__restrict__ x, const float *__restrict__ s,
-                                            _Float16 *__restrict__ xs, int M, int Mpad, int K, int c, int mb)
+                                            _Float16 *__restrict__ xs, int M, int Mpad, int K, int c, int mb, float s_q)
 {
     __shared__ __attribute__((aligned(16))) uint8_t tile[32 * kSmoothRowBytes];
     const int t = threadIdx.x;
     // a thread's four groups are the same 8 columns of four token rows: one set of reciprocals
     const int kg = t & 31, k = c * kTileCols + 8 * kg;
+    const bool quantised = s_q != 0.0f;   // uniform
     float r[8];
+    Divisor dv[8];
     {
         const float4v s0 = *reinterpret_cast<const float4v *>(s + k);
         const float4v s1 = *reinterpret_cast<const float4v *>(s + k + 4);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) r[e] = __builtin_amdgcn_rcpf(e < 4 ? s0[e] : s1[e - 4]);
+        for (int e = 0; e < 8; ++e) {
+            const float se = e < 4 ? s0[e] : s1[e - 4];
+            r[e] = __builtin_amdgcn_rcpf(se);
+            dv[e] = make_divisor(se, quantised ? s_q : 1.0f);
+        }
     }
     uint4v xin[4];
 #pragma unroll
@@ -205,7 +214,7 @@ __device__ __forceinline__ void smooth_tile(const uint16_t *__restrict__ x, cons
             for (int e = 0; e < 8; ++e) {
                 const uint16_t xb = (uint16_t)(xv[e >> 1] >> (16 * (e & 1)));
                 const int slot = e < 4 ? 2 * e : 2 * (e - 4) + 1;
-                o[slot] = smooth_with(xb, r[e]);
+                o[slot] = quantised ? quantise_one(xb, dv[e]) : smooth_with(xb, r[e]);
             }
         } else {
 #pragma unroll
@@ -226,9 +235,9 @@ __device__ __forceinline__ void smooth_tile(const uint16_t *__restrict__ x, cons
 }
 
 __global__ void __launch_bounds__(256) smooth_kernel(const uint16_t *__restrict__ x, const float *__restrict__ s,
-                                                     _Float16 *__restrict__ xs, int M, int Mpad, int K)
+                                                     _Float16 *__restrict__ xs, int M, int Mpad, int K, float s_q)
 {
-    smooth_tile(x, s, xs, M, Mpad, K, blockIdx.x, blockIdx.y);
+    smooth_tile(x, s, xs, M, Mpad, K, blockIdx.x, blockIdx.y, s_q);
 }
 
 // the activations of several layers in one launch: grid.z = layer, grid.x = the widest layer's chunks
@@ -237,7 +246,7 @@ __global__ void __launch_bounds__(256) smooth_group_kernel(const SmoothBatch bat
 {
     const SmoothItem it = batch.p[blockIdx.z];
     if ((int)blockIdx.x * kTileCols >= it.K) return;   // uniform over the workgroup
-    smooth_tile(it.x, it.s, (_Float16 *)it.xs, M, Mpad, it.K, blockIdx.x, blockIdx.y);
+    smooth_tile(it.x, it.s, (_Float16 *)it.xs, M, Mpad, it.K, blockIdx.x, blockIdx.y, it.s_q);
 }
 
 int launch_smooth_group(const SmoothItem *items, int count, int M, int Mpad, void *stream)
@@ -250,10 +259,10 @@ int launch_smooth_group(const SmoothItem *items, int count, int M, int Mpad, voi
     return (int)hipGetLastError();
 }
 
-int launch_smooth(const uint16_t *x, const float *s, void *xs, int M, int Mpad, int K, void *stream)
+int launch_smooth(const uint16_t *x, const float *s, void *xs, int M, int Mpad, int K, float s_q, void *stream)
 {
     const dim3 grid((unsigned)(K / kTileCols), (unsigned)(Mpad / 32)), block(256);
-    hipLaunchKernelGGL(smooth_kernel, grid, block, 0, (hipStream_t)stream, x, s, (_Float16 *)xs, M, Mpad, K);
+    hipLaunchKernelGGL(smooth_kernel, grid, block, 0, (hipStream_t)stream, x, s, (_Float16 *)xs, M, Mpad, K, s_q);
     return (int)hipGetLastError();
 }
 

@@ -29,7 +29,7 @@ int launch_unpack(const void *, int, int, int, uint8_t *, void *) { return reach
 int launch_build_lut(const uint16_t *, int, int, void *, void *) { return reached("build_lut"); }
 int launch_gemv(const void *, const void *, const uint16_t *, const float *, uint16_t *, int, int, int, int, float, void *, void *) { return reached("gemv"); }
 int launch_gemv_noalloc(const void *, const void *, const uint16_t *, const float *, uint16_t *, int, int, int, int, void *) { return reached("gemv_noalloc"); }
-int launch_gemm(const void *, const void *, const uint16_t *, const float *, uint16_t *, int, int, int, int, void *, const GemmPlan &, void *) { return reached("gemm"); }
+int launch_gemm(const void *, const void *, const uint16_t *, const float *, uint16_t *, int, int, int, int, float, void *, const GemmPlan &, void *) { return reached("gemm"); }
 int launch_assign(const uint16_t *, const uint16_t *, int, int, int, int, uint8_t *, void *) { return reached("assign"); }
 int launch_counts(const uint8_t *, int, int, int, uint32_t *, void *) { return reached("counts"); }
 int launch_merge(const uint16_t *, const uint32_t *, const uint8_t *, int, int, int, int, uint16_t *, uint8_t *, uint8_t *, void *) { return reached("merge"); }
@@ -108,6 +108,8 @@ int main(void)
     CHECK(lcd_lut_gemv_noalloc(a, a, a, a, a, 16, 16, 33024, 2, NULL) == LCD_ERR_SIZE);
     CHECK(lcd_lut_gemv_q8(a, a, a, a, 0.0f, a, 1, 16, 256, 2, a, 1 << 20, NULL) == LCD_ERR_BAD_SCALE);
     CHECK(lcd_lut_gemm(a, a, NULL, a, a, 64, 16, 256, 3, a, 1 << 20, NULL) == LCD_ERR_NULL);
+    CHECK(lcd_lut_gemm_q8(a, a, a, a, -0.5f, a, 64, 16, 256, 3, a, 1 << 20, NULL) == LCD_ERR_BAD_SCALE);
+    CHECK(lcd_lut_gemm_q8(a, a, a, a, 0.5f, a, 64, 16, 256, 3, a, 16, NULL) == LCD_ERR_SIZE);
     lcd_gemv_problem pr[17];
     for (int i = 0; i < 17; ++i) { pr[i].packed = a; pr[i].lut = a; pr[i].x = a; pr[i].s = a; pr[i].y = a; pr[i].N = 16 * (i + 1); pr[i].K = 256 * (i + 1); }
     CHECK(lcd_workspace_bytes_grouped(pr, 16, 16, 2) >= 16 * 256 * 136 * 2);
@@ -125,6 +127,8 @@ int main(void)
     float sq[16]; for (int i = 0; i < 16; ++i) sq[i] = 0.1f;
     sq[15] = -1.0f;
     CHECK(lcd_lut_gemv_q8_grouped(pr, sq, 16, 1, 2, a, 1 << 20, NULL) == LCD_ERR_BAD_SCALE);
+    CHECK(lcd_lut_gemm_q8_grouped(pr, sq, 16, 64, 2, a, 1 << 30, NULL) == LCD_ERR_BAD_SCALE);
+    CHECK(lcd_lut_gemm_q8_grouped(pr, NULL, 16, 64, 2, a, 1 << 30, NULL) == LCD_ERR_NULL);
     CHECK(lcd_assign_indices(a, a, 5, 16, 256, 2, a, NULL) == LCD_ERR_SIZE);
     CHECK(lcd_merge_closest(a, a, a, 1, 16, 256, 2, a, a, a, NULL) == LCD_ERR_SIZE);
     CHECK(lcd_cluster_counts(a, 16, 256, 2, odd, NULL) == LCD_ERR_ALIGN);
