@@ -156,20 +156,23 @@ struct StepRegs {
 // (bq, j) then also fetches the multipliers of rows 4bq..4bq+3, bucket j % NC, of the group's
 // tile j / NC (fp32, accumulator order, straight from the table: every wave reads the same few
 // hundred bytes, so they come from the L1/L2 cache).
-template <int NC>
+// NC: accumulator columns one row tile uses; NB: per-bucket multipliers the table holds per row (NB < NC
+// only with two tokens at 2 bits, where columns 4..7 are the second token's bucket sums and take the
+// same multipliers as columns 0..3).
+template <int NC, int NB = NC>
 __device__ __forceinline__ uint4v load_multipliers(__amdgpu_buffer_rsrc_t rs_lut, int tile, int v1, int lane)
 {
     const int j = lane & 15, bq = lane >> 4;
     const int t = tile + j / NC;
-    return __builtin_amdgcn_raw_buffer_load_b128(rs_lut, t < v1 ? (uint32_t)((t * 4 + bq) * NC + (j % NC)) * 16 : kOob, 0, 0);
+    return __builtin_amdgcn_raw_buffer_load_b128(rs_lut, t < v1 ? (uint32_t)((t * 4 + bq) * NB + (j % NB)) * 16 : kOob, 0, 0);
 }
 
-template <int BITS, bool WITH_CF>
+template <int BITS, bool WITH_CF, int MT = 1>
 __device__ __forceinline__ void issue_step_loads(StepRegs<BITS> &r, const Cursor &c, __amdgpu_buffer_rsrc_t rs,
                                                  __amdgpu_buffer_rsrc_t rs_lut, int kc, int wave, int lane)
 {
     constexpr uint32_t TB = BITS == 2 ? 1024 : 1536;
-    constexpr int NC = BITS == 2 ? 4 : 8;
+    constexpr int NB = BITS == 2 ? 4 : 8, NC = MT == 2 ? 8 : NB;
     // a finished cursor or a padding step issues loads that are out of range: zeros, no traffic
     const int tile = c.v0 + c.i;
     const bool tv = !c.done && tile < c.v1;
@@ -184,22 +187,30 @@ __device__ __forceinline__ void issue_step_loads(StepRegs<BITS> &r, const Cursor
         r.lo[ch] = __builtin_amdgcn_raw_buffer_load_b128(rs, v ? 16 * lane : kOob, o, kStreamPolicy);
         if (BITS == 3) r.hi[ch] = __builtin_amdgcn_raw_buffer_load_b64(rs, v ? 8 * lane : kOob, o + 1024, kStreamPolicy);
     }
-    if (WITH_CF) r.cf = load_multipliers<NC>(rs_lut, tile, c.done ? 0 : c.v1, lane);
+    if (WITH_CF) r.cf = load_multipliers<NC, NB>(rs_lut, tile, c.done ? 0 : c.v1, lane);
 }
 
-template <int BITS>
+// MT = 2 (2 bits only): two tokens.  The second token's activations take the place the sign-flipped
+// activations have with 3 bits -- a second sparse pass over the same indices whose bucket sums land in
+// columns 4..7 -- so the kernel has the 3-bit kernel's shape without its sign flips; columns 0..3 and
+// 4..7 are multiplied by the same four centroids and reduced separately, one output per token.
+template <int BITS, int MT = 1>
 __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t t0, const uint32_t t1, const uint32_t t2, const uint32_t t3,
                                                                    const uint32_t t4, const uint32_t t5, const uint32_t t6, const uint32_t t7,
                                                                    const BucketBatch batch)
 {
-    constexpr int NC = BITS == 2 ? 4 : 8;        // accumulator columns one row tile uses
+    static_assert(MT == 1 || (MT == 2 && BITS == 2), "two tokens: 2-bit indices only");
+    constexpr int NB = BITS == 2 ? 4 : 8;        // buckets (centroids) per row
+    constexpr int NC = MT == 2 ? 8 : NB;         // accumulator columns one row tile uses
     constexpr int TG = 16 / NC;                  // row tiles that share one reduction (4 or 2)
     constexpr uint32_t TB = BITS == 2 ? 1024 : 1536;
     constexpr int NT = kBW * 64;
+    constexpr int kSegHalfs = kBSeg * kTileCols;        // activations of one segment, one token
+    constexpr int kPartFloats = kBW * kVisitTiles * 16; // the waves' partial outputs of one visit, one token
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
-    // LDS: [ xs: one segment, kBSeg*256 halfs ][ part: kBW*kVisitTiles*16 floats ]
+    // LDS: [ xs: MT x one segment, kBSeg*256 halfs ][ part: MT x kBW*kVisitTiles*16 floats ]
     _Float16 *xs_lds = reinterpret_cast<_Float16 *>(smem);
-    float *part = reinterpret_cast<float *>(smem + (size_t)kBSeg * kTileCols * 2);
+    float *part = reinterpret_cast<float *>(smem + (size_t)MT * kSegHalfs * 2);
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: keeps addresses scalar
@@ -216,9 +227,9 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
     const bool quantised = pb.act_scale != 0.0f;               // wave-uniform
     const float out_scale = quantised ? pb.act_scale : 1.0f;
     const __amdgpu_buffer_rsrc_t rs_packed = make_rsrc(pb.packed, (uint32_t)pb.nt * (uint32_t)kc * TB);
-    const __amdgpu_buffer_rsrc_t rs_x = make_rsrc(pb.x, (uint32_t)kc * kTileCols * 2);
+    const __amdgpu_buffer_rsrc_t rs_x = make_rsrc(pb.x, (uint32_t)MT * (uint32_t)kc * kTileCols * 2);
     const __amdgpu_buffer_rsrc_t rs_s = make_rsrc(pb.s, (uint32_t)kc * kTileCols * 4);
-    const __amdgpu_buffer_rsrc_t rs_lut = make_rsrc(pb.lutA, (uint32_t)pb.nt * 16 * NC * 4);
+    const __amdgpu_buffer_rsrc_t rs_lut = make_rsrc(pb.lutA, (uint32_t)pb.nt * 16 * NB * 4);
 
     Cursor pf{}, cur{};
     cursor_begin<false>(pf, ta, tb);
@@ -231,21 +242,23 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
     // one segment ahead; the very first ones head the kernel, before the tile loads, because they
     // start the longest dependency chain.  Reads past the end of x / s return zero through the
     // buffer resource.
-    uint4v xv;
+    uint4v xv[MT];
     float4v s0, s1;
     auto load_x = [&](int sg, bool valid) {
         const uint32_t g = (uint32_t)wave_chunk(sg, wave, lane >> 5) * 32 + (lane & 31);   // group of 8 columns
         valid = valid && g < (uint32_t)kc * 32;
-        xv = __builtin_amdgcn_raw_buffer_load_b128(rs_x, valid ? g * 16 : kOob, 0, 0);
+#pragma unroll
+        for (int t = 0; t < MT; ++t)   // token t's row of x starts K fp16 numbers after token t - 1's
+            xv[t] = __builtin_amdgcn_raw_buffer_load_b128(rs_x, valid ? g * 16 + (uint32_t)t * (uint32_t)kc * (kTileCols * 2) : kOob, 0, 0);
         s0 = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(rs_s, valid ? g * 32 : kOob, 0, 0));
         s1 = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(rs_s, valid ? g * 32 + 16 : kOob, 0, 0));
     };
     load_x(0, true);
     StepRegs<BITS> rs[kSets];   // always indexed by compile-time constants: four sets of registers
-    issue_step_loads<BITS, true>(rs[0], pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
+    issue_step_loads<BITS, true, MT>(rs[0], pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
     if (cur.done) return;   // no row tiles (the host never launches such a workgroup); the loads above moved nothing
 
-    uint4v A[kBCH][8];   // this wave's smoothed activations of the current segment, 8 operands per chunk
+    uint4v A[MT][kBCH][8];   // this wave's smoothed activations of the current segment, 8 operands per chunk and token
     bool chunk_in_k[kBCH] = {};   // wave-uniform: a short last segment leaves some of the wave's chunks empty
     half16 B1;        // constant routing matrix (index c -> column c), built after the prologue
     float *my_part = part + wave * (kVisitTiles * 16);
@@ -260,9 +273,14 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
             for (int d = 0; d < 4; ++d) {
                 const int idxreg = (int)r.lo[ch][d];
                 // half a = 0 uses index bits [15:0], a = 1 bits [31:16]
-                if (BITS == 2) {
-                    accx = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(A[ch][2 * d]), B1, accx, idxreg, 0, 0);
-                    accy = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(A[ch][2 * d + 1]), B1, accy, idxreg, 0, 1);
+                if (BITS == 2 && MT == 1) {
+                    accx = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(A[0][ch][2 * d]), B1, accx, idxreg, 0, 0);
+                    accy = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(A[0][ch][2 * d + 1]), B1, accy, idxreg, 0, 1);
+                } else if (BITS == 2) {   // two tokens: accx token 0, accy token 1
+                    accx = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(A[0][ch][2 * d]), B1, accx, idxreg, 0, 0);
+                    accy = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(A[MT - 1][ch][2 * d]), B1, accy, idxreg, 0, 0);
+                    accx = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(A[0][ch][2 * d + 1]), B1, accx, idxreg, 0, 1);
+                    accy = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(A[MT - 1][ch][2 * d + 1]), B1, accy, idxreg, 0, 1);
                 } else {
                     // sign-flipped operands: pair v of half a has its two third bits 16 apart in word a
                     // of r.hi; one 64-bit shift moves them to bits 15 / 31 of both words, one
@@ -274,18 +292,18 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
                         const int sh = 15 - (8 * (v >> 1) + 2 * d + (v & 1));
                         unsigned long long t = h64;   // one full-rate v_lshlrev_b64 (the compiler would split it in two)
                         if (sh) asm("v_lshlrev_b64 %0, %1, %2" : "=v"(t) : "n"(sh), "v"(h64));
-                        f0[v] = xor_and(A[ch][2 * d][v], (uint32_t)t, 0x80008000u);
-                        f1[v] = xor_and(A[ch][2 * d + 1][v], (uint32_t)(t >> 32), 0x80008000u);
+                        f0[v] = xor_and(A[0][ch][2 * d][v], (uint32_t)t, 0x80008000u);
+                        f1[v] = xor_and(A[0][ch][2 * d + 1][v], (uint32_t)(t >> 32), 0x80008000u);
                     }
-                    accx = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(A[ch][2 * d]), B1, accx, idxreg, 0, 0);
+                    accx = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(A[0][ch][2 * d]), B1, accx, idxreg, 0, 0);
                     accy = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(f0), B1, accy, idxreg, 0, 0);
-                    accx = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(A[ch][2 * d + 1]), B1, accx, idxreg, 0, 1);
+                    accx = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(A[0][ch][2 * d + 1]), B1, accx, idxreg, 0, 1);
                     accy = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(f1), B1, accy, idxreg, 0, 1);
                 }
             }
         }
-        if (BITS == 2) return accx + accy;
-        // 3 bits: the sign-flipped sums move from columns 0..3 to columns 4..7
+        if (BITS == 2 && MT == 1) return accx + accy;
+        // 3 bits: the sign-flipped sums move from columns 0..3 to columns 4..7 (two tokens: the second token's)
         float4v m;
 #pragma unroll
         for (int u = 0; u < 4; ++u) m[u] = accx[u] + dpp_f32<0x114>(accy[u]);   // row_shr:4
@@ -303,12 +321,13 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
             float v = m[u] * cf[u];
             v += dpp_f32<kDppQuadXor1>(v);
             v += dpp_f32<kDppQuadXor2>(v);
-            if (NC == 8) v += dpp_f32<kDppRowHalfMirror>(v);
+            if (NC == 8 && MT == 1) v += dpp_f32<kDppRowHalfMirror>(v);
             asm volatile("" : "+v"(v));   // keeps the last add out of the branch below, where it could not take the lane exchange along
             pv[u] = v;
         }
-        if ((j % NC) == 0 && cur.v0 + tl < cur.v1) {
-            float4v *slot = reinterpret_cast<float4v *>(&my_part[tl * 16 + 4 * bq]);
+        // one lane per (tile, token) holds the sum of its columns: two tokens keep columns 0..3 and 4..7 apart
+        if ((j % (NC / MT)) == 0 && cur.v0 + tl < cur.v1) {
+            float4v *slot = reinterpret_cast<float4v *>(&my_part[((j >> 2) & (MT - 1)) * kPartFloats + tl * 16 + 4 * bq]);
             if (cur.sg > 0) pv += *slot;
             *slot = pv;
         }
@@ -326,18 +345,18 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
     const float4v zero = {0.f, 0.f, 0.f, 0.f};
     auto full_turn = [&]() __attribute__((always_inline)) {
         float4v t0, t1, t3;
-        issue_step_loads<BITS, false>(r3, pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
+        issue_step_loads<BITS, false, MT>(r3, pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
         t0 = tile_sums(r0);
         const uint4v cf_a = r0.cf;   // taken before the set is loaded again
-        issue_step_loads<BITS, true>(r0, pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
+        issue_step_loads<BITS, true, MT>(r0, pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
         t1 = tile_sums(r1);
 #pragma unroll
         for (int u = 0; u < 4; ++u) t0[u] += dpp_f32<(TG == 2 ? 0x118 : 0x114)>(t1[u]);   // row_shr:8 / row_shr:4
         if (TG == 2) reduce_group(t0, cur.i, cf_a);
-        issue_step_loads<BITS, false>(r1, pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
+        issue_step_loads<BITS, false, MT>(r1, pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
         t1 = tile_sums(r2);
         const uint4v cf_b = r2.cf;
-        issue_step_loads<BITS, TG == 2>(r2, pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
+        issue_step_loads<BITS, TG == 2, MT>(r2, pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
         t3 = tile_sums(r3);
         if (TG == 2) {
 #pragma unroll
@@ -356,11 +375,11 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
     // the last 1..3 steps of a run (wave-uniform `left`): as many loads as steps
     auto short_turn = [&](int left) __attribute__((always_inline)) {
         float4v t0, t1 = zero;
-        issue_step_loads<BITS, false>(r3, pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
+        issue_step_loads<BITS, false, MT>(r3, pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
         t0 = tile_sums(r0);
         const uint4v cf_a = r0.cf, cf_b = r2.cf;
         if (left > 1) {
-            issue_step_loads<BITS, false>(r0, pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
+            issue_step_loads<BITS, false, MT>(r0, pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
             t1 = tile_sums(r1);
         }
 #pragma unroll
@@ -368,7 +387,7 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
         if (TG == 2) reduce_group(t0, cur.i, cf_a);
         t1 = zero;
         if (left > 2) {
-            issue_step_loads<BITS, false>(r1, pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
+            issue_step_loads<BITS, false, MT>(r1, pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
             t1 = tile_sums(r2);
         }
         if (TG == 2) {
@@ -392,8 +411,8 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
             if (behind == 1) { take(r0, r1); take(r1, r2); take(r2, r3); }
             else if (behind == 2) { StepRegs<BITS> t; take(t, r0); take(r0, r2); take(r1, r3); take(r2, t); }
             else { StepRegs<BITS> t, u; take(t, r0); take(u, r1); take(r0, r3); take(r1, t); take(r2, u); }
-            r0.cf = load_multipliers<NC>(rs_lut, cur.v0, cur.v1, lane);
-            if (TG == 2) r2.cf = load_multipliers<NC>(rs_lut, cur.v0 + 2, cur.v1, lane);
+            r0.cf = load_multipliers<NC, NB>(rs_lut, cur.v0, cur.v1, lane);
+            if (TG == 2) r2.cf = load_multipliers<NC, NB>(rs_lut, cur.v0 + 2, cur.v1, lane);
             behind = 0;
         }
         for (cur.i = 0; cur.i + 4 <= cur.steps;) full_turn();
@@ -401,8 +420,8 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
     };
 
     // the remaining two sets of the pipeline
-    issue_step_loads<BITS, false>(rs[1], pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
-    issue_step_loads<BITS, TG == 2>(rs[2], pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
+    issue_step_loads<BITS, false, MT>(rs[1], pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
+    issue_step_loads<BITS, TG == 2, MT>(rs[2], pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
     while (!cur.done) {
         // (no workgroup synchronisation at the start of a visit: activations and multipliers are
         // per wave; the barrier that ends a visit's epilogue protects the reuse of `part`)
@@ -411,18 +430,21 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
         for (cur.sg = 0; cur.sg < nseg; ++cur.sg) {
             {   // smooth this thread's 8 activations of the segment (loaded one segment ago)
                 const bool in_k = wave_chunk(cur.sg, wave, lane >> 5) < kc;
-                half8 o;
-                if (!quantised) {
 #pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        o[e] = !in_k ? (_Float16)0.0f : smooth_one((uint16_t)(xv[e >> 1] >> (16 * (e & 1))), e < 4 ? s0[e] : s1[e - 4]);
-                } else {   // wave-uniform branch
+                for (int t = 0; t < MT; ++t) {
+                    half8 o;
+                    if (!quantised) {
 #pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        o[e] = !in_k ? (_Float16)0.0f
-                                     : quantise_one((uint16_t)(xv[e >> 1] >> (16 * (e & 1))), make_divisor(e < 4 ? s0[e] : s1[e - 4], pb.act_scale));
+                        for (int e = 0; e < 8; ++e)
+                            o[e] = !in_k ? (_Float16)0.0f : smooth_one((uint16_t)(xv[t][e >> 1] >> (16 * (e & 1))), e < 4 ? s0[e] : s1[e - 4]);
+                    } else {   // wave-uniform branch
+#pragma unroll
+                        for (int e = 0; e < 8; ++e)
+                            o[e] = !in_k ? (_Float16)0.0f
+                                         : quantise_one((uint16_t)(xv[t][e >> 1] >> (16 * (e & 1))), make_divisor(e < 4 ? s0[e] : s1[e - 4], pb.act_scale));
+                    }
+                    *reinterpret_cast<half8 *>(&xs_lds[t * kSegHalfs + 8 * threadIdx.x]) = o;
                 }
-                *reinterpret_cast<half8 *>(&xs_lds[8 * threadIdx.x]) = o;
                 // next segment's activations: of this visit, or segment 0 again for the next visit
                 const bool more = cur.sg + 1 < nseg;
                 load_x(more ? cur.sg + 1 : 0, more || cur.v1 < cur.range_end);
@@ -431,18 +453,23 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
             for (int ch = 0; ch < kBCH; ++ch) {
                 chunk_in_k[ch] = wave_chunk(cur.sg, wave, ch) < kc;
 #pragma unroll
-                for (int g = 0; g < 8; ++g)   // written by this wave only: no barrier
-                    A[ch][g] = *reinterpret_cast<const uint4v *>(&xs_lds[(wave * kBCH + ch) * kTileCols + 64 * q + 8 * g]);
+                for (int t = 0; t < MT; ++t)
+#pragma unroll
+                    for (int g = 0; g < 8; ++g)   // written by this wave only: no barrier
+                        A[t][ch][g] = *reinterpret_cast<const uint4v *>(&xs_lds[t * kSegHalfs + (wave * kBCH + ch) * kTileCols + 64 * q + 8 * g]);
             }
             run_turns();
         }
         __syncthreads();
         // ---- visit epilogue: add the waves' slots in a fixed order, round once, store
         for (int e = threadIdx.x; e < (cur.v1 - cur.v0) * 16; e += NT) {
-            float sum = 0.f;
 #pragma unroll
-            for (int w = 0; w < kBW; ++w) sum += part[w * (kVisitTiles * 16) + e];
-            pb.y[(size_t)cur.v0 * kTileRows + e] = __builtin_bit_cast(uint16_t, (_Float16)(sum * out_scale));
+            for (int t = 0; t < MT; ++t) {   // token t's row of y starts N outputs after token t - 1's
+                float sum = 0.f;
+#pragma unroll
+                for (int w = 0; w < kBW; ++w) sum += part[t * kPartFloats + w * (kVisitTiles * 16) + e];
+                pb.y[(size_t)t * pb.nt * kTileRows + (size_t)cur.v0 * kTileRows + e] = __builtin_bit_cast(uint16_t, (_Float16)(sum * out_scale));
+            }
         }
         cursor_next_visit(cur);
         if (!cur.done) __syncthreads();   // the next visit's waves overwrite their slots
@@ -772,7 +799,9 @@ int launch_decode_group(const GroupItem *items, int count, int M, int bits, void
     hipStream_t stream = (hipStream_t)stream_;
     BucketBatch batch{};
     int tiles = 0;
-    const bool tokens_path = M > 1 || bits == 4;   // 4 bits: the register dequantiser serves one token too
+    // 4 bits: the register dequantiser serves one token too; 2 bits: the sparse-matrix-core kernel also takes
+    // two tokens (one sparse pass per token costs less than dequantising once)
+    const bool tokens_path = bits == 4 || M > 2 || (M == 2 && bits == 3);
     // several tokens: quantised activations are made once, ahead of the product, and so are smoothed
     // ones when the layers are wide (measured: the launch costs about 3.6 us; re-smoothing in every
     // workgroup costs 1.9 us for K = 4096 / 11008 and 4.3 us for K = 8192 / 28672)
@@ -780,19 +809,25 @@ int launch_decode_group(const GroupItem *items, int count, int M, int bits, void
     int widest = 0;
     for (int i = 0; i < count; ++i) widest = items[i].K > widest ? items[i].K : widest;
     if (tokens_path && (force_prepass || items[0].act_scale != 0.0f || widest >= kPrepassMinK)) {
+        // layers that read the same input (same x, s, K and quantisation step: q/k/v or gate/up of a decoder
+        // block) share one transformed copy
         TransformBatch qb{};
         size_t offset = 0;
-        int max_k = 0;
+        int max_k = 0, distinct = 0;
         for (int i = 0; i < count; ++i) {
+            for (int d = 0; d < distinct && !codes[i]; ++d)
+                if (qb.p[d].x == items[i].x && qb.p[d].s == items[i].s && qb.p[d].K == items[i].K && qb.p[d].s_q == items[i].act_scale)
+                    codes[i] = qb.p[d].codes;
+            if (codes[i]) continue;
             uint16_t *dst = reinterpret_cast<uint16_t *>(static_cast<char *>(workspace) + offset);
-            qb.p[i] = TransformItem{items[i].x, items[i].s, dst, items[i].K, items[i].act_scale};
+            qb.p[distinct++] = TransformItem{items[i].x, items[i].s, dst, items[i].K, items[i].act_scale};
             codes[i] = dst;
             offset += decode_codes_bytes(M, items[i].K);
             if (items[i].K > max_k) max_k = items[i].K;
         }
         const int per_block = kQuantThreads * 8;
         void *qargs[] = {&qb, const_cast<int *>(&M)};
-        if (hipError_t e = hipLaunchKernel((const void *)transform_kernel, dim3((max_k + per_block - 1) / per_block, count, (M + kQuantTokens - 1) / kQuantTokens),
+        if (hipError_t e = hipLaunchKernel((const void *)transform_kernel, dim3((max_k + per_block - 1) / per_block, distinct, (M + kQuantTokens - 1) / kQuantTokens),
                                            dim3(kQuantThreads), qargs, 0, stream)) return (int)e;
     }
     for (int i = 0; i < count; ++i) {
@@ -812,8 +847,9 @@ int launch_decode_group(const GroupItem *items, int count, int M, int bits, void
     int grid = num_cus();
     if (grid > tiles) grid = tiles;
     if (grid < count) grid = count;
-    const double startup_steps = tokens_path ? 3.0 : bits == 2 ? 3.5 : 2.0;
-    const double segment_steps = tokens_path ? 1.5 : bits == 2 ? 1.8 : 0.4;
+    const bool light_steps = !tokens_path && bits == 2 && M == 1;   // one sparse pass per tile: a step is short next to the fixed costs
+    const double startup_steps = tokens_path ? 3.0 : light_steps ? 3.5 : 2.0;
+    const double segment_steps = tokens_path ? 1.5 : light_steps ? 1.8 : 0.4;
     const double step_overhead = tokens_path ? 0.3 : 0.1;   // per tile and segment: barrier / bookkeeping
     auto split = [&](int ch, int *nwg) {
         const int seg = kBW * ch;
@@ -908,15 +944,15 @@ int launch_decode_group(const GroupItem *items, int count, int M, int bits, void
     size_t lds;
     const void *fn;
     if (!tokens_path) {
-        lds = (size_t)kBSeg * kTileCols * 2 + (size_t)kBW * kVisitTiles * 16 * 4;
-        fn = bits == 2 ? (const void *)gemv_bucket_kernel<2> : (const void *)gemv_bucket_kernel<3>;
+        lds = (size_t)M * ((size_t)kBSeg * kTileCols * 2 + (size_t)kBW * kVisitTiles * 16 * 4);
+        fn = bits == 3 ? (const void *)gemv_bucket_kernel<3> : M == 2 ? (const void *)gemv_bucket_kernel<2, 2> : (const void *)gemv_bucket_kernel<2>;
     } else {
         lds = (size_t)kBW * 16 * kStageStride * 2 + (size_t)2 * 2 * kBW * 256 * 4 + (size_t)kVisitTiles * 256 * 4;
         fn = bits == 2 ? (const void *)gemv_tokens_kernel<2, kBCH> : bits == 3 ? (const void *)gemv_tokens_kernel<3, kBCH>
                                                                               : (const void *)gemv_tokens_kernel<4, kBCH>;
     }
-    static bool lds_set[2][3] = {};
-    const int variant = tokens_path ? 1 : 0;
+    static bool lds_set[3][3] = {};
+    const int variant = tokens_path ? 1 : M == 2 ? 2 : 0;
     if (!lds_set[variant][bits - 2]) {
         if (hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)) return (int)e;
         lds_set[variant][bits - 2] = true;

@@ -83,6 +83,11 @@ def test_config2_batched_decode_full_size_every_output():
     _check_every_output(2, 16)
 
 
+def test_config2_shapes_two_tokens_full_size_every_output():
+    # two tokens at 2 bits run on the sparse-matrix-core kernel (one pass per token)
+    _check_every_output(2, 2)
+
+
 @pytest.mark.parametrize("M", [1, 8])
 def test_config4_70b_mlp_full_size_every_output(M):
     _check_every_output(4, M)

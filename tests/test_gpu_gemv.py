@@ -26,11 +26,12 @@ def test_gemv_m1_runs_of_every_length_modulo_four(bits, tiles_per_workgroup, K):
     # row tiles (one visit in one K segment) whose length is no multiple of four ends in a short turn and
     # hands the next run its loads in other sets.  One layer over all compute units gives every workgroup
     # the same run length: 3, 5, 6, 7 (remainders 3, 1, 2, 3) with two or three segments, and 33 = a full
-    # visit of 32 plus one tile.  M = 2 takes the other kernel over the same sequence.
+    # visit of 32 plus one tile.  M = 2 takes the two-token variant of that kernel at 2 bits and the
+    # dequantising kernel at 3 bits over the same sequence; M = 3 the dequantising kernel.
     import torch
     cus = torch.cuda.get_device_properties(0).multi_processor_count
     N = cus * tiles_per_workgroup * 16
-    for M in (1, 2):
+    for M in (1, 2, 3):
         layer = synth.make_layer_uniform(N, K, bits, M, seed=100 * tiles_per_workgroup + bits + M)
         err = check_layer(layer, bits)
         print(N, K, bits, M, err)
@@ -73,7 +74,7 @@ def test_gemv_is_deterministic():
     assert np.array_equal(y1.view(np.uint16), y2.view(np.uint16))
 
 
-@pytest.mark.parametrize("bits,M", [(3, 1), (2, 1), (2, 4), (4, 1), (4, 7)])
+@pytest.mark.parametrize("bits,M", [(3, 1), (2, 1), (2, 2), (3, 2), (2, 4), (4, 1), (4, 7)])
 def test_grouped_launch_matches_oracle_and_single_calls(bits, M):
     # a mixed group: different N and K per layer, one launch
     import torch
@@ -117,7 +118,7 @@ def test_grouped_config_full_size_every_output(cfg):
         assert_parity(p[4].cpu().numpy(), Y, what=(cfg, spec))
 
 
-@pytest.mark.parametrize("bits,M,quantised", [(3, 1, False), (2, 16, False), (2, 16, True), (4, 3, True), (3, 1, True)])
+@pytest.mark.parametrize("bits,M,quantised", [(3, 1, False), (2, 16, False), (2, 16, True), (4, 3, True), (3, 1, True), (2, 2, False), (2, 2, True)])
 def test_grouped_launch_replayed_from_a_hip_graph(bits, M, quantised):
     # the launch configuration bench.py times: the grouped call captured once, replayed several times
     # with eager work and synchronisations in between; every replay must reproduce the eager result
@@ -163,7 +164,7 @@ def test_grouped_launch_replayed_from_a_hip_graph(bits, M, quantised):
 
 
 @pytest.mark.parametrize("bits", [2, 3, 4])
-@pytest.mark.parametrize("M", [1, 5, 16])
+@pytest.mark.parametrize("M", [1, 2, 5, 16])
 @pytest.mark.parametrize("shape", [(64, 1024), (48, 11008)])
 def test_gemv_q8_matches_the_quantised_oracle(bits, M, shape):
     # input transformation (Eq. 10-11, b = 8) in front of the product; s_q such that ~1 % of the codes clip
@@ -179,7 +180,7 @@ def test_gemv_q8_matches_the_quantised_oracle(bits, M, shape):
     assert err["max_rel_floored"] <= 1e-3, err      # only fp32 accumulation and the fp16 store differ
 
 
-@pytest.mark.parametrize("M", [1, 4, 16])
+@pytest.mark.parametrize("M", [1, 2, 4, 16])
 def test_gemv_q8_codes_are_bit_exact(M):
     # identity layer (row n reads column n through a one-hot codebook): y[m][n] = s_q * q[m][n], so the
     # quantiser's integer decisions are visible one by one; s_q = 2^-3 keeps the scaling exact.
@@ -304,3 +305,37 @@ def test_gemv_q8_decides_hard_cases_like_the_binary32_oracle():
             y = lcd.lcd_lut_gemv_q8(packed, lut, to_dev(x), to_dev(s), s_q, N, bits).cpu().numpy()
             got = np.rint(y.astype(np.float64) / s_q).astype(np.int32)      # y = fp16(s_q * q): q is recoverable
             assert np.array_equal(got, expect), (M, bits16, s0, s_q, got[:, 0], expect[:, 0])
+
+
+@pytest.mark.parametrize("bits,M,quantised", [(2, 4, True), (3, 16, False), (4, 2, True), (2, 1, True)])
+def test_grouped_decode_layers_that_share_an_input(bits, M, quantised):
+    # q/k/v-like: three layers read ONE x and s (same pointers), so the ahead-of-time transformation keeps
+    # one copy for them; a fourth layer with the same K has its own input and (quantised) a fifth shares x
+    # with another step.  Not quantised: one layer is wide enough (K >= 16384) to send the whole group through
+    # the ahead-of-time route.  Every output against the oracle and against the single calls.
+    import torch
+    from paper_2506_12038_amd.binding import GemvGroup
+    K = 1024 if quantised else 16384
+    base = synth.make_layer(2, 0, 64, K, bits, M, seed_offset=1)
+    other = synth.make_layer(2, 1, 64, K, bits, M, seed_offset=2)
+    x0, s0, x1, s1 = to_dev(base["x"]), to_dev(base["s"]), to_dev(other["x"]), to_dev(other["s"])
+    step = lambda L: float(np.float32(np.quantile(np.abs(L["x"].astype(np.float64) / L["s"]), 0.99) / 127.0))
+    specs = [(48, x0, s0, base, step(base)), (16, x0, s0, base, step(base)), (80, x0, s0, base, step(base)),
+             (32, x1, s1, other, step(other)), (64, x0, s0, base, step(base) * 1.5)]
+    problems, refs = [], []
+    for i, (N, x, s, src, s_q) in enumerate(specs):
+        w = synth.make_layer(2, 10 + i, N, K, bits, 1, seed_offset=i)
+        packed = lcd.lcd_pack_indices(to_dev(w["idx"]), bits)
+        lut = lcd.lcd_build_lut(to_dev(w["codebook"]), bits)
+        y = torch.full((M, N), float("nan"), dtype=torch.float16, device="cuda")
+        problems.append((packed, lut, x, s, y, N))
+        if quantised:
+            refs.append((oracle.quantised_lut_matmul(w["codebook"], w["idx"], src["x"], src["s"], s_q, bits),
+                         lcd.lcd_lut_gemv_q8(packed, lut, x, s, s_q, N, bits), 1e-3))
+        else:
+            refs.append((oracle.lut_matmul(w["codebook"], w["idx"], src["x"], src["s"], bits), lcd.lcd_lut_gemv(packed, lut, x, s, N, bits), TOL))
+    GemvGroup(problems, bits, s_q=[sp[4] for sp in specs] if quantised else None)()
+    torch.cuda.synchronize()
+    for p, (Y, single, tol) in zip(problems, refs):
+        assert torch.equal(p[4], single)
+        assert_parity(p[4].cpu().numpy(), Y, tol)
