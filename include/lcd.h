@@ -128,13 +128,13 @@ lcd_status lcd_build_lut(const uint16_t *codebook /*DEVICE*/, int N, int bits,
  * y       DEVICE fp16 [M][N] row-major (written, never read)
  * workspace  DEVICE, >= lcd_workspace_bytes(M,N,K,bits) bytes, contents ignored on entry.
  *
- * lcd_lut_gemv: decode path, 1 <= M <= 16, one kernel launch, any K.  M = 1: centroid-bucket
- *               sums on the sparse matrix core (Sec. 4.2); 2 <= M <= 16, and every M with
- *               4 bits: register dequantisation into fp16 MFMA operands with the tokens as the
- *               matrix columns.  The smoothing
- *               is fused into the kernel, except for M >= 2 with K >= 16384, where a small
- *               kernel ahead of the product leaves the smoothed activations in the workspace
- *               (same rounding, same result).
+ * lcd_lut_gemv: decode path, 1 <= M <= 16, one kernel launch, any K.  M = 1 (and M = 2 with
+ *               2 bits): centroid-bucket sums on the sparse matrix core (Sec. 4.2), one sparse
+ *               pass per token; otherwise (3 <= M <= 16, M = 2 with 3 bits, every M with 4 bits):
+ *               register dequantisation into fp16 MFMA operands with the tokens as the matrix
+ *               columns.  The smoothing is fused into the kernel, except on the dequantising
+ *               route with K >= 16384, where a small kernel ahead of the product leaves the
+ *               smoothed activations in the workspace (same rounding, same result).
  * lcd_lut_gemm: prefill path, any M >= 1 (tuned for M >= 64): a smoothing kernel into the
  *               workspace, then register dequantisation into fp16 MFMA operands.
  * Both give bit-identical results from run to run (fixed reduction order).
