@@ -848,9 +848,13 @@ int launch_decode_group(const GroupItem *items, int count, int M, int bits, void
     if (grid > tiles) grid = tiles;
     if (grid < count) grid = count;
     const bool light_steps = !tokens_path && bits == 2 && M == 1;   // one sparse pass per tile: a step is short next to the fixed costs
-    const double startup_steps = tokens_path ? 3.0 : light_steps ? 3.5 : 2.0;
-    const double segment_steps = tokens_path ? 1.5 : light_steps ? 1.8 : 0.4;
-    const double step_overhead = tokens_path ? 0.3 : 0.1;   // per tile and segment: barrier / bookkeeping
+    // the several-token kernel, measured per workgroup (unit: the time of two chunks of one row tile, about 1 us):
+    // smoothing inside the kernel, a segment switch re-stages 16 tokens x 512 columns per wave (2.3); with the
+    // activations transformed ahead it only permutes them (1.5)
+    const bool staged_ahead = tokens_path && codes[0] != nullptr;
+    const double startup_steps = tokens_path ? (staged_ahead ? 0.5 : 0.7) : light_steps ? 3.5 : 2.0;
+    const double segment_steps = tokens_path ? (staged_ahead ? 1.5 : 2.3) : light_steps ? 1.8 : 0.4;
+    const double step_overhead = tokens_path ? (staged_ahead ? 0.22 : 0.3) : 0.1;   // per tile and segment: barrier / bookkeeping
     auto split = [&](int ch, int *nwg) {
         const int seg = kBW * ch;
         auto layer_time = [&](int i, int n) {
@@ -911,16 +915,16 @@ int launch_decode_group(const GroupItem *items, int count, int M, int bits, void
         }
     };
     // the split depends on the shapes only: the last one is kept (serving loops repeat a few groups)
-    struct SplitMemo { int count, M, bits, grid, nt[kMaxGroup], kc[kMaxGroup], nwg[kMaxGroup]; };
+    struct SplitMemo { int count, M, bits, grid, ahead, nt[kMaxGroup], kc[kMaxGroup], nwg[kMaxGroup]; };
     static thread_local SplitMemo memo = {};
-    bool known = memo.count == count && memo.M == M && memo.bits == bits && memo.grid == grid;
+    bool known = memo.count == count && memo.M == M && memo.bits == bits && memo.grid == grid && memo.ahead == (int)staged_ahead;
     for (int i = 0; known && i < count; ++i) known = memo.nt[i] == batch.p[i].nt && memo.kc[i] == batch.p[i].kc;
     int nwg[kMaxGroup];
     if (known) {
         for (int i = 0; i < count; ++i) nwg[i] = memo.nwg[i];
     } else {
         split(kBCH, nwg);
-        memo.count = count; memo.M = M; memo.bits = bits; memo.grid = grid;
+        memo.count = count; memo.M = M; memo.bits = bits; memo.grid = grid; memo.ahead = (int)staged_ahead;
         for (int i = 0; i < count; ++i) { memo.nt[i] = batch.p[i].nt; memo.kc[i] = batch.p[i].kc; memo.nwg[i] = nwg[i]; }
     }
     grid = 0;
