@@ -855,15 +855,16 @@ int launch_decode_group(const GroupItem *items, int count, int M, int bits, void
     const double startup_steps = tokens_path ? (staged_ahead ? 0.5 : 0.7) : light_steps ? 3.5 : 2.0;
     const double segment_steps = tokens_path ? (staged_ahead ? 1.5 : 2.3) : light_steps ? 1.8 : 0.4;
     const double step_overhead = tokens_path ? (staged_ahead ? 0.22 : 0.3) : 0.1;   // per tile and segment: barrier / bookkeeping
-    auto split = [&](int ch, int *nwg) {
+    auto layer_time_with = [&](int ch, int i, int n) {
         const int seg = kBW * ch;
-        auto layer_time = [&](int i, int n) {
-            const int kc = batch.p[i].kc, segs = (kc + seg - 1) / seg, rest = kc % seg;
-            const double steps_per_tile = (kc / seg) * (0.5 * ch + step_overhead) +
-                                          (rest ? 0.5 * ((rest + kBW - 1) / kBW) + step_overhead : 0.0);
-            const int t = (batch.p[i].nt + n - 1) / n, visits = (t + kVisitTiles - 1) / kVisitTiles;
-            return startup_steps + steps_per_tile * t + segs * visits * segment_steps;
-        };
+        const int kc = batch.p[i].kc, segs = (kc + seg - 1) / seg, rest = kc % seg;
+        const double steps_per_tile = (kc / seg) * (0.5 * ch + step_overhead) +
+                                      (rest ? 0.5 * ((rest + kBW - 1) / kBW) + step_overhead : 0.0);
+        const int t = (batch.p[i].nt + n - 1) / n, visits = (t + kVisitTiles - 1) / kVisitTiles;
+        return startup_steps + steps_per_tile * t + segs * visits * segment_steps;
+    };
+    auto split = [&](int ch, int *nwg) {
+        auto layer_time = [&](int i, int n) { return layer_time_with(ch, i, n); };
         // smallest number of workgroups with which layer i takes at most T (0: not even one per tile does)
         auto need = [&](int i, double T) {
             const int nt = batch.p[i].nt;
@@ -926,6 +927,18 @@ int launch_decode_group(const GroupItem *items, int count, int M, int bits, void
         split(kBCH, nwg);
         memo.count = count; memo.M = M; memo.bits = bits; memo.grid = grid; memo.ahead = (int)staged_ahead;
         for (int i = 0; i < count; ++i) { memo.nt[i] = batch.p[i].nt; memo.kc[i] = batch.p[i].kc; memo.nwg[i] = nwg[i]; }
+    }
+    // Workgroups are dispatched in the order of their ids, the last of a full grid almost 1 us after the
+    // first: the layers whose workgroups have the most to do take the lowest ids.
+    {
+        int order[kMaxGroup];
+        double t[kMaxGroup];
+        for (int i = 0; i < count; ++i) { order[i] = i; t[i] = layer_time_with(kBCH, i, nwg[i]); }
+        std::stable_sort(order, order + count, [&](int a, int b) { return t[a] > t[b]; });
+        BucketProblem sorted_p[kMaxGroup];
+        int sorted_n[kMaxGroup];
+        for (int q = 0; q < count; ++q) { sorted_p[q] = batch.p[order[q]]; sorted_n[q] = nwg[order[q]]; }
+        for (int q = 0; q < count; ++q) { batch.p[q] = sorted_p[q]; nwg[q] = sorted_n[q]; }
     }
     grid = 0;
     for (int i = 0; i < count; ++i) grid += nwg[i];
