@@ -26,10 +26,11 @@
  *     message (thread-local).
  *   - Shapes: bits in {2,3,4};  N % 16 == 0;  K % 256 == 0;  N, K >= 1 tile.
  *   - Two calls that share a workspace buffer must be ordered on one stream.
- *   - One device per process, and product calls from one thread at a time: the launchers keep a
- *     few host-side statics (the device's compute-unit count, "kernel attributes already set"
- *     flags) per process, not per device, and do not lock them.  The per-thread state is the error
- *     string and the remembered workgroup split of the last grouped decode call.
+ *   - Every call works on the current HIP device; the little state the launchers keep (the
+ *     device's compute-unit count, "dynamic-LDS limit raised" flags) is per device and atomic, and
+ *     the error string and the remembered workgroup split of the last grouped decode call are per
+ *     thread, so calls from several threads and on several devices of one process do not disturb
+ *     each other.  (This build is tested on one GPU.)
  */
 #ifndef LCD_H
 #define LCD_H

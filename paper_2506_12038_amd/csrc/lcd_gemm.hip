@@ -22,6 +22,7 @@
 #include <algorithm>
 #include "lcd_internal.h"
 #include "lcd_device.h"
+#include "lcd_launch.h"
 
 namespace lcd {
 
@@ -641,12 +642,9 @@ int launch_gemm(const void *packed, const void *lut, const uint16_t *x, const fl
     const int tiles_per_xcd = (total_tiles + kXcds - 1) / kXcds;
     const dim3 grid(tiles_per_xcd * kXcds), block(kGemmWaves * 64);
     const size_t lds_bytes = 2 * kStageBytes;
-    static bool attr_set[3] = {false, false, false};
+    static PerDeviceFlags<3> lds_raised;
     const void *fn = bits == 2 ? (const void *)gemm_kernel<2> : bits == 3 ? (const void *)gemm_kernel<3> : (const void *)gemm_kernel<4>;
-    if (!attr_set[bits - 2]) {
-        if (hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes)) return (int)e;
-        attr_set[bits - 2] = true;
-    }
+    if (hipError_t e = raise_lds_limit_once(lds_raised, bits - 2, fn, lds_bytes)) return (int)e;
     const uint8_t *packed_arg = static_cast<const uint8_t *>(packed), *xs_arg = static_cast<const uint8_t *>(workspace);
     int M_arg = M, Mpad_arg = Mpad, N_arg = N, K_arg = K, rows_arg = grid_rows, xcd_arg = tiles_per_xcd;
     float scale_arg = act_scale != 0.0f ? act_scale : 1.0f;
@@ -697,12 +695,9 @@ int launch_gemm_group(const GroupItem *items, int count, int M, int bits, void *
     batch.count = count; batch.M = M; batch.Mpad = Mpad;
     if (int e = launch_smooth_group(sm, distinct, M, Mpad, stream)) return e;
     const size_t lds_bytes = 2 * kStageBytes;
-    static bool attr_set[3] = {false, false, false};
+    static PerDeviceFlags<3> lds_raised;
     const void *fn = bits == 2 ? (const void *)gemm_group_kernel<2> : bits == 3 ? (const void *)gemm_group_kernel<3> : (const void *)gemm_group_kernel<4>;
-    if (!attr_set[bits - 2]) {
-        if (hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes)) return (int)e;
-        attr_set[bits - 2] = true;
-    }
+    if (hipError_t e = raise_lds_limit_once(lds_raised, bits - 2, fn, lds_bytes)) return (int)e;
     void *args[] = {&batch};
     if (hipError_t e = hipLaunchKernel(fn, dim3((unsigned)queue * kXcds), dim3(kGemmWaves * 64), args, lds_bytes, stream)) return (int)e;
     return (int)hipGetLastError();

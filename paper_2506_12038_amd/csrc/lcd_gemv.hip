@@ -26,6 +26,7 @@
 #include <mutex>
 #include "lcd_internal.h"
 #include "lcd_device.h"
+#include "lcd_launch.h"
 
 
 namespace lcd {
@@ -782,15 +783,18 @@ __global__ __launch_bounds__(kQuantThreads) void transform_kernel(TransformBatch
     }
 }
 
-static int g_num_cus = 0;
+// compute units of the current device (looked up once per device)
 static int num_cus()
 {
-    if (g_num_cus == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
-        g_num_cus = n;
+    static std::atomic<int> cus[kMaxDevices] = {};
+    const int dev = current_device();
+    if (dev < 0) return 256;
+    int n = cus[dev].load(std::memory_order_relaxed);
+    if (n == 0) {
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cus[dev].store(n, std::memory_order_relaxed);
     }
-    return g_num_cus;
+    return n;
 }
 
 // One launch for a group of decode problems: the bucket kernel for one token, the tokens kernel for 2..16.
@@ -968,12 +972,9 @@ int launch_decode_group(const GroupItem *items, int count, int M, int bits, void
         fn = bits == 2 ? (const void *)gemv_tokens_kernel<2, kBCH> : bits == 3 ? (const void *)gemv_tokens_kernel<3, kBCH>
                                                                               : (const void *)gemv_tokens_kernel<4, kBCH>;
     }
-    static bool lds_set[3][3] = {};
+    static PerDeviceFlags<9> lds_raised;
     const int variant = tokens_path ? 1 : M == 2 ? 2 : 0;
-    if (!lds_set[variant][bits - 2]) {
-        if (hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds)) return (int)e;
-        lds_set[variant][bits - 2] = true;
-    }
+    if (hipError_t e = raise_lds_limit_once(lds_raised, variant * 3 + (bits - 2), fn, lds)) return (int)e;
     void *args[] = {&table.t[0], &table.t[1], &table.t[2], &table.t[3], &table.t[4], &table.t[5], &table.t[6], &table.t[7],
                     &batch, const_cast<int *>(&M)};   // the bucket kernel takes no M
     if (hipError_t e = hipLaunchKernel(fn, dim3(grid), dim3(kBW * 64), args, lds, stream)) return (int)e;
@@ -985,7 +986,6 @@ int launch_decode_group(const GroupItem *items, int count, int M, int bits, void
 // columns, fp16) in this file-scope device array instead of a workspace the caller brings.  Every GPU
 // holds its own copy at its own address; the array's name is only a host-side handle, so the device
 // address is asked for once per device and kernels are given that address.
-constexpr int kMaxDevices = 64;
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 static void *g_scratch_ptr[kMaxDevices] = {};
 static std::mutex g_scratch_mutex;
