@@ -68,6 +68,7 @@ def test_golden_bytes_hand_worked():
     expect = np.zeros(1024, dtype=np.uint8)
     expect[0] = 0x03; expect[17] = 0x08; expect[288] = 0x01; expect[1023] = 0xC0
     assert np.array_equal(p, expect)
+    assert np.array_equal(pack_ref(idx, 2), expect)          # the oracle's layout packer against the same hand-worked bytes
     # 3-bit: same low fields plus the third-bit plane.
     #  (n=0,k=0)=7:  w=0 -> d=0,a=0,e=0 -> word 0 of lane 0, bit 0        -> byte 1024 = 0x01
     #  (n=1,k=5)=6:  w=5 -> d=0,a=0,e=5 -> bit 8*(1+2)+0+0 = 24           -> byte 1024+8+3 = 0x01
@@ -79,6 +80,7 @@ def test_golden_bytes_hand_worked():
     e3[0] = 0x03; e3[17] = 0x08
     e3[1024] = 0x01; e3[1024 + 8 + 3] = 0x01; e3[1024 + 144 + 4 + 2] = 0x08
     assert np.array_equal(p3, e3)
+    assert np.array_equal(pack_ref(idx3, 3), e3)
     # 4-bit: the low fields as before, index bits 3:2 in the same arrangement 1024 bytes further on.
     #  (n=0,k=0)=15    -> low byte 0 = 0x03, high field: bits [1:0] of tile byte 1024      -> 0x03
     #  (n=1,k=5)=9     -> low = 1: byte 17 = 0x04; high = 2: bits [11:10] at byte 1024+16  -> byte 1041 = 0x08
@@ -91,6 +93,7 @@ def test_golden_bytes_hand_worked():
     e4[0] = 0x03; e4[17] = 0x04; e4[1023] = 0x80
     e4[1024] = 0x03; e4[1041] = 0x08; e4[1312] = 0x01; e4[2047] = 0xC0
     assert np.array_equal(p4, e4)
+    assert np.array_equal(pack_ref(idx4, 4), e4)
 
 
 def test_host_packer_rejects_out_of_range_and_bad_shapes():
