@@ -62,3 +62,45 @@ def test_random_groups(seed):
     for (packed, lut, x, s, y, N), Y in zip(problems, refs):
         err = oracle.parity_errors(y.cpu().numpy(), Y)
         assert err["max_rel_floored"] <= (1e-3 if quantised else TOL), (seed, N, err)
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_prefill_groups(seed):
+    # grouped prefill with random shapes, token counts, index widths; some layers read the input of the
+    # layer before them (same tensors), with fp16 activations or INT8 codes
+    import torch
+    from paper_2506_12038_amd.binding import GemmGroup
+    rng = np.random.default_rng(3000 + seed)
+    count = int(rng.integers(1, 7))
+    bits = int(rng.integers(2, 5))
+    M = int(rng.choice([1, 17, 64, 100, 128, 129, 300]))
+    quantised = bool(rng.integers(0, 2))
+    problems, refs, steps = [], [], []
+    prev = None
+    for i in range(count):
+        N, K = _draw(rng, max_weights=400_000)
+        share = prev is not None and bool(rng.integers(0, 2))
+        if share:                                   # same K, same x and s tensors as the layer before
+            K, src, x, s, s_q = prev
+        else:
+            src = synth.make_layer(3, i, 16, K, bits, M, seed_offset=100 * seed + i)
+            x, s = to_dev(src["x"]), to_dev(src["s"])
+            s_q = float(np.float32(np.quantile(np.abs(src["x"].astype(np.float64) / src["s"]), 0.99) / 127.0))
+        prev = (K, src, x, s, s_q)
+        w = synth.make_layer(3, 20 + i, N, K, bits, 1, seed_offset=100 * seed + i)
+        packed = lcd.lcd_pack_indices(to_dev(w["idx"]), bits)
+        lut = lcd.lcd_build_lut(to_dev(w["codebook"]), bits)
+        y = torch.full((M, N), float("nan"), dtype=torch.float16, device="cuda")
+        problems.append((packed, lut, x, s, y, N))
+        steps.append(s_q)
+        if quantised:
+            refs.append(oracle.quantised_lut_matmul(w["codebook"], w["idx"], src["x"], src["s"], s_q, bits))
+        else:
+            refs.append(oracle.lut_matmul(w["codebook"], w["idx"], src["x"], src["s"], bits))
+    GemmGroup(problems, bits, s_q=steps if quantised else None)()
+    torch.cuda.synchronize()
+    for (packed, lut, x, s, y, N), Y in zip(problems, refs):
+        got = y.cpu().numpy()
+        assert np.all(np.isfinite(got.astype(np.float32)))
+        err = oracle.parity_errors(got, Y)
+        assert err["max_rel_floored"] <= (1e-3 if quantised else TOL), (seed, N, M, bits, err)
