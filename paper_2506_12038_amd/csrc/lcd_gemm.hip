@@ -53,232 +53,60 @@ typedef __attribute__((address_space(1))) const uint32_t glb_u32;
 // instruction occupies the matrix pipe for 32 cycles, so the two issue cycles are hidden.
 template <int IDX> __device__ __forceinline__ void mfma_acc(uint4v a, uint4v b);
 template <int IDX> __device__ __forceinline__ float16v read_acc();
-template <> __device__ __forceinline__ void mfma_acc<0>(uint4v a, uint4v b)
-{
-    asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_f16 a[0:15], %0, %1, a[0:15]" : : "v"(a), "v"(b) : "a0", "a1", "a2", "a3", "a4", "a5", "a6", "a7", "a8", "a9", "a10", "a11", "a12", "a13", "a14", "a15");
-}
-template <> __device__ __forceinline__ float16v read_acc<0>()
-{
-    float16v v;
-    float t0, t1, t2, t3, t4, t5, t6, t7, t8, t9, t10, t11, t12, t13, t14, t15;
-    asm volatile("v_accvgpr_read_b32 %0, a0\n\tv_accvgpr_read_b32 %1, a1\n\tv_accvgpr_read_b32 %2, a2\n\tv_accvgpr_read_b32 %3, a3\n\tv_accvgpr_read_b32 %4, a4\n\tv_accvgpr_read_b32 %5, a5\n\tv_accvgpr_read_b32 %6, a6\n\tv_accvgpr_read_b32 %7, a7\n\tv_accvgpr_read_b32 %8, a8\n\tv_accvgpr_read_b32 %9, a9\n\tv_accvgpr_read_b32 %10, a10\n\tv_accvgpr_read_b32 %11, a11\n\tv_accvgpr_read_b32 %12, a12\n\tv_accvgpr_read_b32 %13, a13\n\tv_accvgpr_read_b32 %14, a14\n\tv_accvgpr_read_b32 %15, a15" : "=v"(t0), "=v"(t1), "=v"(t2), "=v"(t3), "=v"(t4), "=v"(t5), "=v"(t6), "=v"(t7), "=v"(t8), "=v"(t9), "=v"(t10), "=v"(t11), "=v"(t12), "=v"(t13), "=v"(t14), "=v"(t15));
-    v[0] = t0;
-    v[1] = t1;
-    v[2] = t2;
-    v[3] = t3;
-    v[4] = t4;
-    v[5] = t5;
-    v[6] = t6;
-    v[7] = t7;
-    v[8] = t8;
-    v[9] = t9;
-    v[10] = t10;
-    v[11] = t11;
-    v[12] = t12;
-    v[13] = t13;
-    v[14] = t14;
-    v[15] = t15;
-    return v;
-}
-template <> __device__ __forceinline__ void mfma_acc<1>(uint4v a, uint4v b)
-{
-    asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_f16 a[16:31], %0, %1, a[16:31]" : : "v"(a), "v"(b) : "a16", "a17", "a18", "a19", "a20", "a21", "a22", "a23", "a24", "a25", "a26", "a27", "a28", "a29", "a30", "a31");
-}
-template <> __device__ __forceinline__ float16v read_acc<1>()
-{
-    float16v v;
-    float t0, t1, t2, t3, t4, t5, t6, t7, t8, t9, t10, t11, t12, t13, t14, t15;
-    asm volatile("v_accvgpr_read_b32 %0, a16\n\tv_accvgpr_read_b32 %1, a17\n\tv_accvgpr_read_b32 %2, a18\n\tv_accvgpr_read_b32 %3, a19\n\tv_accvgpr_read_b32 %4, a20\n\tv_accvgpr_read_b32 %5, a21\n\tv_accvgpr_read_b32 %6, a22\n\tv_accvgpr_read_b32 %7, a23\n\tv_accvgpr_read_b32 %8, a24\n\tv_accvgpr_read_b32 %9, a25\n\tv_accvgpr_read_b32 %10, a26\n\tv_accvgpr_read_b32 %11, a27\n\tv_accvgpr_read_b32 %12, a28\n\tv_accvgpr_read_b32 %13, a29\n\tv_accvgpr_read_b32 %14, a30\n\tv_accvgpr_read_b32 %15, a31" : "=v"(t0), "=v"(t1), "=v"(t2), "=v"(t3), "=v"(t4), "=v"(t5), "=v"(t6), "=v"(t7), "=v"(t8), "=v"(t9), "=v"(t10), "=v"(t11), "=v"(t12), "=v"(t13), "=v"(t14), "=v"(t15));
-    v[0] = t0;
-    v[1] = t1;
-    v[2] = t2;
-    v[3] = t3;
-    v[4] = t4;
-    v[5] = t5;
-    v[6] = t6;
-    v[7] = t7;
-    v[8] = t8;
-    v[9] = t9;
-    v[10] = t10;
-    v[11] = t11;
-    v[12] = t12;
-    v[13] = t13;
-    v[14] = t14;
-    v[15] = t15;
-    return v;
-}
-template <> __device__ __forceinline__ void mfma_acc<2>(uint4v a, uint4v b)
-{
-    asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_f16 a[32:47], %0, %1, a[32:47]" : : "v"(a), "v"(b) : "a32", "a33", "a34", "a35", "a36", "a37", "a38", "a39", "a40", "a41", "a42", "a43", "a44", "a45", "a46", "a47");
-}
-template <> __device__ __forceinline__ float16v read_acc<2>()
-{
-    float16v v;
-    float t0, t1, t2, t3, t4, t5, t6, t7, t8, t9, t10, t11, t12, t13, t14, t15;
-    asm volatile("v_accvgpr_read_b32 %0, a32\n\tv_accvgpr_read_b32 %1, a33\n\tv_accvgpr_read_b32 %2, a34\n\tv_accvgpr_read_b32 %3, a35\n\tv_accvgpr_read_b32 %4, a36\n\tv_accvgpr_read_b32 %5, a37\n\tv_accvgpr_read_b32 %6, a38\n\tv_accvgpr_read_b32 %7, a39\n\tv_accvgpr_read_b32 %8, a40\n\tv_accvgpr_read_b32 %9, a41\n\tv_accvgpr_read_b32 %10, a42\n\tv_accvgpr_read_b32 %11, a43\n\tv_accvgpr_read_b32 %12, a44\n\tv_accvgpr_read_b32 %13, a45\n\tv_accvgpr_read_b32 %14, a46\n\tv_accvgpr_read_b32 %15, a47" : "=v"(t0), "=v"(t1), "=v"(t2), "=v"(t3), "=v"(t4), "=v"(t5), "=v"(t6), "=v"(t7), "=v"(t8), "=v"(t9), "=v"(t10), "=v"(t11), "=v"(t12), "=v"(t13), "=v"(t14), "=v"(t15));
-    v[0] = t0;
-    v[1] = t1;
-    v[2] = t2;
-    v[3] = t3;
-    v[4] = t4;
-    v[5] = t5;
-    v[6] = t6;
-    v[7] = t7;
-    v[8] = t8;
-    v[9] = t9;
-    v[10] = t10;
-    v[11] = t11;
-    v[12] = t12;
-    v[13] = t13;
-    v[14] = t14;
-    v[15] = t15;
-    return v;
-}
-template <> __device__ __forceinline__ void mfma_acc<3>(uint4v a, uint4v b)
-{
-    asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_f16 a[48:63], %0, %1, a[48:63]" : : "v"(a), "v"(b) : "a48", "a49", "a50", "a51", "a52", "a53", "a54", "a55", "a56", "a57", "a58", "a59", "a60", "a61", "a62", "a63");
-}
-template <> __device__ __forceinline__ float16v read_acc<3>()
-{
-    float16v v;
-    float t0, t1, t2, t3, t4, t5, t6, t7, t8, t9, t10, t11, t12, t13, t14, t15;
-    asm volatile("v_accvgpr_read_b32 %0, a48\n\tv_accvgpr_read_b32 %1, a49\n\tv_accvgpr_read_b32 %2, a50\n\tv_accvgpr_read_b32 %3, a51\n\tv_accvgpr_read_b32 %4, a52\n\tv_accvgpr_read_b32 %5, a53\n\tv_accvgpr_read_b32 %6, a54\n\tv_accvgpr_read_b32 %7, a55\n\tv_accvgpr_read_b32 %8, a56\n\tv_accvgpr_read_b32 %9, a57\n\tv_accvgpr_read_b32 %10, a58\n\tv_accvgpr_read_b32 %11, a59\n\tv_accvgpr_read_b32 %12, a60\n\tv_accvgpr_read_b32 %13, a61\n\tv_accvgpr_read_b32 %14, a62\n\tv_accvgpr_read_b32 %15, a63" : "=v"(t0), "=v"(t1), "=v"(t2), "=v"(t3), "=v"(t4), "=v"(t5), "=v"(t6), "=v"(t7), "=v"(t8), "=v"(t9), "=v"(t10), "=v"(t11), "=v"(t12), "=v"(t13), "=v"(t14), "=v"(t15));
-    v[0] = t0;
-    v[1] = t1;
-    v[2] = t2;
-    v[3] = t3;
-    v[4] = t4;
-    v[5] = t5;
-    v[6] = t6;
-    v[7] = t7;
-    v[8] = t8;
-    v[9] = t9;
-    v[10] = t10;
-    v[11] = t11;
-    v[12] = t12;
-    v[13] = t13;
-    v[14] = t14;
-    v[15] = t15;
-    return v;
-}
-template <> __device__ __forceinline__ void mfma_acc<4>(uint4v a, uint4v b)
-{
-    asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_f16 a[64:79], %0, %1, a[64:79]" : : "v"(a), "v"(b) : "a64", "a65", "a66", "a67", "a68", "a69", "a70", "a71", "a72", "a73", "a74", "a75", "a76", "a77", "a78", "a79");
-}
-template <> __device__ __forceinline__ float16v read_acc<4>()
-{
-    float16v v;
-    float t0, t1, t2, t3, t4, t5, t6, t7, t8, t9, t10, t11, t12, t13, t14, t15;
-    asm volatile("v_accvgpr_read_b32 %0, a64\n\tv_accvgpr_read_b32 %1, a65\n\tv_accvgpr_read_b32 %2, a66\n\tv_accvgpr_read_b32 %3, a67\n\tv_accvgpr_read_b32 %4, a68\n\tv_accvgpr_read_b32 %5, a69\n\tv_accvgpr_read_b32 %6, a70\n\tv_accvgpr_read_b32 %7, a71\n\tv_accvgpr_read_b32 %8, a72\n\tv_accvgpr_read_b32 %9, a73\n\tv_accvgpr_read_b32 %10, a74\n\tv_accvgpr_read_b32 %11, a75\n\tv_accvgpr_read_b32 %12, a76\n\tv_accvgpr_read_b32 %13, a77\n\tv_accvgpr_read_b32 %14, a78\n\tv_accvgpr_read_b32 %15, a79" : "=v"(t0), "=v"(t1), "=v"(t2), "=v"(t3), "=v"(t4), "=v"(t5), "=v"(t6), "=v"(t7), "=v"(t8), "=v"(t9), "=v"(t10), "=v"(t11), "=v"(t12), "=v"(t13), "=v"(t14), "=v"(t15));
-    v[0] = t0;
-    v[1] = t1;
-    v[2] = t2;
-    v[3] = t3;
-    v[4] = t4;
-    v[5] = t5;
-    v[6] = t6;
-    v[7] = t7;
-    v[8] = t8;
-    v[9] = t9;
-    v[10] = t10;
-    v[11] = t11;
-    v[12] = t12;
-    v[13] = t13;
-    v[14] = t14;
-    v[15] = t15;
-    return v;
-}
-template <> __device__ __forceinline__ void mfma_acc<5>(uint4v a, uint4v b)
-{
-    asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_f16 a[80:95], %0, %1, a[80:95]" : : "v"(a), "v"(b) : "a80", "a81", "a82", "a83", "a84", "a85", "a86", "a87", "a88", "a89", "a90", "a91", "a92", "a93", "a94", "a95");
-}
-template <> __device__ __forceinline__ float16v read_acc<5>()
-{
-    float16v v;
-    float t0, t1, t2, t3, t4, t5, t6, t7, t8, t9, t10, t11, t12, t13, t14, t15;
-    asm volatile("v_accvgpr_read_b32 %0, a80\n\tv_accvgpr_read_b32 %1, a81\n\tv_accvgpr_read_b32 %2, a82\n\tv_accvgpr_read_b32 %3, a83\n\tv_accvgpr_read_b32 %4, a84\n\tv_accvgpr_read_b32 %5, a85\n\tv_accvgpr_read_b32 %6, a86\n\tv_accvgpr_read_b32 %7, a87\n\tv_accvgpr_read_b32 %8, a88\n\tv_accvgpr_read_b32 %9, a89\n\tv_accvgpr_read_b32 %10, a90\n\tv_accvgpr_read_b32 %11, a91\n\tv_accvgpr_read_b32 %12, a92\n\tv_accvgpr_read_b32 %13, a93\n\tv_accvgpr_read_b32 %14, a94\n\tv_accvgpr_read_b32 %15, a95" : "=v"(t0), "=v"(t1), "=v"(t2), "=v"(t3), "=v"(t4), "=v"(t5), "=v"(t6), "=v"(t7), "=v"(t8), "=v"(t9), "=v"(t10), "=v"(t11), "=v"(t12), "=v"(t13), "=v"(t14), "=v"(t15));
-    v[0] = t0;
-    v[1] = t1;
-    v[2] = t2;
-    v[3] = t3;
-    v[4] = t4;
-    v[5] = t5;
-    v[6] = t6;
-    v[7] = t7;
-    v[8] = t8;
-    v[9] = t9;
-    v[10] = t10;
-    v[11] = t11;
-    v[12] = t12;
-    v[13] = t13;
-    v[14] = t14;
-    v[15] = t15;
-    return v;
-}
-template <> __device__ __forceinline__ void mfma_acc<6>(uint4v a, uint4v b)
-{
-    asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_f16 a[96:111], %0, %1, a[96:111]" : : "v"(a), "v"(b) : "a96", "a97", "a98", "a99", "a100", "a101", "a102", "a103", "a104", "a105", "a106", "a107", "a108", "a109", "a110", "a111");
-}
-template <> __device__ __forceinline__ float16v read_acc<6>()
-{
-    float16v v;
-    float t0, t1, t2, t3, t4, t5, t6, t7, t8, t9, t10, t11, t12, t13, t14, t15;
-    asm volatile("v_accvgpr_read_b32 %0, a96\n\tv_accvgpr_read_b32 %1, a97\n\tv_accvgpr_read_b32 %2, a98\n\tv_accvgpr_read_b32 %3, a99\n\tv_accvgpr_read_b32 %4, a100\n\tv_accvgpr_read_b32 %5, a101\n\tv_accvgpr_read_b32 %6, a102\n\tv_accvgpr_read_b32 %7, a103\n\tv_accvgpr_read_b32 %8, a104\n\tv_accvgpr_read_b32 %9, a105\n\tv_accvgpr_read_b32 %10, a106\n\tv_accvgpr_read_b32 %11, a107\n\tv_accvgpr_read_b32 %12, a108\n\tv_accvgpr_read_b32 %13, a109\n\tv_accvgpr_read_b32 %14, a110\n\tv_accvgpr_read_b32 %15, a111" : "=v"(t0), "=v"(t1), "=v"(t2), "=v"(t3), "=v"(t4), "=v"(t5), "=v"(t6), "=v"(t7), "=v"(t8), "=v"(t9), "=v"(t10), "=v"(t11), "=v"(t12), "=v"(t13), "=v"(t14), "=v"(t15));
-    v[0] = t0;
-    v[1] = t1;
-    v[2] = t2;
-    v[3] = t3;
-    v[4] = t4;
-    v[5] = t5;
-    v[6] = t6;
-    v[7] = t7;
-    v[8] = t8;
-    v[9] = t9;
-    v[10] = t10;
-    v[11] = t11;
-    v[12] = t12;
-    v[13] = t13;
-    v[14] = t14;
-    v[15] = t15;
-    return v;
-}
-template <> __device__ __forceinline__ void mfma_acc<7>(uint4v a, uint4v b)
-{
-    asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_f16 a[112:127], %0, %1, a[112:127]" : : "v"(a), "v"(b) : "a112", "a113", "a114", "a115", "a116", "a117", "a118", "a119", "a120", "a121", "a122", "a123", "a124", "a125", "a126", "a127");
-}
-template <> __device__ __forceinline__ float16v read_acc<7>()
-{
-    float16v v;
-    float t0, t1, t2, t3, t4, t5, t6, t7, t8, t9, t10, t11, t12, t13, t14, t15;
-    asm volatile("v_accvgpr_read_b32 %0, a112\n\tv_accvgpr_read_b32 %1, a113\n\tv_accvgpr_read_b32 %2, a114\n\tv_accvgpr_read_b32 %3, a115\n\tv_accvgpr_read_b32 %4, a116\n\tv_accvgpr_read_b32 %5, a117\n\tv_accvgpr_read_b32 %6, a118\n\tv_accvgpr_read_b32 %7, a119\n\tv_accvgpr_read_b32 %8, a120\n\tv_accvgpr_read_b32 %9, a121\n\tv_accvgpr_read_b32 %10, a122\n\tv_accvgpr_read_b32 %11, a123\n\tv_accvgpr_read_b32 %12, a124\n\tv_accvgpr_read_b32 %13, a125\n\tv_accvgpr_read_b32 %14, a126\n\tv_accvgpr_read_b32 %15, a127" : "=v"(t0), "=v"(t1), "=v"(t2), "=v"(t3), "=v"(t4), "=v"(t5), "=v"(t6), "=v"(t7), "=v"(t8), "=v"(t9), "=v"(t10), "=v"(t11), "=v"(t12), "=v"(t13), "=v"(t14), "=v"(t15));
-    v[0] = t0;
-    v[1] = t1;
-    v[2] = t2;
-    v[3] = t3;
-    v[4] = t4;
-    v[5] = t5;
-    v[6] = t6;
-    v[7] = t7;
-    v[8] = t8;
-    v[9] = t9;
-    v[10] = t10;
-    v[11] = t11;
-    v[12] = t12;
-    v[13] = t13;
-    v[14] = t14;
-    v[15] = t15;
-    return v;
-}
+template <int IDX> __device__ __forceinline__ void zero_acc();
+// Register names cannot be computed inside assembly text, so each accumulator lists its 16 registers once.
+#define LCD_ACC_CLOBBERS(r0, r1, r2, r3, r4, r5, r6, r7, r8, r9, r10, r11, r12, r13, r14, r15)                                   \
+    "a" #r0, "a" #r1, "a" #r2, "a" #r3, "a" #r4, "a" #r5, "a" #r6, "a" #r7, "a" #r8, "a" #r9, "a" #r10, "a" #r11, "a" #r12,      \
+        "a" #r13, "a" #r14, "a" #r15
+#define LCD_ACC_READ(n, r) "v_accvgpr_read_b32 %" #n ", a" #r
+#define LCD_ACC_ZERO(r) "v_accvgpr_write_b32 a" #r ", 0"
+#define LCD_ACCUMULATOR(IDX, r0, r1, r2, r3, r4, r5, r6, r7, r8, r9, r10, r11, r12, r13, r14, r15)                                \
+    template <> __device__ __forceinline__ void mfma_acc<IDX>(uint4v a, uint4v b)                                                 \
+    {                                                                                                                              \
+        asm volatile("s_nop 1\n\tv_mfma_f32_32x32x16_f16 a[" #r0 ":" #r15 "], %0, %1, a[" #r0 ":" #r15 "]"                     \
+                     :                                                                                                             \
+                     : "v"(a), "v"(b)                                                                                              \
+                     : LCD_ACC_CLOBBERS(r0, r1, r2, r3, r4, r5, r6, r7, r8, r9, r10, r11, r12, r13, r14, r15));                    \
+    }                                                                                                                              \
+    template <> __device__ __forceinline__ float16v read_acc<IDX>()                                                                \
+    {                                                                                                                              \
+        float t[16];                                                                                                               \
+        asm volatile(LCD_ACC_READ(0, r0) "\n\t" LCD_ACC_READ(1, r1) "\n\t" LCD_ACC_READ(2, r2) "\n\t" LCD_ACC_READ(3, r3) "\n\t"   \
+                     LCD_ACC_READ(4, r4) "\n\t" LCD_ACC_READ(5, r5) "\n\t" LCD_ACC_READ(6, r6) "\n\t" LCD_ACC_READ(7, r7) "\n\t"   \
+                     LCD_ACC_READ(8, r8) "\n\t" LCD_ACC_READ(9, r9) "\n\t" LCD_ACC_READ(10, r10) "\n\t" LCD_ACC_READ(11, r11)      \
+                     "\n\t" LCD_ACC_READ(12, r12) "\n\t" LCD_ACC_READ(13, r13) "\n\t" LCD_ACC_READ(14, r14) "\n\t"                 \
+                     LCD_ACC_READ(15, r15)                                                                                         \
+                     : "=v"(t[0]), "=v"(t[1]), "=v"(t[2]), "=v"(t[3]), "=v"(t[4]), "=v"(t[5]), "=v"(t[6]), "=v"(t[7]),             \
+                       "=v"(t[8]), "=v"(t[9]), "=v"(t[10]), "=v"(t[11]), "=v"(t[12]), "=v"(t[13]), "=v"(t[14]), "=v"(t[15]));      \
+        float16v v;                                                                                                                \
+        for (int i = 0; i < 16; ++i) v[i] = t[i];                                                                                  \
+        return v;                                                                                                                  \
+    }                                                                                                                              \
+    template <> __device__ __forceinline__ void zero_acc<IDX>()                                                                    \
+    {                                                                                                                              \
+        asm volatile(LCD_ACC_ZERO(r0) "\n\t" LCD_ACC_ZERO(r1) "\n\t" LCD_ACC_ZERO(r2) "\n\t" LCD_ACC_ZERO(r3) "\n\t"               \
+                     LCD_ACC_ZERO(r4) "\n\t" LCD_ACC_ZERO(r5) "\n\t" LCD_ACC_ZERO(r6) "\n\t" LCD_ACC_ZERO(r7) "\n\t"               \
+                     LCD_ACC_ZERO(r8) "\n\t" LCD_ACC_ZERO(r9) "\n\t" LCD_ACC_ZERO(r10) "\n\t" LCD_ACC_ZERO(r11) "\n\t"             \
+                     LCD_ACC_ZERO(r12) "\n\t" LCD_ACC_ZERO(r13) "\n\t" LCD_ACC_ZERO(r14) "\n\t" LCD_ACC_ZERO(r15)                  \
+                     :                                                                                                             \
+                     :                                                                                                             \
+                     : LCD_ACC_CLOBBERS(r0, r1, r2, r3, r4, r5, r6, r7, r8, r9, r10, r11, r12, r13, r14, r15));                    \
+    }
+LCD_ACCUMULATOR(0, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15)
+LCD_ACCUMULATOR(1, 16, 17, 18, 19, 20, 21, 22, 23, 24, 25, 26, 27, 28, 29, 30, 31)
+LCD_ACCUMULATOR(2, 32, 33, 34, 35, 36, 37, 38, 39, 40, 41, 42, 43, 44, 45, 46, 47)
+LCD_ACCUMULATOR(3, 48, 49, 50, 51, 52, 53, 54, 55, 56, 57, 58, 59, 60, 61, 62, 63)
+LCD_ACCUMULATOR(4, 64, 65, 66, 67, 68, 69, 70, 71, 72, 73, 74, 75, 76, 77, 78, 79)
+LCD_ACCUMULATOR(5, 80, 81, 82, 83, 84, 85, 86, 87, 88, 89, 90, 91, 92, 93, 94, 95)
+LCD_ACCUMULATOR(6, 96, 97, 98, 99, 100, 101, 102, 103, 104, 105, 106, 107, 108, 109, 110, 111)
+LCD_ACCUMULATOR(7, 112, 113, 114, 115, 116, 117, 118, 119, 120, 121, 122, 123, 124, 125, 126, 127)
+#undef LCD_ACCUMULATOR
+#undef LCD_ACC_ZERO
+#undef LCD_ACC_READ
+#undef LCD_ACC_CLOBBERS
 __device__ __forceinline__ void zero_accs()
 {
-    asm volatile("v_accvgpr_write_b32 a0, 0\n\tv_accvgpr_write_b32 a1, 0\n\tv_accvgpr_write_b32 a2, 0\n\tv_accvgpr_write_b32 a3, 0\n\tv_accvgpr_write_b32 a4, 0\n\tv_accvgpr_write_b32 a5, 0\n\tv_accvgpr_write_b32 a6, 0\n\tv_accvgpr_write_b32 a7, 0\n\tv_accvgpr_write_b32 a8, 0\n\tv_accvgpr_write_b32 a9, 0\n\tv_accvgpr_write_b32 a10, 0\n\tv_accvgpr_write_b32 a11, 0\n\tv_accvgpr_write_b32 a12, 0\n\tv_accvgpr_write_b32 a13, 0\n\tv_accvgpr_write_b32 a14, 0\n\tv_accvgpr_write_b32 a15, 0" : : : "a0", "a1", "a2", "a3", "a4", "a5", "a6", "a7", "a8", "a9", "a10", "a11", "a12", "a13", "a14", "a15");
-    asm volatile("v_accvgpr_write_b32 a16, 0\n\tv_accvgpr_write_b32 a17, 0\n\tv_accvgpr_write_b32 a18, 0\n\tv_accvgpr_write_b32 a19, 0\n\tv_accvgpr_write_b32 a20, 0\n\tv_accvgpr_write_b32 a21, 0\n\tv_accvgpr_write_b32 a22, 0\n\tv_accvgpr_write_b32 a23, 0\n\tv_accvgpr_write_b32 a24, 0\n\tv_accvgpr_write_b32 a25, 0\n\tv_accvgpr_write_b32 a26, 0\n\tv_accvgpr_write_b32 a27, 0\n\tv_accvgpr_write_b32 a28, 0\n\tv_accvgpr_write_b32 a29, 0\n\tv_accvgpr_write_b32 a30, 0\n\tv_accvgpr_write_b32 a31, 0" : : : "a16", "a17", "a18", "a19", "a20", "a21", "a22", "a23", "a24", "a25", "a26", "a27", "a28", "a29", "a30", "a31");
-    asm volatile("v_accvgpr_write_b32 a32, 0\n\tv_accvgpr_write_b32 a33, 0\n\tv_accvgpr_write_b32 a34, 0\n\tv_accvgpr_write_b32 a35, 0\n\tv_accvgpr_write_b32 a36, 0\n\tv_accvgpr_write_b32 a37, 0\n\tv_accvgpr_write_b32 a38, 0\n\tv_accvgpr_write_b32 a39, 0\n\tv_accvgpr_write_b32 a40, 0\n\tv_accvgpr_write_b32 a41, 0\n\tv_accvgpr_write_b32 a42, 0\n\tv_accvgpr_write_b32 a43, 0\n\tv_accvgpr_write_b32 a44, 0\n\tv_accvgpr_write_b32 a45, 0\n\tv_accvgpr_write_b32 a46, 0\n\tv_accvgpr_write_b32 a47, 0" : : : "a32", "a33", "a34", "a35", "a36", "a37", "a38", "a39", "a40", "a41", "a42", "a43", "a44", "a45", "a46", "a47");
-    asm volatile("v_accvgpr_write_b32 a48, 0\n\tv_accvgpr_write_b32 a49, 0\n\tv_accvgpr_write_b32 a50, 0\n\tv_accvgpr_write_b32 a51, 0\n\tv_accvgpr_write_b32 a52, 0\n\tv_accvgpr_write_b32 a53, 0\n\tv_accvgpr_write_b32 a54, 0\n\tv_accvgpr_write_b32 a55, 0\n\tv_accvgpr_write_b32 a56, 0\n\tv_accvgpr_write_b32 a57, 0\n\tv_accvgpr_write_b32 a58, 0\n\tv_accvgpr_write_b32 a59, 0\n\tv_accvgpr_write_b32 a60, 0\n\tv_accvgpr_write_b32 a61, 0\n\tv_accvgpr_write_b32 a62, 0\n\tv_accvgpr_write_b32 a63, 0" : : : "a48", "a49", "a50", "a51", "a52", "a53", "a54", "a55", "a56", "a57", "a58", "a59", "a60", "a61", "a62", "a63");
-    asm volatile("v_accvgpr_write_b32 a64, 0\n\tv_accvgpr_write_b32 a65, 0\n\tv_accvgpr_write_b32 a66, 0\n\tv_accvgpr_write_b32 a67, 0\n\tv_accvgpr_write_b32 a68, 0\n\tv_accvgpr_write_b32 a69, 0\n\tv_accvgpr_write_b32 a70, 0\n\tv_accvgpr_write_b32 a71, 0\n\tv_accvgpr_write_b32 a72, 0\n\tv_accvgpr_write_b32 a73, 0\n\tv_accvgpr_write_b32 a74, 0\n\tv_accvgpr_write_b32 a75, 0\n\tv_accvgpr_write_b32 a76, 0\n\tv_accvgpr_write_b32 a77, 0\n\tv_accvgpr_write_b32 a78, 0\n\tv_accvgpr_write_b32 a79, 0" : : : "a64", "a65", "a66", "a67", "a68", "a69", "a70", "a71", "a72", "a73", "a74", "a75", "a76", "a77", "a78", "a79");
-    asm volatile("v_accvgpr_write_b32 a80, 0\n\tv_accvgpr_write_b32 a81, 0\n\tv_accvgpr_write_b32 a82, 0\n\tv_accvgpr_write_b32 a83, 0\n\tv_accvgpr_write_b32 a84, 0\n\tv_accvgpr_write_b32 a85, 0\n\tv_accvgpr_write_b32 a86, 0\n\tv_accvgpr_write_b32 a87, 0\n\tv_accvgpr_write_b32 a88, 0\n\tv_accvgpr_write_b32 a89, 0\n\tv_accvgpr_write_b32 a90, 0\n\tv_accvgpr_write_b32 a91, 0\n\tv_accvgpr_write_b32 a92, 0\n\tv_accvgpr_write_b32 a93, 0\n\tv_accvgpr_write_b32 a94, 0\n\tv_accvgpr_write_b32 a95, 0" : : : "a80", "a81", "a82", "a83", "a84", "a85", "a86", "a87", "a88", "a89", "a90", "a91", "a92", "a93", "a94", "a95");
-    asm volatile("v_accvgpr_write_b32 a96, 0\n\tv_accvgpr_write_b32 a97, 0\n\tv_accvgpr_write_b32 a98, 0\n\tv_accvgpr_write_b32 a99, 0\n\tv_accvgpr_write_b32 a100, 0\n\tv_accvgpr_write_b32 a101, 0\n\tv_accvgpr_write_b32 a102, 0\n\tv_accvgpr_write_b32 a103, 0\n\tv_accvgpr_write_b32 a104, 0\n\tv_accvgpr_write_b32 a105, 0\n\tv_accvgpr_write_b32 a106, 0\n\tv_accvgpr_write_b32 a107, 0\n\tv_accvgpr_write_b32 a108, 0\n\tv_accvgpr_write_b32 a109, 0\n\tv_accvgpr_write_b32 a110, 0\n\tv_accvgpr_write_b32 a111, 0" : : : "a96", "a97", "a98", "a99", "a100", "a101", "a102", "a103", "a104", "a105", "a106", "a107", "a108", "a109", "a110", "a111");
-    asm volatile("v_accvgpr_write_b32 a112, 0\n\tv_accvgpr_write_b32 a113, 0\n\tv_accvgpr_write_b32 a114, 0\n\tv_accvgpr_write_b32 a115, 0\n\tv_accvgpr_write_b32 a116, 0\n\tv_accvgpr_write_b32 a117, 0\n\tv_accvgpr_write_b32 a118, 0\n\tv_accvgpr_write_b32 a119, 0\n\tv_accvgpr_write_b32 a120, 0\n\tv_accvgpr_write_b32 a121, 0\n\tv_accvgpr_write_b32 a122, 0\n\tv_accvgpr_write_b32 a123, 0\n\tv_accvgpr_write_b32 a124, 0\n\tv_accvgpr_write_b32 a125, 0\n\tv_accvgpr_write_b32 a126, 0\n\tv_accvgpr_write_b32 a127, 0" : : : "a112", "a113", "a114", "a115", "a116", "a117", "a118", "a119", "a120", "a121", "a122", "a123", "a124", "a125", "a126", "a127");
+    zero_acc<0>(); zero_acc<1>(); zero_acc<2>(); zero_acc<3>(); zero_acc<4>(); zero_acc<5>(); zero_acc<6>(); zero_acc<7>();
 }
 
 // One lane's packed words of a chunk half: per pair, the lane's row and the 64 columns
