@@ -104,3 +104,12 @@ def test_random_prefill_groups(seed):
         assert np.all(np.isfinite(got.astype(np.float32)))
         err = oracle.parity_errors(got, Y)
         assert err["max_rel_floored"] <= (1e-3 if quantised else TOL), (seed, N, M, bits, err)
+
+
+@pytest.mark.parametrize("M,N,K,bits", [(5000, 48, 512, 3), (8192 + 33, 16, 256, 2), (4097, 272, 768, 4)])
+def test_prefill_many_tokens(M, N, K, bits):
+    # token counts far beyond one workgroup's 128-token tile, ragged at the end, on matrices small
+    # enough for the oracle: every token block of the grid is compared
+    layer = synth.make_layer(4, M % 97, N, K, bits, M, seed_offset=M)
+    err = check_layer(layer, bits, "gemm")
+    print(M, N, K, bits, err["max_rel_floored"])
