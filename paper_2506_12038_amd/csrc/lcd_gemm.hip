@@ -353,6 +353,10 @@ __device__ __forceinline__ void gemm_tile(const uint8_t *__restrict__ packed_, c
     // one 32-row pair and hands the other pair's four accumulators to its partner through LDS (the
     // stages are free now): per row group two 16 KiB areas, area h read by the wave with khalf == h,
     // [accumulator 4][register quad 4][lane] float4.
+    // The accumulator reads below are assembly text too: the distance the hardware requires between a
+    // matrix instruction's register write and a vector instruction's read of it (19 wait states for
+    // the 16-pass instruction) is kept here by hand, once per workgroup.
+    asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");
     float4v *area_in = reinterpret_cast<float4v *>(lds) + (size_t)(rgrp * 2 + khalf) * (4 * 4 * 64);
     float4v *area_out = reinterpret_cast<float4v *>(lds) + (size_t)(rgrp * 2 + (khalf ^ 1)) * (4 * 4 * 64);
     auto put_acc = [&](const float16v &v, int slot) {
