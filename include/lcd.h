@@ -177,6 +177,10 @@ lcd_status lcd_lut_gemv_noalloc(const void *packed, const void *lut, const uint1
  * sums), one rounding to fp16 at the store.  Precondition on the data: every s[k]*s_q lies in
  * (2^-64, 2^64) and X is finite (the quotient is computed without range scaling).
  * All other arguments as lcd_lut_gemv (1 <= M <= 16).
+ * Routing: as lcd_lut_gemv, except that with 2 bits the codes travel as int8 numbers through the
+ * sparse matrix core's int8 instruction (half the matrix instructions per weight, same bits in the
+ * result: the bucket sums are integers either way), which then takes up to four tokens (one sparse
+ * pass per token) before the dequantising route takes over at M >= 5.
  */
 lcd_status lcd_lut_gemv_q8(const void *packed, const void *lut, const uint16_t *x, const float *s, float s_q,
                            uint16_t *y, int M, int N, int K, int bits,

@@ -105,6 +105,7 @@ __device__ __forceinline__ int layer_of_workgroup(uint32_t b, uint32_t t0, uint3
 struct BucketBatch {
     BucketProblem p[kMaxGroup];
     int count;
+    int tokens;   // M (the bucket kernel's token slots beyond it read zeros and store nothing)
 };
 
 // Walks the (visit, segment, tile) sequence of one workgroup.  Everything is wave-uniform.
@@ -173,7 +174,7 @@ __device__ __forceinline__ void issue_step_loads(StepRegs<BITS> &r, const Cursor
                                                  __amdgpu_buffer_rsrc_t rs_lut, int kc, int wave, int lane)
 {
     constexpr uint32_t TB = BITS == 2 ? 1024 : 1536;
-    constexpr int NB = BITS == 2 ? 4 : 8, NC = MT == 2 ? 8 : NB;
+    constexpr int NB = BITS == 2 ? 4 : 8, NC = NB * MT;
     // a finished cursor or a padding step issues loads that are out of range: zeros, no traffic
     const int tile = c.v0 + c.i;
     const bool tv = !c.done && tile < c.v1;
@@ -195,15 +196,27 @@ __device__ __forceinline__ void issue_step_loads(StepRegs<BITS> &r, const Cursor
 // activations have with 3 bits -- a second sparse pass over the same indices whose bucket sums land in
 // columns 4..7 -- so the kernel has the 3-bit kernel's shape without its sign flips; columns 0..3 and
 // 4..7 are multiplied by the same four centroids and reduced separately, one output per token.
-template <int BITS, int MT = 1>
+//
+// I8 (2 bits, activations quantised to the INT8 codes of Sec. 4.1): the codes travel as int8 numbers
+// through v_smfmac_i32_16x16x128_i8, which takes all 16 two-bit fields of a packed word at once (stored
+// byte e of a lane goes with field e, pairs of bytes share a group of four rows of B, and every fourth
+// byte of B belongs to the same slot whichever lane holds it -- checked against a model on random data):
+// half the matrix instructions and half the operand registers per weight.  The bucket sums are
+// integers either way (exact in the fp32 accumulators of the fp16 route as well), so both routes give
+// the same bits.
+template <int BITS, int MT = 1, bool I8 = false>
 __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t t0, const uint32_t t1, const uint32_t t2, const uint32_t t3,
                                                                    const uint32_t t4, const uint32_t t5, const uint32_t t6, const uint32_t t7,
                                                                    const BucketBatch batch)
 {
-    static_assert(MT == 1 || (MT == 2 && BITS == 2), "two tokens: 2-bit indices only");
+    static_assert(MT == 1 || (MT == 2 && BITS == 2) || (MT == 4 && I8), "two tokens: 2-bit indices only; four: int8 operands only");
+    static_assert(!I8 || BITS == 2, "int8 operands: 2-bit indices only");
+    typedef int int4v __attribute__((ext_vector_type(4)));
+    typedef int int8v __attribute__((ext_vector_type(8)));
+    constexpr int NA = I8 ? 4 : 8;               // operand registers (uint4) per chunk and token
     constexpr int NB = BITS == 2 ? 4 : 8;        // buckets (centroids) per row
-    constexpr int NC = MT == 2 ? 8 : NB;         // accumulator columns one row tile uses
-    constexpr int TG = 16 / NC;                  // row tiles that share one reduction (4 or 2)
+    constexpr int NC = NB * MT;                  // accumulator columns one row tile uses (MT > 1: 2 bits only)
+    constexpr int TG = 16 / NC;                  // row tiles that share one reduction (4, 2 or 1)
     constexpr uint32_t TB = BITS == 2 ? 1024 : 1536;
     constexpr int NT = kBW * 64;
     constexpr int kSegHalfs = kBSeg * kTileCols;        // activations of one segment, one token
@@ -228,7 +241,8 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
     const bool quantised = pb.act_scale != 0.0f;               // wave-uniform
     const float out_scale = quantised ? pb.act_scale : 1.0f;
     const __amdgpu_buffer_rsrc_t rs_packed = make_rsrc(pb.packed, (uint32_t)pb.nt * (uint32_t)kc * TB);
-    const __amdgpu_buffer_rsrc_t rs_x = make_rsrc(pb.x, (uint32_t)MT * (uint32_t)kc * kTileCols * 2);
+    const int tokens = MT == 1 ? 1 : batch.tokens;   // MT > tokens: the slots beyond read zeros through the buffer range
+    const __amdgpu_buffer_rsrc_t rs_x = make_rsrc(pb.x, (uint32_t)tokens * (uint32_t)kc * kTileCols * 2);
     const __amdgpu_buffer_rsrc_t rs_s = make_rsrc(pb.s, (uint32_t)kc * kTileCols * 4);
     const __amdgpu_buffer_rsrc_t rs_lut = make_rsrc(pb.lutA, (uint32_t)pb.nt * 16 * NB * 4);
 
@@ -259,13 +273,47 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
     issue_step_loads<BITS, true, MT>(rs[0], pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
     if (cur.done) return;   // no row tiles (the host never launches such a workgroup); the loads above moved nothing
 
-    uint4v A[MT][kBCH][8];   // this wave's smoothed activations of the current segment, 8 operands per chunk and token
+    uint4v A[MT][kBCH][NA];   // this wave's smoothed activations of the current segment, NA operands per chunk and token
     bool chunk_in_k[kBCH] = {};   // wave-uniform: a short last segment leaves some of the wave's chunks empty
     half16 B1;        // constant routing matrix (index c -> column c), built after the prologue
+    int8v Bq[MT];     // I8: the same as int8 numbers; token t's sums go to columns 4t .. 4t+3
     float *my_part = part + wave * (kVisitTiles * 16);
 
     // bucket sums of one (tile, chunk): columns [0, NC) of a 16x16 accumulator
     auto tile_sums = [&](const StepRegs<BITS> &r) -> float4v {
+        if constexpr (I8) {
+            int4v ax = {0, 0, 0, 0}, ay = {0, 0, 0, 0}, az = {0, 0, 0, 0}, aw = {0, 0, 0, 0};
+#pragma unroll
+            for (int ch = 0; ch < kBCH; ++ch) {
+                if (!chunk_in_k[ch]) continue;
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                    const int idxreg = (int)r.lo[ch][d];
+                    if (MT == 1) {
+                        if (d & 1) ay = __builtin_amdgcn_smfmac_i32_16x16x128_i8(__builtin_bit_cast(int4v, A[0][ch][d]), Bq[0], ay, idxreg, 0, 0);
+                        else ax = __builtin_amdgcn_smfmac_i32_16x16x128_i8(__builtin_bit_cast(int4v, A[0][ch][d]), Bq[0], ax, idxreg, 0, 0);
+                    } else if (MT == 2) {
+                        ax = __builtin_amdgcn_smfmac_i32_16x16x128_i8(__builtin_bit_cast(int4v, A[0][ch][d]), Bq[0], ax, idxreg, 0, 0);
+                        ay = __builtin_amdgcn_smfmac_i32_16x16x128_i8(__builtin_bit_cast(int4v, A[MT - 1][ch][d]), Bq[MT - 1], ay, idxreg, 0, 0);
+                    } else {   // four tokens: all routed to columns 0..3, moved apart below
+                        ax = __builtin_amdgcn_smfmac_i32_16x16x128_i8(__builtin_bit_cast(int4v, A[0][ch][d]), Bq[0], ax, idxreg, 0, 0);
+                        ay = __builtin_amdgcn_smfmac_i32_16x16x128_i8(__builtin_bit_cast(int4v, A[MT / 4][ch][d]), Bq[0], ay, idxreg, 0, 0);
+                        az = __builtin_amdgcn_smfmac_i32_16x16x128_i8(__builtin_bit_cast(int4v, A[MT / 2][ch][d]), Bq[0], az, idxreg, 0, 0);
+                        aw = __builtin_amdgcn_smfmac_i32_16x16x128_i8(__builtin_bit_cast(int4v, A[MT - 1][ch][d]), Bq[0], aw, idxreg, 0, 0);
+                    }
+                }
+            }
+            float4v m;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {   // sums of at most 2^15 codes: exact
+                int v = ax[u] + ay[u];
+                if (MT == 4)   // tokens 1, 2, 3 to columns 4.., 8.., 12.. (row_shr:4 / 8 / 12; lanes shifted in read zero)
+                    v = ax[u] + __builtin_amdgcn_update_dpp(0, ay[u], 0x114, 0xF, 0xF, true) + __builtin_amdgcn_update_dpp(0, az[u], 0x118, 0xF, 0xF, true) +
+                        __builtin_amdgcn_update_dpp(0, aw[u], 0x11C, 0xF, 0xF, true);
+                m[u] = (float)v;
+            }
+            return m;
+        } else {
         float4v accx = {0.f, 0.f, 0.f, 0.f}, accy = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ch = 0; ch < kBCH; ++ch) {
@@ -309,6 +357,7 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
 #pragma unroll
         for (int u = 0; u < 4; ++u) m[u] = accx[u] + dpp_f32<0x114>(accy[u]);   // row_shr:4
         return m;
+        }
     };
 
     // TG tiles share one multiply-and-reduce: tile u of the group moves to columns [u*NC, (u+1)*NC)
@@ -345,6 +394,23 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
     StepRegs<BITS> &r0 = rs[0], &r1 = rs[1], &r2 = rs[2], &r3 = rs[3];
     const float4v zero = {0.f, 0.f, 0.f, 0.f};
     auto full_turn = [&]() __attribute__((always_inline)) {
+        if constexpr (TG == 1) {   // every row tile has its own multipliers and its own reduction
+            issue_step_loads<BITS, true, MT>(r3, pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
+            float4v t = tile_sums(r0);
+            uint4v cf = r0.cf;   // taken before the set is loaded again
+            issue_step_loads<BITS, true, MT>(r0, pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
+            reduce_group(t, cur.i, cf);
+            t = tile_sums(r1); cf = r1.cf;
+            issue_step_loads<BITS, true, MT>(r1, pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
+            reduce_group(t, cur.i + 1, cf);
+            t = tile_sums(r2); cf = r2.cf;
+            issue_step_loads<BITS, true, MT>(r2, pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
+            reduce_group(t, cur.i + 2, cf);
+            t = tile_sums(r3);
+            reduce_group(t, cur.i + 3, r3.cf);
+            cur.i += 4;
+            return;
+        }
         float4v t0, t1, t3;
         issue_step_loads<BITS, false, MT>(r3, pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
         t0 = tile_sums(r0);
@@ -375,6 +441,23 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
     };
     // the last 1..3 steps of a run (wave-uniform `left`): as many loads as steps
     auto short_turn = [&](int left) __attribute__((always_inline)) {
+        if constexpr (TG == 1) {
+            issue_step_loads<BITS, false, MT>(r3, pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
+            float4v t = tile_sums(r0);
+            reduce_group(t, cur.i, r0.cf);
+            if (left > 1) {
+                issue_step_loads<BITS, false, MT>(r0, pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
+                t = tile_sums(r1);
+                reduce_group(t, cur.i + 1, r1.cf);
+            }
+            if (left > 2) {
+                issue_step_loads<BITS, false, MT>(r1, pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
+                t = tile_sums(r2);
+                reduce_group(t, cur.i + 2, r2.cf);
+            }
+            cur.i += 4;
+            return;
+        }
         float4v t0, t1 = zero;
         issue_step_loads<BITS, false, MT>(r3, pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
         t0 = tile_sums(r0);
@@ -414,6 +497,10 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
             else { StepRegs<BITS> t, u; take(t, r0); take(u, r1); take(r0, r3); take(r1, t); take(r2, u); }
             r0.cf = load_multipliers<NC, NB>(rs_lut, cur.v0, cur.v1, lane);
             if (TG == 2) r2.cf = load_multipliers<NC, NB>(rs_lut, cur.v0 + 2, cur.v1, lane);
+            if (TG == 1) {
+                r1.cf = load_multipliers<NC, NB>(rs_lut, cur.v0 + 1, cur.v1, lane);
+                r2.cf = load_multipliers<NC, NB>(rs_lut, cur.v0 + 2, cur.v1, lane);
+            }
             behind = 0;
         }
         for (cur.i = 0; cur.i + 4 <= cur.steps;) full_turn();
@@ -421,13 +508,19 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
     };
 
     // the remaining two sets of the pipeline
-    issue_step_loads<BITS, false, MT>(rs[1], pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
-    issue_step_loads<BITS, TG == 2, MT>(rs[2], pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
+    issue_step_loads<BITS, TG == 1, MT>(rs[1], pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
+    issue_step_loads<BITS, TG <= 2, MT>(rs[2], pf, rs_packed, rs_lut, kc, wave, lane); cursor_advance(pf, nseg);
     while (!cur.done) {
         // (no workgroup synchronisation at the start of a visit: activations and multipliers are
         // per wave; the barrier that ends a visit's epilogue protects the reuse of `part`)
 #pragma unroll
         for (int b = 0; b < 16; ++b) B1[b] = ((b & 3) == j) ? (_Float16)1.0f : (_Float16)0.0f;
+        if constexpr (I8) {
+#pragma unroll
+            for (int t = 0; t < MT; ++t)
+#pragma unroll
+                for (int b = 0; b < 8; ++b) Bq[t][b] = (j >> 2) == t ? 1 << (8 * (j & 3)) : 0;   // byte (b & 3) == j - 4t
+        }
         for (cur.sg = 0; cur.sg < nseg; ++cur.sg) {
             {   // smooth this thread's 8 activations of the segment (loaded one segment ago)
                 const bool in_k = wave_chunk(cur.sg, wave, lane >> 5) < kc;
@@ -444,7 +537,15 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
                             o[e] = !in_k ? (_Float16)0.0f
                                          : quantise_one((uint16_t)(xv[t][e >> 1] >> (16 * (e & 1))), make_divisor(e < 4 ? s0[e] : s1[e - 4], pb.act_scale));
                     }
-                    *reinterpret_cast<half8 *>(&xs_lds[t * kSegHalfs + 8 * threadIdx.x]) = o;
+                    if constexpr (I8) {   // the codes as int8 numbers, one byte per column
+                        int c[8];
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) c[e] = (int)(float)o[e] & 0xff;
+                        const uint2v packed8 = {(uint32_t)(c[0] | c[1] << 8 | c[2] << 16 | c[3] << 24), (uint32_t)(c[4] | c[5] << 8 | c[6] << 16 | c[7] << 24)};
+                        *reinterpret_cast<uint2v *>(reinterpret_cast<uint8_t *>(xs_lds) + t * kSegHalfs + 8 * threadIdx.x) = packed8;
+                    } else {
+                        *reinterpret_cast<half8 *>(&xs_lds[t * kSegHalfs + 8 * threadIdx.x]) = o;
+                    }
                 }
                 // next segment's activations: of this visit, or segment 0 again for the next visit
                 const bool more = cur.sg + 1 < nseg;
@@ -456,8 +557,12 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
 #pragma unroll
                 for (int t = 0; t < MT; ++t)
 #pragma unroll
-                    for (int g = 0; g < 8; ++g)   // written by this wave only: no barrier
-                        A[t][ch][g] = *reinterpret_cast<const uint4v *>(&xs_lds[t * kSegHalfs + (wave * kBCH + ch) * kTileCols + 64 * q + 8 * g]);
+                    for (int g = 0; g < NA; ++g) {   // written by this wave only: no barrier
+                        if constexpr (I8)
+                            A[t][ch][g] = *reinterpret_cast<const uint4v *>(reinterpret_cast<const uint8_t *>(xs_lds) + t * kSegHalfs + (wave * kBCH + ch) * kTileCols + 64 * q + 16 * g);
+                        else
+                            A[t][ch][g] = *reinterpret_cast<const uint4v *>(&xs_lds[t * kSegHalfs + (wave * kBCH + ch) * kTileCols + 64 * q + 8 * g]);
+                    }
             }
             run_turns();
         }
@@ -466,6 +571,7 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
         for (int e = threadIdx.x; e < (cur.v1 - cur.v0) * 16; e += NT) {
 #pragma unroll
             for (int t = 0; t < MT; ++t) {   // token t's row of y starts N outputs after token t - 1's
+                if (t >= tokens) break;
                 float sum = 0.f;
 #pragma unroll
                 for (int w = 0; w < kBW; ++w) sum += part[t * kPartFloats + w * (kVisitTiles * 16) + e];
@@ -805,7 +911,12 @@ int launch_decode_group(const GroupItem *items, int count, int M, int bits, void
     int tiles = 0;
     // 4 bits: the register dequantiser serves one token too; 2 bits: the sparse-matrix-core kernel also takes
     // two tokens (one sparse pass per token costs less than dequantising once)
-    const bool tokens_path = bits == 4 || M > 2 || (M == 2 && bits == 3);
+    // (with the INT8 codes of Sec. 4.1 as int8 operands the sparse-matrix-core kernel has room for four tokens)
+    bool all_quantised = true;
+    for (int i = 0; i < count; ++i) all_quantised = all_quantised && items[i].act_scale != 0.0f;
+    const int sparse_tokens = bits != 2 ? 1 : all_quantised ? 4 : 2;   // most tokens the bucket kernel takes
+    const bool tokens_path = bits == 4 || M > sparse_tokens;
+    const int MT = M <= 2 ? M : 4;                                      // token slots of the bucket kernel variant
     // several tokens: quantised activations are made once, ahead of the product, and so are smoothed
     // ones when the layers are wide (measured: the launch costs about 3.6 us; re-smoothing in every
     // workgroup costs 1.9 us for K = 4096 / 11008 and 4.3 us for K = 8192 / 28672)
@@ -851,6 +962,8 @@ int launch_decode_group(const GroupItem *items, int count, int M, int bits, void
     int grid = num_cus();
     if (grid > tiles) grid = tiles;
     if (grid < count) grid = count;
+    // 2 bits on the sparse matrix core with quantised activations: the codes go in as int8 numbers
+    const bool int8_codes = !tokens_path && bits == 2 && all_quantised;
     const bool light_steps = !tokens_path && bits == 2 && M == 1;   // one sparse pass per tile: a step is short next to the fixed costs
     // the several-token kernel, measured per workgroup (unit: the time of two chunks of one row tile, about 1 us):
     // smoothing inside the kernel, a segment switch re-stages 16 tokens x 512 columns per wave (2.3); with the
@@ -920,16 +1033,17 @@ int launch_decode_group(const GroupItem *items, int count, int M, int bits, void
         }
     };
     // the split depends on the shapes only: the last one is kept (serving loops repeat a few groups)
-    struct SplitMemo { int count, M, bits, grid, ahead, nt[kMaxGroup], kc[kMaxGroup], nwg[kMaxGroup]; };
+    struct SplitMemo { int count, M, bits, grid, ahead, route, nt[kMaxGroup], kc[kMaxGroup], nwg[kMaxGroup]; };
     static thread_local SplitMemo memo = {};
-    bool known = memo.count == count && memo.M == M && memo.bits == bits && memo.grid == grid && memo.ahead == (int)staged_ahead;
+    const int route = tokens_path ? 1 : int8_codes ? 2 : 0;   // the cost constants depend on it
+    bool known = memo.count == count && memo.M == M && memo.bits == bits && memo.grid == grid && memo.ahead == (int)staged_ahead && memo.route == route;
     for (int i = 0; known && i < count; ++i) known = memo.nt[i] == batch.p[i].nt && memo.kc[i] == batch.p[i].kc;
     int nwg[kMaxGroup];
     if (known) {
         for (int i = 0; i < count; ++i) nwg[i] = memo.nwg[i];
     } else {
         split(kBCH, nwg);
-        memo.count = count; memo.M = M; memo.bits = bits; memo.grid = grid; memo.ahead = (int)staged_ahead;
+        memo.count = count; memo.M = M; memo.bits = bits; memo.grid = grid; memo.ahead = (int)staged_ahead; memo.route = route;
         for (int i = 0; i < count; ++i) { memo.nt[i] = batch.p[i].nt; memo.kc[i] = batch.p[i].kc; memo.nwg[i] = nwg[i]; }
     }
     // Workgroups are dispatched in the order of their ids, the last of a full grid almost 1 us after the
@@ -956,6 +1070,7 @@ int launch_decode_group(const GroupItem *items, int count, int M, int bits, void
     }
     for (int i = count; i <= kMaxGroup; ++i) wg_begin[i] = acc;
     batch.count = count;
+    batch.tokens = M;
     static_assert(kMaxGroup == 16, "eight leading kernel arguments hold wg_begin[1..16]");
     if (acc >= 0x7fff) return (int)hipErrorInvalidConfiguration;   // 16-bit table fields (acc <= max(CUs, count))
     WgTable table;
@@ -965,15 +1080,18 @@ int launch_decode_group(const GroupItem *items, int count, int M, int bits, void
     size_t lds;
     const void *fn;
     if (!tokens_path) {
-        lds = (size_t)M * ((size_t)kBSeg * kTileCols * 2 + (size_t)kBW * kVisitTiles * 16 * 4);
-        fn = bits == 3 ? (const void *)gemv_bucket_kernel<3> : M == 2 ? (const void *)gemv_bucket_kernel<2, 2> : (const void *)gemv_bucket_kernel<2>;
+        lds = (size_t)MT * ((size_t)kBSeg * kTileCols * 2 + (size_t)kBW * kVisitTiles * 16 * 4);
+        fn = bits == 3 ? (const void *)gemv_bucket_kernel<3>
+             : int8_codes ? (MT == 4 ? (const void *)gemv_bucket_kernel<2, 4, true>
+                             : MT == 2 ? (const void *)gemv_bucket_kernel<2, 2, true> : (const void *)gemv_bucket_kernel<2, 1, true>)
+             : MT == 2 ? (const void *)gemv_bucket_kernel<2, 2> : (const void *)gemv_bucket_kernel<2>;
     } else {
         lds = (size_t)kBW * 16 * kStageStride * 2 + (size_t)2 * 2 * kBW * 256 * 4 + (size_t)kVisitTiles * 256 * 4;
         fn = bits == 2 ? (const void *)gemv_tokens_kernel<2, kBCH> : bits == 3 ? (const void *)gemv_tokens_kernel<3, kBCH>
                                                                               : (const void *)gemv_tokens_kernel<4, kBCH>;
     }
-    static PerDeviceFlags<9> lds_raised;
-    const int variant = tokens_path ? 1 : M == 2 ? 2 : 0;
+    static PerDeviceFlags<18> lds_raised;
+    const int variant = tokens_path ? 1 : int8_codes ? (MT == 4 ? 5 : MT == 2 ? 4 : 3) : MT == 2 ? 2 : 0;
     if (hipError_t e = raise_lds_limit_once(lds_raised, variant * 3 + (bits - 2), fn, lds)) return (int)e;
     void *args[] = {&table.t[0], &table.t[1], &table.t[2], &table.t[3], &table.t[4], &table.t[5], &table.t[6], &table.t[7],
                     &batch, const_cast<int *>(&M)};   // the bucket kernel takes no M

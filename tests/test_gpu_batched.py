@@ -88,6 +88,31 @@ def test_config2_shapes_two_tokens_full_size_every_output():
     _check_every_output(2, 2)
 
 
+@pytest.mark.parametrize("M", [1, 3, 4])
+def test_config2_shapes_int8_codes_full_size_every_output(M):
+    # 2 bits with the INT8 codes of Sec. 4.1: up to four tokens run on the sparse-matrix-core kernel with
+    # int8 operands.  One grouped call over the whole set, every output against the quantised oracle.
+    import torch
+    from paper_2506_12038_amd.binding import GemvGroup
+    config = synth.get_config(2)
+    problems, keep, steps = [], [], []
+    for mid, spec, layer in config_layers(2, M, distinct_shapes_only=False):
+        packed = lcd.lcd_pack_indices(to_dev(layer["idx"]), config.bits)
+        lut = lcd.lcd_build_lut(to_dev(layer["codebook"]), config.bits)
+        y = torch.full((M, spec.N), float("nan"), dtype=torch.float16, device="cuda")
+        problems.append((packed, lut, to_dev(layer["x"]), to_dev(layer["s"]), y, spec.N))
+        steps.append(float(np.float32(np.quantile(np.abs(layer["x"].astype(np.float64) / layer["s"]), 0.99) / 127.0)))
+        keep.append((spec, layer))
+    GemvGroup(problems, config.bits, s_q=steps)()
+    torch.cuda.synchronize()
+    for (spec, layer), p, s_q in zip(keep, problems, steps):
+        got = p[4].cpu().numpy()
+        assert np.all(np.isfinite(got.astype(np.float32))), spec
+        Y = oracle.quantised_lut_matmul(layer["codebook"], layer["idx"], layer["x"], layer["s"], s_q, config.bits)
+        err = oracle.parity_errors(got, Y)
+        assert err["max_rel_floored"] <= 1e-3, (spec, M, err)
+
+
 @pytest.mark.parametrize("M", [1, 8])
 def test_config4_70b_mlp_full_size_every_output(M):
     _check_every_output(4, M)

@@ -118,7 +118,7 @@ def test_grouped_config_full_size_every_output(cfg):
         assert_parity(p[4].cpu().numpy(), Y, what=(cfg, spec))
 
 
-@pytest.mark.parametrize("bits,M,quantised", [(3, 1, False), (2, 16, False), (2, 16, True), (4, 3, True), (3, 1, True), (2, 2, False), (2, 2, True)])
+@pytest.mark.parametrize("bits,M,quantised", [(3, 1, False), (2, 16, False), (2, 16, True), (4, 3, True), (3, 1, True), (2, 2, False), (2, 2, True), (2, 3, True), (2, 1, True)])
 def test_grouped_launch_replayed_from_a_hip_graph(bits, M, quantised):
     # the launch configuration bench.py times: the grouped call captured once, replayed several times
     # with eager work and synchronisations in between; every replay must reproduce the eager result
@@ -164,7 +164,7 @@ def test_grouped_launch_replayed_from_a_hip_graph(bits, M, quantised):
 
 
 @pytest.mark.parametrize("bits", [2, 3, 4])
-@pytest.mark.parametrize("M", [1, 2, 5, 16])
+@pytest.mark.parametrize("M", [1, 2, 3, 4, 5, 16])
 @pytest.mark.parametrize("shape", [(64, 1024), (48, 11008)])
 def test_gemv_q8_matches_the_quantised_oracle(bits, M, shape):
     # input transformation (Eq. 10-11, b = 8) in front of the product; s_q such that ~1 % of the codes clip
@@ -180,7 +180,7 @@ def test_gemv_q8_matches_the_quantised_oracle(bits, M, shape):
     assert err["max_rel_floored"] <= 1e-3, err      # only fp32 accumulation and the fp16 store differ
 
 
-@pytest.mark.parametrize("M", [1, 2, 4, 16])
+@pytest.mark.parametrize("M", [1, 2, 3, 4, 16])
 def test_gemv_q8_codes_are_bit_exact(M):
     # identity layer (row n reads column n through a one-hot codebook): y[m][n] = s_q * q[m][n], so the
     # quantiser's integer decisions are visible one by one; s_q = 2^-3 keeps the scaling exact.
@@ -203,7 +203,7 @@ def test_gemv_q8_codes_are_bit_exact(M):
     assert np.array_equal(y.astype(np.float64) / s_q, q.astype(np.float64))
 
 
-@pytest.mark.parametrize("bits,M", [(3, 1), (2, 1), (2, 8), (4, 1), (4, 5)])
+@pytest.mark.parametrize("bits,M", [(3, 1), (2, 1), (2, 2), (2, 3), (2, 4), (2, 8), (4, 1), (4, 5)])
 def test_grouped_q8_matches_oracle_and_single_calls(bits, M):
     # one launch over layers with different shapes and different quantisation steps
     import torch

@@ -40,7 +40,7 @@ def test_random_groups(seed):
     rng = np.random.default_rng(2000 + seed)
     count = int(rng.integers(1, 9))
     bits = int(rng.integers(2, 5))
-    M = int(rng.choice([1, 1, 2, 5, 16]))
+    M = int(rng.choice([1, 1, 2, 3, 4, 5, 16]))
     quantised = bool(rng.integers(0, 2))
     problems, refs, steps = [], [], []
     for i in range(count):
