@@ -105,7 +105,6 @@ __device__ __forceinline__ int layer_of_workgroup(uint32_t b, uint32_t t0, uint3
 struct BucketBatch {
     BucketProblem p[kMaxGroup];
     int count;
-    int tokens;   // M (the bucket kernel's token slots beyond it read zeros and store nothing)
 };
 
 // Walks the (visit, segment, tile) sequence of one workgroup.  Everything is wave-uniform.
@@ -204,7 +203,8 @@ __device__ __forceinline__ void issue_step_loads(StepRegs<BITS> &r, const Cursor
 // half the matrix instructions and half the operand registers per weight.  The bucket sums are
 // integers either way (exact in the fp32 accumulators of the fp16 route as well), so both routes give
 // the same bits.
-template <int BITS, int MT = 1, bool I8 = false>
+// NTOK: tokens the launch has (MT = 4 token slots also serve three tokens, which then leave the fourth pass out).
+template <int BITS, int MT = 1, bool I8 = false, int NTOK = MT>
 __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t t0, const uint32_t t1, const uint32_t t2, const uint32_t t3,
                                                                    const uint32_t t4, const uint32_t t5, const uint32_t t6, const uint32_t t7,
                                                                    const BucketBatch batch)
@@ -241,8 +241,7 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
     const bool quantised = pb.act_scale != 0.0f;               // wave-uniform
     const float out_scale = quantised ? pb.act_scale : 1.0f;
     const __amdgpu_buffer_rsrc_t rs_packed = make_rsrc(pb.packed, (uint32_t)pb.nt * (uint32_t)kc * TB);
-    const int tokens = MT == 1 ? 1 : batch.tokens;   // MT > tokens: the slots beyond read zeros through the buffer range
-    const __amdgpu_buffer_rsrc_t rs_x = make_rsrc(pb.x, (uint32_t)tokens * (uint32_t)kc * kTileCols * 2);
+    const __amdgpu_buffer_rsrc_t rs_x = make_rsrc(pb.x, (uint32_t)NTOK * (uint32_t)kc * kTileCols * 2);
     const __amdgpu_buffer_rsrc_t rs_s = make_rsrc(pb.s, (uint32_t)kc * kTileCols * 4);
     const __amdgpu_buffer_rsrc_t rs_lut = make_rsrc(pb.lutA, (uint32_t)pb.nt * 16 * NB * 4);
 
@@ -263,7 +262,7 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
         const uint32_t g = (uint32_t)wave_chunk(sg, wave, lane >> 5) * 32 + (lane & 31);   // group of 8 columns
         valid = valid && g < (uint32_t)kc * 32;
 #pragma unroll
-        for (int t = 0; t < MT; ++t)   // token t's row of x starts K fp16 numbers after token t - 1's
+        for (int t = 0; t < NTOK; ++t)   // token t's row of x starts K fp16 numbers after token t - 1's
             xv[t] = __builtin_amdgcn_raw_buffer_load_b128(rs_x, valid ? g * 16 + (uint32_t)t * (uint32_t)kc * (kTileCols * 2) : kOob, 0, 0);
         s0 = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(rs_s, valid ? g * 32 : kOob, 0, 0));
         s1 = __builtin_bit_cast(float4v, __builtin_amdgcn_raw_buffer_load_b128(rs_s, valid ? g * 32 + 16 : kOob, 0, 0));
@@ -299,7 +298,7 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
                         ax = __builtin_amdgcn_smfmac_i32_16x16x128_i8(__builtin_bit_cast(int4v, A[0][ch][d]), Bq[0], ax, idxreg, 0, 0);
                         ay = __builtin_amdgcn_smfmac_i32_16x16x128_i8(__builtin_bit_cast(int4v, A[MT / 4][ch][d]), Bq[0], ay, idxreg, 0, 0);
                         az = __builtin_amdgcn_smfmac_i32_16x16x128_i8(__builtin_bit_cast(int4v, A[MT / 2][ch][d]), Bq[0], az, idxreg, 0, 0);
-                        aw = __builtin_amdgcn_smfmac_i32_16x16x128_i8(__builtin_bit_cast(int4v, A[MT - 1][ch][d]), Bq[0], aw, idxreg, 0, 0);
+                        if (NTOK > 3) aw = __builtin_amdgcn_smfmac_i32_16x16x128_i8(__builtin_bit_cast(int4v, A[MT - 1][ch][d]), Bq[0], aw, idxreg, 0, 0);
                     }
                 }
             }
@@ -525,7 +524,7 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
             {   // smooth this thread's 8 activations of the segment (loaded one segment ago)
                 const bool in_k = wave_chunk(cur.sg, wave, lane >> 5) < kc;
 #pragma unroll
-                for (int t = 0; t < MT; ++t) {
+                for (int t = 0; t < NTOK; ++t) {
                     half8 o;
                     if (!quantised) {
 #pragma unroll
@@ -555,7 +554,7 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
             for (int ch = 0; ch < kBCH; ++ch) {
                 chunk_in_k[ch] = wave_chunk(cur.sg, wave, ch) < kc;
 #pragma unroll
-                for (int t = 0; t < MT; ++t)
+                for (int t = 0; t < NTOK; ++t)
 #pragma unroll
                     for (int g = 0; g < NA; ++g) {   // written by this wave only: no barrier
                         if constexpr (I8)
@@ -570,8 +569,7 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
         // ---- visit epilogue: add the waves' slots in a fixed order, round once, store
         for (int e = threadIdx.x; e < (cur.v1 - cur.v0) * 16; e += NT) {
 #pragma unroll
-            for (int t = 0; t < MT; ++t) {   // token t's row of y starts N outputs after token t - 1's
-                if (t >= tokens) break;
+            for (int t = 0; t < NTOK; ++t) {   // token t's row of y starts N outputs after token t - 1's
                 float sum = 0.f;
 #pragma unroll
                 for (int w = 0; w < kBW; ++w) sum += part[t * kPartFloats + w * (kVisitTiles * 16) + e];
@@ -1070,7 +1068,6 @@ int launch_decode_group(const GroupItem *items, int count, int M, int bits, void
     }
     for (int i = count; i <= kMaxGroup; ++i) wg_begin[i] = acc;
     batch.count = count;
-    batch.tokens = M;
     static_assert(kMaxGroup == 16, "eight leading kernel arguments hold wg_begin[1..16]");
     if (acc >= 0x7fff) return (int)hipErrorInvalidConfiguration;   // 16-bit table fields (acc <= max(CUs, count))
     WgTable table;
@@ -1082,7 +1079,7 @@ int launch_decode_group(const GroupItem *items, int count, int M, int bits, void
     if (!tokens_path) {
         lds = (size_t)MT * ((size_t)kBSeg * kTileCols * 2 + (size_t)kBW * kVisitTiles * 16 * 4);
         fn = bits == 3 ? (const void *)gemv_bucket_kernel<3>
-             : int8_codes ? (MT == 4 ? (const void *)gemv_bucket_kernel<2, 4, true>
+             : int8_codes ? (MT == 4 ? (M == 3 ? (const void *)gemv_bucket_kernel<2, 4, true, 3> : (const void *)gemv_bucket_kernel<2, 4, true>)
                              : MT == 2 ? (const void *)gemv_bucket_kernel<2, 2, true> : (const void *)gemv_bucket_kernel<2, 1, true>)
              : MT == 2 ? (const void *)gemv_bucket_kernel<2, 2> : (const void *)gemv_bucket_kernel<2>;
     } else {
@@ -1090,8 +1087,8 @@ int launch_decode_group(const GroupItem *items, int count, int M, int bits, void
         fn = bits == 2 ? (const void *)gemv_tokens_kernel<2, kBCH> : bits == 3 ? (const void *)gemv_tokens_kernel<3, kBCH>
                                                                               : (const void *)gemv_tokens_kernel<4, kBCH>;
     }
-    static PerDeviceFlags<18> lds_raised;
-    const int variant = tokens_path ? 1 : int8_codes ? (MT == 4 ? 5 : MT == 2 ? 4 : 3) : MT == 2 ? 2 : 0;
+    static PerDeviceFlags<21> lds_raised;
+    const int variant = tokens_path ? 1 : int8_codes ? (MT == 4 ? (M == 3 ? 6 : 5) : MT == 2 ? 4 : 3) : MT == 2 ? 2 : 0;
     if (hipError_t e = raise_lds_limit_once(lds_raised, variant * 3 + (bits - 2), fn, lds)) return (int)e;
     void *args[] = {&table.t[0], &table.t[1], &table.t[2], &table.t[3], &table.t[4], &table.t[5], &table.t[6], &table.t[7],
                     &batch, const_cast<int *>(&M)};   // the bucket kernel takes no M
