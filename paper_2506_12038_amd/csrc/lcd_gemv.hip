@@ -14,6 +14,9 @@
 //     y[n] = sum_l P[n][l] * (sum_{k: l_k==l} xs[k]) + Q[n][l] * (sum_{k: l_k==l} (-1)^{h_k} xs[k]).
 // The sign flips cost one xor-and (v_bitop3_b32) per pair of weights plus one 64-bit shift per
 // two pairs.
+// Two tokens at 2 bits take the sign-flipped pass's place with the second token's activations.
+// With the INT8 activation codes of Sec. 4.1 at 2 bits, A holds the codes as int8 numbers and the
+// instruction is v_smfmac_i32_16x16x128_i8 (64 values per row and instruction): one to four tokens.
 //
 // Work split: the 8 waves of a workgroup split K into segments of 16 chunks (256 columns each),
 // two chunks per wave, and keep their chunks' activations in registers for a whole segment; the
