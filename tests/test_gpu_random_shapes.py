@@ -34,7 +34,7 @@ def test_random_single_layer(seed):
     print(seed, N, K, bits, M, entry, err["max_rel_floored"])
 
 
-@pytest.mark.parametrize("seed", range(12))
+@pytest.mark.parametrize("seed", range(32))
 def test_random_groups(seed):
     import torch
     rng = np.random.default_rng(2000 + seed)
