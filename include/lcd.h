@@ -180,7 +180,8 @@ lcd_status lcd_lut_gemv_noalloc(const void *packed, const void *lut, const uint1
  * Routing: as lcd_lut_gemv, except that with 2 bits the codes travel as int8 numbers through the
  * sparse matrix core's int8 instruction (half the matrix instructions per weight, same bits in the
  * result: the bucket sums are integers either way), which then takes up to four tokens (one sparse
- * pass per token) before the dequantising route takes over at M >= 5.
+ * pass per token) before the dequantising route takes over at M >= 5; with 3 bits and one token the
+ * plain pass runs on int8 operands and the sign-flipped pass on fp16 operands.
  */
 lcd_status lcd_lut_gemv_q8(const void *packed, const void *lut, const uint16_t *x, const float *s, float s_q,
                            uint16_t *y, int M, int N, int K, int bits,

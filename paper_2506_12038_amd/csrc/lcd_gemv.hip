@@ -213,10 +213,12 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
                                                                    const BucketBatch batch)
 {
     static_assert(MT == 1 || (MT == 2 && BITS == 2) || (MT == 4 && I8), "two tokens: 2-bit indices only; four: int8 operands only");
-    static_assert(!I8 || BITS == 2, "int8 operands: 2-bit indices only");
+    static_assert(!I8 || BITS == 2 || MT == 1, "int8 operands: 2-bit indices, or one token at 3 bits");
     typedef int int4v __attribute__((ext_vector_type(4)));
     typedef int int8v __attribute__((ext_vector_type(8)));
-    constexpr int NA = I8 ? 4 : 8;               // operand registers (uint4) per chunk and token
+    constexpr bool kHalfOps = !I8 || BITS == 3;  // fp16 operands kept (3 bits with int8 codes: for the sign-flipped pass)
+    constexpr int NA = kHalfOps ? 8 : 1;         // fp16 operand registers (uint4) per chunk and token
+    constexpr int NQ = I8 ? 4 : 1;               // int8 operand registers (uint4) per chunk and token
     constexpr int NB = BITS == 2 ? 4 : 8;        // buckets (centroids) per row
     constexpr int NC = NB * MT;                  // accumulator columns one row tile uses (MT > 1: 2 bits only)
     constexpr int TG = 16 / NC;                  // row tiles that share one reduction (4, 2 or 1)
@@ -225,9 +227,11 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
     constexpr int kSegHalfs = kBSeg * kTileCols;        // activations of one segment, one token
     constexpr int kPartFloats = kBW * kVisitTiles * 16; // the waves' partial outputs of one visit, one token
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
-    // LDS: [ xs: MT x one segment, kBSeg*256 halfs ][ part: MT x kBW*kVisitTiles*16 floats ]
+    // LDS: [ xs: MT x one segment, kBSeg*256 halfs ][ part: MT x kBW*kVisitTiles*16 floats ][ 3 bits with int8 codes: one segment of bytes ]
+    // (2 bits with int8 codes: the bytes take the place of the halfs)
     _Float16 *xs_lds = reinterpret_cast<_Float16 *>(smem);
     float *part = reinterpret_cast<float *>(smem + (size_t)MT * kSegHalfs * 2);
+    uint8_t *xs8 = kHalfOps ? smem + (size_t)MT * kSegHalfs * 2 + (size_t)MT * kPartFloats * 4 : smem;
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: keeps addresses scalar
@@ -276,6 +280,7 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
     if (cur.done) return;   // no row tiles (the host never launches such a workgroup); the loads above moved nothing
 
     uint4v A[MT][kBCH][NA];   // this wave's smoothed activations of the current segment, NA operands per chunk and token
+    uint4v Aq[MT][kBCH][NQ];  // I8: the codes as int8 numbers
     bool chunk_in_k[kBCH] = {};   // wave-uniform: a short last segment leaves some of the wave's chunks empty
     half16 B1;        // constant routing matrix (index c -> column c), built after the prologue
     int8v Bq[MT];     // I8: the same as int8 numbers; token t's sums go to columns 4t .. 4t+3
@@ -283,7 +288,37 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
 
     // bucket sums of one (tile, chunk): columns [0, NC) of a 16x16 accumulator
     auto tile_sums = [&](const StepRegs<BITS> &r) -> float4v {
-        if constexpr (I8) {
+        if constexpr (I8 && BITS == 3) {
+            // the plain pass on int8 operands (4 instructions per chunk), the sign-flipped pass on fp16
+            // operands as without I8 (8 per chunk): its flips are cheaper on fp16 numbers than on bytes
+            int4v ax = {0, 0, 0, 0};
+            float4v fy0 = {0.f, 0.f, 0.f, 0.f}, fy1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ch = 0; ch < kBCH; ++ch) {
+                if (!chunk_in_k[ch]) continue;
+                const unsigned long long h64 = ((unsigned long long)r.hi[ch][1] << 32) | r.hi[ch][0];
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                    const int idxreg = (int)r.lo[ch][d];
+                    uint4v f0, f1;
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int sh = 15 - (8 * (v >> 1) + 2 * d + (v & 1));
+                        unsigned long long t = h64;
+                        if (sh) asm("v_lshlrev_b64 %0, %1, %2" : "=v"(t) : "n"(sh), "v"(h64));
+                        f0[v] = xor_and(A[0][ch][2 * d][v], (uint32_t)t, 0x80008000u);
+                        f1[v] = xor_and(A[0][ch][2 * d + 1][v], (uint32_t)(t >> 32), 0x80008000u);
+                    }
+                    ax = __builtin_amdgcn_smfmac_i32_16x16x128_i8(__builtin_bit_cast(int4v, Aq[0][ch][d]), Bq[0], ax, idxreg, 0, 0);
+                    fy0 = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(f0), B1, fy0, idxreg, 0, 0);
+                    fy1 = __builtin_amdgcn_smfmac_f32_16x16x64_f16(as_half8(f1), B1, fy1, idxreg, 0, 1);
+                }
+            }
+            float4v m;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) m[u] = (float)ax[u] + dpp_f32<0x114>(fy0[u] + fy1[u]);   // flipped sums to columns 4..7
+            return m;
+        } else if constexpr (I8) {
             int4v ax = {0, 0, 0, 0}, ay = {0, 0, 0, 0}, az = {0, 0, 0, 0}, aw = {0, 0, 0, 0};
 #pragma unroll
             for (int ch = 0; ch < kBCH; ++ch) {
@@ -292,16 +327,16 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
                 for (int d = 0; d < 4; ++d) {
                     const int idxreg = (int)r.lo[ch][d];
                     if (MT == 1) {
-                        if (d & 1) ay = __builtin_amdgcn_smfmac_i32_16x16x128_i8(__builtin_bit_cast(int4v, A[0][ch][d]), Bq[0], ay, idxreg, 0, 0);
-                        else ax = __builtin_amdgcn_smfmac_i32_16x16x128_i8(__builtin_bit_cast(int4v, A[0][ch][d]), Bq[0], ax, idxreg, 0, 0);
+                        if (d & 1) ay = __builtin_amdgcn_smfmac_i32_16x16x128_i8(__builtin_bit_cast(int4v, Aq[0][ch][d]), Bq[0], ay, idxreg, 0, 0);
+                        else ax = __builtin_amdgcn_smfmac_i32_16x16x128_i8(__builtin_bit_cast(int4v, Aq[0][ch][d]), Bq[0], ax, idxreg, 0, 0);
                     } else if (MT == 2) {
-                        ax = __builtin_amdgcn_smfmac_i32_16x16x128_i8(__builtin_bit_cast(int4v, A[0][ch][d]), Bq[0], ax, idxreg, 0, 0);
-                        ay = __builtin_amdgcn_smfmac_i32_16x16x128_i8(__builtin_bit_cast(int4v, A[MT - 1][ch][d]), Bq[MT - 1], ay, idxreg, 0, 0);
+                        ax = __builtin_amdgcn_smfmac_i32_16x16x128_i8(__builtin_bit_cast(int4v, Aq[0][ch][d]), Bq[0], ax, idxreg, 0, 0);
+                        ay = __builtin_amdgcn_smfmac_i32_16x16x128_i8(__builtin_bit_cast(int4v, Aq[MT - 1][ch][d]), Bq[MT - 1], ay, idxreg, 0, 0);
                     } else {   // four tokens: all routed to columns 0..3, moved apart below
-                        ax = __builtin_amdgcn_smfmac_i32_16x16x128_i8(__builtin_bit_cast(int4v, A[0][ch][d]), Bq[0], ax, idxreg, 0, 0);
-                        ay = __builtin_amdgcn_smfmac_i32_16x16x128_i8(__builtin_bit_cast(int4v, A[MT / 4][ch][d]), Bq[0], ay, idxreg, 0, 0);
-                        az = __builtin_amdgcn_smfmac_i32_16x16x128_i8(__builtin_bit_cast(int4v, A[MT / 2][ch][d]), Bq[0], az, idxreg, 0, 0);
-                        if (NTOK > 3) aw = __builtin_amdgcn_smfmac_i32_16x16x128_i8(__builtin_bit_cast(int4v, A[MT - 1][ch][d]), Bq[0], aw, idxreg, 0, 0);
+                        ax = __builtin_amdgcn_smfmac_i32_16x16x128_i8(__builtin_bit_cast(int4v, Aq[0][ch][d]), Bq[0], ax, idxreg, 0, 0);
+                        ay = __builtin_amdgcn_smfmac_i32_16x16x128_i8(__builtin_bit_cast(int4v, Aq[MT / 4][ch][d]), Bq[0], ay, idxreg, 0, 0);
+                        az = __builtin_amdgcn_smfmac_i32_16x16x128_i8(__builtin_bit_cast(int4v, Aq[MT / 2][ch][d]), Bq[0], az, idxreg, 0, 0);
+                        if (NTOK > 3) aw = __builtin_amdgcn_smfmac_i32_16x16x128_i8(__builtin_bit_cast(int4v, Aq[MT - 1][ch][d]), Bq[0], aw, idxreg, 0, 0);
                     }
                 }
             }
@@ -544,10 +579,9 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
 #pragma unroll
                         for (int e = 0; e < 8; ++e) c[e] = (int)(float)o[e] & 0xff;
                         const uint2v packed8 = {(uint32_t)(c[0] | c[1] << 8 | c[2] << 16 | c[3] << 24), (uint32_t)(c[4] | c[5] << 8 | c[6] << 16 | c[7] << 24)};
-                        *reinterpret_cast<uint2v *>(reinterpret_cast<uint8_t *>(xs_lds) + t * kSegHalfs + 8 * threadIdx.x) = packed8;
-                    } else {
-                        *reinterpret_cast<half8 *>(&xs_lds[t * kSegHalfs + 8 * threadIdx.x]) = o;
+                        *reinterpret_cast<uint2v *>(xs8 + t * kSegHalfs + 8 * threadIdx.x) = packed8;
                     }
+                    if constexpr (kHalfOps) *reinterpret_cast<half8 *>(&xs_lds[t * kSegHalfs + 8 * threadIdx.x]) = o;
                 }
                 // next segment's activations: of this visit, or segment 0 again for the next visit
                 const bool more = cur.sg + 1 < nseg;
@@ -557,14 +591,18 @@ __global__ void __launch_bounds__(kBW * 64, 1) gemv_bucket_kernel(const uint32_t
             for (int ch = 0; ch < kBCH; ++ch) {
                 chunk_in_k[ch] = wave_chunk(cur.sg, wave, ch) < kc;
 #pragma unroll
-                for (int t = 0; t < NTOK; ++t)
+                for (int t = 0; t < NTOK; ++t) {   // written by this wave only: no barrier
+                    if constexpr (kHalfOps) {
 #pragma unroll
-                    for (int g = 0; g < NA; ++g) {   // written by this wave only: no barrier
-                        if constexpr (I8)
-                            A[t][ch][g] = *reinterpret_cast<const uint4v *>(reinterpret_cast<const uint8_t *>(xs_lds) + t * kSegHalfs + (wave * kBCH + ch) * kTileCols + 64 * q + 16 * g);
-                        else
+                        for (int g = 0; g < 8; ++g)
                             A[t][ch][g] = *reinterpret_cast<const uint4v *>(&xs_lds[t * kSegHalfs + (wave * kBCH + ch) * kTileCols + 64 * q + 8 * g]);
                     }
+                    if constexpr (I8) {
+#pragma unroll
+                        for (int g = 0; g < 4; ++g)
+                            Aq[t][ch][g] = *reinterpret_cast<const uint4v *>(xs8 + t * kSegHalfs + (wave * kBCH + ch) * kTileCols + 64 * q + 16 * g);
+                    }
+                }
             }
             run_turns();
         }
@@ -964,7 +1002,7 @@ int launch_decode_group(const GroupItem *items, int count, int M, int bits, void
     if (grid > tiles) grid = tiles;
     if (grid < count) grid = count;
     // 2 bits on the sparse matrix core with quantised activations: the codes go in as int8 numbers
-    const bool int8_codes = !tokens_path && bits == 2 && all_quantised;
+    const bool int8_codes = !tokens_path && bits != 4 && all_quantised;   // (3 bits: one token, the plain pass only)
     const bool light_steps = !tokens_path && bits == 2 && M == 1;   // one sparse pass per tile: a step is short next to the fixed costs
     // the several-token kernel, measured per workgroup (unit: the time of two chunks of one row tile, about 1 us):
     // smoothing inside the kernel, a segment switch re-stages 16 tokens x 512 columns per wave (2.3); with the
@@ -1080,8 +1118,8 @@ int launch_decode_group(const GroupItem *items, int count, int M, int bits, void
     size_t lds;
     const void *fn;
     if (!tokens_path) {
-        lds = (size_t)MT * ((size_t)kBSeg * kTileCols * 2 + (size_t)kBW * kVisitTiles * 16 * 4);
-        fn = bits == 3 ? (const void *)gemv_bucket_kernel<3>
+        lds = (size_t)MT * ((size_t)kBSeg * kTileCols * 2 + (size_t)kBW * kVisitTiles * 16 * 4) + (bits == 3 && int8_codes ? (size_t)kBSeg * kTileCols : 0);
+        fn = bits == 3 ? (int8_codes ? (const void *)gemv_bucket_kernel<3, 1, true> : (const void *)gemv_bucket_kernel<3>)
              : int8_codes ? (MT == 4 ? (M == 3 ? (const void *)gemv_bucket_kernel<2, 4, true, 3> : (const void *)gemv_bucket_kernel<2, 4, true>)
                              : MT == 2 ? (const void *)gemv_bucket_kernel<2, 2, true> : (const void *)gemv_bucket_kernel<2, 1, true>)
              : MT == 2 ? (const void *)gemv_bucket_kernel<2, 2> : (const void *)gemv_bucket_kernel<2>;
@@ -1090,7 +1128,7 @@ int launch_decode_group(const GroupItem *items, int count, int M, int bits, void
         fn = bits == 2 ? (const void *)gemv_tokens_kernel<2, kBCH> : bits == 3 ? (const void *)gemv_tokens_kernel<3, kBCH>
                                                                               : (const void *)gemv_tokens_kernel<4, kBCH>;
     }
-    static PerDeviceFlags<21> lds_raised;
+    static PerDeviceFlags<21> lds_raised;   // (variant 3 at 3 bits is the kernel with the int8 plain pass)
     const int variant = tokens_path ? 1 : int8_codes ? (MT == 4 ? (M == 3 ? 6 : 5) : MT == 2 ? 4 : 3) : MT == 2 ? 2 : 0;
     if (hipError_t e = raise_lds_limit_once(lds_raised, variant * 3 + (bits - 2), fn, lds)) return (int)e;
     void *args[] = {&table.t[0], &table.t[1], &table.t[2], &table.t[3], &table.t[4], &table.t[5], &table.t[6], &table.t[7],
